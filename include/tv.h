@@ -1,0 +1,170 @@
+/*
+ * tv.h - C ABI of libtv: linear-relaxation bound propagation for transformer
+ * encoders on AMD gfx950 (MI355X).
+ *
+ * Problem (paper Sec. 1 and Sec. 2.1 "Transformer Verification"): given a
+ * sentence, a model and an l_p ball of radius eps around the embeddings of P
+ * chosen token positions, compute lower/upper bounds on the model outputs
+ * that hold for every point of the ball (tv_verify) and the largest eps for
+ * which the predicted class provably cannot change (tv_certify).
+ *
+ * Bound state (paper Sec. 2.1, Table 1).  Every neuron x carries
+ *     lb + lw . delta  <=  x(delta)  <=  ub + uw . delta ,   delta in R^{P*E}
+ * (delta = offsets of the P perturbed embeddings, E = hidden size).  The
+ * library stores a state in centre/radius form, two fp32 planes
+ *     S = (upper + lower) / 2 ,   R = (upper - lower) / 2       (elementwise)
+ * each laid out [rows][C][n] with C = P*E + 1: coefficient rows 0..P*E-1
+ * (block r*E..r*E+E-1 belongs to the r-th perturbed position) followed by the
+ * bias row; n (the neuron axis) is contiguous.  With W = W+ + W- the sign-split
+ * affine rule of Eq. (2) becomes  S_y = W S_x + c,  R_y = |W| R_x.
+ *
+ * Conventions.  All pointers are DEVICE pointers unless a comment says host.
+ * All arrays are fp32 or int32, densely packed, row-major.  Calls are
+ * asynchronous on the given HIP stream (a hipStream_t passed as void*; NULL
+ * = the default stream) and never synchronise the device, except
+ * tv_model_create / tv_model_destroy.  Every function returns 0 on success and
+ * a negative TV_E_* code on error; on error nothing has been launched and
+ * tv_last_error() describes the cause (thread-local string).  The library owns
+ * only what tv_model_create allocates; inputs, outputs and workspaces belong to
+ * the caller and must stay valid until the stream has finished the call.
+ */
+#ifndef TV_H_
+#define TV_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define TV_OK            0
+#define TV_E_NULL       -1   /* required pointer is NULL */
+#define TV_E_SHAPE      -2   /* inconsistent or unsupported sizes */
+#define TV_E_NORM       -3   /* p_norm not 1, 2 or TV_NORM_INF */
+#define TV_E_WORKSPACE  -4   /* workspace too small */
+#define TV_E_HIP        -5   /* a HIP runtime call failed */
+#define TV_E_ARG        -6   /* other invalid argument */
+
+#define TV_NORM_INF 0        /* p = infinity; p = 1 and p = 2 are passed as 1 and 2 */
+
+#define TV_ACT_RELU 0
+#define TV_ACT_TANH 1
+#define TV_ACT_GELU 2        /* tanh-form GELU, relaxed as square/product/tanh/product chain */
+
+typedef struct tv_model tv_model;
+
+typedef struct {
+  int32_t n_layers, hidden, n_heads, ffn, vocab, max_len, n_classes, activation;
+  float ln_eps;
+} tv_config;
+
+/* Linear weights are [out][in] (Y[j] = sum_i W[j][i] X[i] + b[j]). */
+typedef struct {
+  const float *Wq, *bq, *Wk, *bk, *Wv, *bv, *Wo, *bo;   /* [D][D], [D] */
+  const float *ln1_g, *ln1_b;                           /* [D] */
+  const float *W1, *b1;                                 /* [F][D], [F] */
+  const float *W2, *b2;                                 /* [D][F], [D] */
+  const float *ln2_g, *ln2_b;                           /* [D] */
+} tv_layer_weights;
+
+typedef struct {
+  const float *tok_emb;               /* [vocab][D] */
+  const float *pos_emb;               /* [max_len][D] */
+  const tv_layer_weights *layers;     /* HOST array of n_layers entries */
+  const float *Wc, *bc;               /* head on token 0: [n_classes][D], [n_classes] */
+  int32_t on_device;                  /* 0: the float pointers are host memory; 1: device memory */
+} tv_weights;
+
+const char *tv_version(void);
+const char *tv_last_error(void);
+
+/* Copies the weights to the device (and builds |W| for every matrix).  Post-norm encoder:
+ * a = x + Wo.Attn(x) + bo; x' = LN(a); f = x' + W2.act(W1.x' + b1) + b2; x'' = LN(f); head on token 0.
+ * Requires hidden % n_heads == 0 and hidden, ffn, hidden/n_heads multiples of 4.  Synchronous. */
+int tv_model_create(const tv_config *cfg, const tv_weights *w, tv_model **out);
+void tv_model_destroy(tv_model *m);
+
+/* Workspace bytes for a call on B sentences of L tokens with P perturbed positions when all B
+ * sentences are resident at once (*bytes_full) and the minimum, one sentence at a time
+ * (*bytes_min).  Any size in between is accepted by tv_verify / tv_certify, which process the
+ * batch in chunks of as many sentences as fit.  Either output pointer may be NULL. */
+int tv_workspace_query(const tv_model *m, int B, int L, int P, size_t *bytes_full, size_t *bytes_min);
+
+/* Bounds on the logits over the perturbation set (forward bound propagation: Eq. (2) for affine
+ * layers, relaxation rules for ReLU/tanh/GELU, dot products, softmax and LayerNorm, Eq. (1) at the
+ * output).
+ *   tokens    [B][L] int32 in [0, vocab);  positions [B][P] int32, distinct, in [0, L), L % 4 == 0
+ *   p_norm    1, 2 or TV_NORM_INF: each perturbed embedding moves in its own l_p ball of radius eps[b]
+ *   eps       [B] >= 0
+ *   labels    [B] int32 or NULL; NULL = the clean prediction (argmax of the unperturbed logits)
+ *   out_lower, out_upper [B][n_classes]; out_margin_lower [B][n_classes-1] or NULL: lower bounds of
+ *             y_label - y_j for j != label in increasing j (bounded before concretization)
+ *   out_labels [B] int32 or NULL: the label used
+ *   status    [B] int32: 0 ok; 1 a bound left the fp32 range or a reciprocal met a lower bound
+ *             < 1e-12 (then lower = -inf, upper = +inf, margins = -inf) */
+int tv_verify(const tv_model *m, const int32_t *tokens, int B, int L, const int32_t *positions, int P,
+              int p_norm, const float *eps, const int32_t *labels, float *out_lower, float *out_upper,
+              float *out_margin_lower, int32_t *out_labels, int32_t *status, void *workspace,
+              size_t workspace_bytes, void *stream);
+
+/* Largest verified eps per sentence by bisection (paper Sec. 1: "identifies a maximal bound eps"):
+ * lo, hi = eps_lo, eps_hi; `steps` times: mid = (lo+hi)/2; verified(mid) ? lo = mid : hi = mid;
+ * out_eps[b] = lo.  verified = status 0 and every margin lower bound > 0.  The search state lives
+ * on the device; the host never waits inside the loop.  status [B]: number of probes that ended
+ * with status 1. */
+int tv_certify(const tv_model *m, const int32_t *tokens, int B, int L, const int32_t *positions, int P,
+               int p_norm, float eps_lo, float eps_hi, int steps, const int32_t *labels, float *out_eps,
+               int32_t *out_labels, int32_t *status, void *workspace, size_t workspace_bytes,
+               void *stream);
+
+/* ---- single operators on bound states (the kernels behind tv_verify; exported for unit parity
+ * tests and per-kernel benchmarks).  S*, R* are the two planes of a state, [rows][C][n]. ---------- */
+
+/* Eq. (1): l = (S_b - R_b) - eps * N(S - R),  u = (S_b + R_b) + eps * N(S + R), with
+ * N = sum over the P blocks of the dual (l_q) norm; eps is indexed by row / rows_per_sentence.
+ * l, u: [rows][n].  n % 4 == 0. */
+int tv_op_concretize(const float *S, const float *R, int rows, int P, int E, int n, int rows_per_sentence,
+                     int p_norm, const float *eps, float *l, float *u, void *stream);
+
+/* out = |in| elementwise (builds |W| for tv_op_affine). */
+int tv_op_abs(const float *in, float *out, size_t count, void *stream);
+
+/* Eq. (2) in centre/radius form on MFMA: Sy = Sx W^T (+ bias on the bias row) (+ Sadd),
+ * Ry = Rx |W|^T (+ Radd).  Sx, Rx: [rows][C][K]; W, Wabs: [N][K]; bias [N] or NULL; Sadd/Radd
+ * [rows][C][N] or both NULL (residual input, fused strict-elementwise add); Sy, Ry: [rows][C][N]
+ * (must not alias the inputs).  K % 4 == 0, N % 4 == 0. */
+int tv_op_affine(const float *Sx, const float *Rx, int rows, int P, int E, int K, int N, const float *W,
+                 const float *Wabs, const float *bias, const float *Sadd, const float *Radd, float *Sy,
+                 float *Ry, void *stream);
+
+/* Fused concretize + relaxation + substitution for an activation (paper Sec. 4.1 second pattern,
+ * Sec. 4.3): act = TV_ACT_*.  In-place allowed (Sy == Sx, Ry == Rx).  status [rows/rows_per_sentence]
+ * is OR-ed with 1 on non-finite bounds. */
+int tv_op_activation(int act, const float *Sx, const float *Rx, int rows, int P, int E, int n,
+                     int rows_per_sentence, int p_norm, const float *eps, float *Sy, float *Ry,
+                     int32_t *status, void *stream);
+
+/* Full LayerNorm bound over the neuron axis (centre, square, mean, sqrt, reciprocal, product,
+ * gamma/beta).  x: [rows][C][n] -> y same shape, must not alias. */
+int tv_op_layernorm(const float *Sx, const float *Rx, int rows, int P, int E, int n, int rows_per_sentence,
+                    int p_norm, const float *eps, const float *gamma, const float *beta, float ln_eps,
+                    float *Sy, float *Ry, int32_t *status, void *stream);
+
+/* Self-attention core of one layer, all heads: scores = q k^T / sqrt(d_h) (dot-product bound with
+ * both operands perturbed, paper Sec. 2.3), softmax bound, o = p v (dot-product bound).
+ * q, k, v: [B*L][C][D]; o: [B*L][C][D] (heads concatenated); must not alias.
+ * If Ss/Rs are non-NULL ([B*H*L][C][L]) the softmax output state p is left there, otherwise the
+ * workspace holds it.  workspace >= tv_attention_workspace(B, L, H, D, P) bytes. */
+size_t tv_attention_workspace(int B, int L, int H, int D, int P);
+int tv_op_attention(const float *Sq, const float *Rq, const float *Sk, const float *Rk, const float *Sv,
+                    const float *Rv, int B, int L, int H, int D, int P, int p_norm, const float *eps,
+                    float *So, float *Ro, float *Ss, float *Rs, int stop_after, int32_t *status,
+                    void *workspace, size_t workspace_bytes, void *stream);
+/* stop_after: 0 = full block; 1 = stop after the q k^T bound (Ss/Rs hold the score state);
+ * 2 = stop after the softmax bound (Ss/Rs hold p). */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TV_H_ */

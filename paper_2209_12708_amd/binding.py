@@ -1,0 +1,251 @@
+"""ctypes binding of libtv (argument marshalling only; every step of the method runs in the HIP kernels).
+
+PyTorch is used for device memory (tensors own every buffer) and for the HIP stream handle.
+The names mirror include/tv.h: tv_model_create -> Model(...), tv_verify -> Model.verify, ...
+"""
+import ctypes as C
+import os
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "lib", "libtv.so")
+
+NORM_INF = 0
+ACT_RELU, ACT_TANH, ACT_GELU = 0, 1, 2
+
+
+class TvError(RuntimeError):
+    pass
+
+
+class _Config(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in
+                ("n_layers", "hidden", "n_heads", "ffn", "vocab", "max_len", "n_classes", "activation")] + \
+               [("ln_eps", C.c_float)]
+
+
+_LAYER_FIELDS = ("Wq", "bq", "Wk", "bk", "Wv", "bv", "Wo", "bo", "ln1_g", "ln1_b", "W1", "b1", "W2", "b2",
+                 "ln2_g", "ln2_b")
+
+
+class _LayerWeights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in _LAYER_FIELDS]
+
+
+class _Weights(C.Structure):
+    _fields_ = [("tok_emb", C.c_void_p), ("pos_emb", C.c_void_p), ("layers", C.POINTER(_LayerWeights)),
+                ("Wc", C.c_void_p), ("bc", C.c_void_p), ("on_device", C.c_int32)]
+
+
+_lib = None
+
+EXPORTS = ("tv_version", "tv_last_error", "tv_model_create", "tv_model_destroy", "tv_workspace_query", "tv_verify",
+           "tv_certify", "tv_op_concretize", "tv_op_abs", "tv_op_affine", "tv_op_activation", "tv_op_layernorm",
+           "tv_attention_workspace", "tv_op_attention")
+
+
+def lib():
+    """Load libtv.so (built in-tree by __graft_entry__.build()).  There is no fallback path."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise TvError(f"{LIB_PATH} is missing: build it with `python -c 'import __graft_entry__ as g; g.build()'`")
+        L = C.CDLL(LIB_PATH)
+        L.tv_version.restype = C.c_char_p
+        L.tv_last_error.restype = C.c_char_p
+        L.tv_attention_workspace.restype = C.c_size_t
+        L.tv_attention_workspace.argtypes = [C.c_int] * 5
+        L.tv_model_create.argtypes = [C.POINTER(_Config), C.POINTER(_Weights), C.POINTER(C.c_void_p)]
+        L.tv_model_destroy.argtypes = [C.c_void_p]
+        L.tv_model_destroy.restype = None
+        L.tv_workspace_query.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_size_t),
+                                         C.POINTER(C.c_size_t)]
+        vp, i, f, sz = C.c_void_p, C.c_int, C.c_float, C.c_size_t
+        L.tv_verify.argtypes = [vp, vp, i, i, vp, i, i, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.tv_certify.argtypes = [vp, vp, i, i, vp, i, i, f, f, i, vp, vp, vp, vp, vp, sz, vp]
+        L.tv_op_concretize.argtypes = [vp, vp, i, i, i, i, i, i, vp, vp, vp, vp]
+        L.tv_op_abs.argtypes = [vp, vp, sz, vp]
+        L.tv_op_affine.argtypes = [vp, vp, i, i, i, i, i, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.tv_op_activation.argtypes = [i, vp, vp, i, i, i, i, i, i, vp, vp, vp, vp, vp]
+        L.tv_op_layernorm.argtypes = [vp, vp, i, i, i, i, i, i, vp, vp, vp, f, vp, vp, vp, vp]
+        L.tv_op_attention.argtypes = [vp] * 6 + [i] * 6 + [vp] * 5 + [i, vp, vp, sz, vp]
+        _lib = L
+    return _lib
+
+
+def _check(rc):
+    if rc != 0:
+        raise TvError(f"libtv error {rc}: {lib().tv_last_error().decode()}")
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous(), "device, contiguous tensors only"
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def version():
+    return lib().tv_version().decode()
+
+
+class Model:
+    """Owns a tv_model handle.  `weights` is the dict produced by tv_synth.make_model (fp32 numpy arrays)."""
+
+    def __init__(self, weights: dict, device="cuda:0"):
+        cfg = weights["cfg"]
+        self.cfg = cfg
+        self.device = torch.device(device)
+        torch.cuda.set_device(self.device)
+        c = _Config(cfg.n_layers, cfg.hidden, cfg.n_heads, cfg.ffn, cfg.vocab, cfg.max_len, cfg.n_classes,
+                    cfg.activation, cfg.ln_eps)
+        keep = []
+
+        def host(a):
+            a = np.ascontiguousarray(a, dtype=np.float32)
+            keep.append(a)
+            return a.ctypes.data_as(C.c_void_p)
+
+        layers = (_LayerWeights * cfg.n_layers)()
+        for l in range(cfg.n_layers):
+            for n in _LAYER_FIELDS:
+                setattr(layers[l], n, host(weights[f"l{l}.{n}"]))
+        w = _Weights(host(weights["tok_emb"]), host(weights["pos_emb"]), layers, host(weights["Wc"]),
+                     host(weights["bc"]), 0)
+        h = C.c_void_p()
+        _check(lib().tv_model_create(C.byref(c), C.byref(w), C.byref(h)))
+        self._h = h
+        self._ws = None
+
+    def close(self):
+        if getattr(self, "_h", None):
+            lib().tv_model_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def workspace_query(self, B, L, P):
+        full, mn = C.c_size_t(), C.c_size_t()
+        _check(lib().tv_workspace_query(self._h, B, L, P, C.byref(full), C.byref(mn)))
+        return full.value, mn.value
+
+    def workspace(self, B, L, P, cap_bytes=None):
+        """A cached torch buffer: all B sentences resident if that fits under cap_bytes, else as many as fit."""
+        full, mn = self.workspace_query(B, L, P)
+        if cap_bytes is None:
+            free, _ = torch.cuda.mem_get_info(self.device)
+            held = 0 if self._ws is None else self._ws.numel()
+            cap_bytes = int((free + held) * 0.85)
+        if cap_bytes < mn:
+            raise TvError(f"one sentence needs {mn} workspace bytes, only {cap_bytes} available")
+        want = min(full, cap_bytes)
+        if self._ws is None or self._ws.numel() < want:
+            self._ws = None
+            self._ws = torch.empty(want, dtype=torch.uint8, device=self.device)
+        return self._ws
+
+    def verify(self, tokens, positions, p_norm, eps, labels=None, workspace=None):
+        """tokens [B,L] int32, positions [B,P] int32, eps [B] fp32, labels [B] int32 or None (device tensors).
+        Returns dict of device tensors: lower, upper [B,n_cls], margin_lower [B,n_cls-1], labels, status."""
+        B, L = tokens.shape
+        P = positions.shape[1]
+        nc = self.cfg.n_classes
+        ws = workspace if workspace is not None else self.workspace(B, L, P)
+        dev = tokens.device
+        lower = torch.empty(B, nc, dtype=torch.float32, device=dev)
+        upper = torch.empty(B, nc, dtype=torch.float32, device=dev)
+        margin = torch.empty(B, nc - 1, dtype=torch.float32, device=dev)
+        out_labels = torch.empty(B, dtype=torch.int32, device=dev)
+        status = torch.empty(B, dtype=torch.int32, device=dev)
+        _check(lib().tv_verify(self._h, _ptr(tokens), B, L, _ptr(positions), P, p_norm, _ptr(eps), _ptr(labels),
+                               _ptr(lower), _ptr(upper), _ptr(margin), _ptr(out_labels), _ptr(status), _ptr(ws),
+                               ws.numel(), _stream()))
+        return {"lower": lower, "upper": upper, "margin_lower": margin, "labels": out_labels, "status": status}
+
+    def certify(self, tokens, positions, p_norm, eps_lo, eps_hi, steps, labels=None, workspace=None):
+        B, L = tokens.shape
+        P = positions.shape[1]
+        ws = workspace if workspace is not None else self.workspace(B, L, P)
+        dev = tokens.device
+        out_eps = torch.empty(B, dtype=torch.float32, device=dev)
+        out_labels = torch.empty(B, dtype=torch.int32, device=dev)
+        status = torch.empty(B, dtype=torch.int32, device=dev)
+        _check(lib().tv_certify(self._h, _ptr(tokens), B, L, _ptr(positions), P, p_norm, eps_lo, eps_hi, steps,
+                                _ptr(labels), _ptr(out_eps), _ptr(out_labels), _ptr(status), _ptr(ws), ws.numel(),
+                                _stream()))
+        return {"eps": out_eps, "labels": out_labels, "status": status}
+
+
+# ---- single operators (device tensors in, device tensors out) ----------------------------------
+def op_concretize(S, R, P, E, rows_per_sentence, p_norm, eps):
+    rows, Cc, n = S.shape
+    assert Cc == P * E + 1
+    l = torch.empty(rows, n, dtype=torch.float32, device=S.device)
+    u = torch.empty_like(l)
+    _check(lib().tv_op_concretize(_ptr(S), _ptr(R), rows, P, E, n, rows_per_sentence, p_norm, _ptr(eps), _ptr(l),
+                                  _ptr(u), _stream()))
+    return l, u
+
+
+def op_abs(x):
+    out = torch.empty_like(x)
+    _check(lib().tv_op_abs(_ptr(x), _ptr(out), x.numel(), _stream()))
+    return out
+
+
+def op_affine(S, R, P, E, W, bias=None, add=None):
+    rows, Cc, K = S.shape
+    N = W.shape[0]
+    Wabs = op_abs(W)
+    Sy = torch.empty(rows, Cc, N, dtype=torch.float32, device=S.device)
+    Ry = torch.empty_like(Sy)
+    _check(lib().tv_op_affine(_ptr(S), _ptr(R), rows, P, E, K, N, _ptr(W), _ptr(Wabs), _ptr(bias),
+                              _ptr(add[0]) if add else None, _ptr(add[1]) if add else None, _ptr(Sy), _ptr(Ry),
+                              _stream()))
+    return Sy, Ry
+
+
+def op_activation(act, S, R, P, E, rows_per_sentence, p_norm, eps, inplace=False):
+    rows, Cc, n = S.shape
+    Sy, Ry = (S, R) if inplace else (torch.empty_like(S), torch.empty_like(R))
+    status = torch.zeros(rows // rows_per_sentence, dtype=torch.int32, device=S.device)
+    _check(lib().tv_op_activation(act, _ptr(S), _ptr(R), rows, P, E, n, rows_per_sentence, p_norm, _ptr(eps),
+                                  _ptr(Sy), _ptr(Ry), _ptr(status), _stream()))
+    return Sy, Ry, status
+
+
+def op_layernorm(S, R, P, E, rows_per_sentence, p_norm, eps, gamma, beta, ln_eps):
+    rows, Cc, n = S.shape
+    Sy, Ry = torch.empty_like(S), torch.empty_like(R)
+    status = torch.zeros(rows // rows_per_sentence, dtype=torch.int32, device=S.device)
+    _check(lib().tv_op_layernorm(_ptr(S), _ptr(R), rows, P, E, n, rows_per_sentence, p_norm, _ptr(eps), _ptr(gamma),
+                                 _ptr(beta), ln_eps, _ptr(Sy), _ptr(Ry), _ptr(status), _stream()))
+    return Sy, Ry, status
+
+
+def op_attention(q, k, v, B, L, H, P, p_norm, eps, stop_after=0):
+    """q, k, v: (S, R) pairs [B*L, C, D].  Returns (o pair or None, score/softmax state pair, status)."""
+    D = q[0].shape[2]
+    Cc = q[0].shape[1]
+    dev = q[0].device
+    nbytes = lib().tv_attention_workspace(B, L, H, D, P)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    So = torch.empty(B * L, Cc, D, dtype=torch.float32, device=dev)
+    Ro = torch.empty_like(So)
+    Ss = torch.empty(B * H * L, Cc, L, dtype=torch.float32, device=dev)
+    Rs = torch.empty_like(Ss)
+    status = torch.zeros(B, dtype=torch.int32, device=dev)
+    _check(lib().tv_op_attention(_ptr(q[0]), _ptr(q[1]), _ptr(k[0]), _ptr(k[1]), _ptr(v[0]), _ptr(v[1]), B, L, H, D,
+                                 P, p_norm, _ptr(eps), _ptr(So), _ptr(Ro), _ptr(Ss), _ptr(Rs), stop_after,
+                                 _ptr(status), _ptr(ws), nbytes, _stream()))
+    return (So, Ro), (Ss, Rs), status

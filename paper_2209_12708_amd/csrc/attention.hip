@@ -1,0 +1,236 @@
+// Self-attention core on bound states: the dot-product bound with both operands perturbed (paper
+// Sec. 2.3, first observation; the "generalized scalar-vector multiplication" pattern of Sec. 4.1),
+// the softmax bound, and the attention x value product.
+//
+// z = x * y is relaxed per scalar product with the planes  z >= ly x + lx y - lx ly,
+// z <= uy x + lx y - lx uy,  then both operands are substituted with the sign rule of Eq. (2).
+// In centre/radius form, summed over the contracted index, this is
+//   S_z = [S_x | R_x] . [(ly+uy)/2 ; (|uy|-|ly|)/2]  +  lx . S_y  - lx.(ly+uy)/2
+//   R_z = [S_x | R_x] . [(uy-ly)/2 ; (|uy|+|ly|)/2]  + |lx| . R_y - lx.(uy-ly)/2
+// i.e. per head two dense contractions over the state of x (K doubled, coefficients from y's
+// concretized range) and two over the state of y (coefficients from x's range).  The scalars that the
+// paper's kernels broadcast per vector become the small B operands of MFMA products.
+#include "common.h"
+
+namespace tv {
+namespace {
+
+// coefficient matrices for q k^T from the concretized ranges of q and k
+//   coef[b][h][plane][j][kk]   (kk < dh: on S_q ; kk >= dh: on R_q),  lqs[plane][b][i][D]
+__global__ void qk_prep_kernel(const float *lq, const float *lk, const float *uk, int B, int L, int H, int dh,
+                               float scale, float *coef, float *lqs) {
+  const int D = H * dh;
+  const long total = (long)B * L * D;
+  for (long i = (long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long)gridDim.x * blockDim.x) {
+    const int dfull = (int)(i % D);
+    const long bj = i / D;
+    const int j = (int)(bj % L), b = (int)(bj / L);
+    const int h = dfull / dh, d = dfull % dh;
+    const float l = lk[i], u = uk[i];
+    float *c0 = coef + ((((long)b * H + h) * 2 + 0) * L + j) * (2 * dh);
+    float *c1 = coef + ((((long)b * H + h) * 2 + 1) * L + j) * (2 * dh);
+    c0[d] = 0.5f * (l + u) * scale;
+    c0[dh + d] = 0.5f * (fabsf(u) - fabsf(l)) * scale;
+    c1[d] = 0.5f * (u - l) * scale;
+    c1[dh + d] = 0.5f * (fabsf(u) + fabsf(l)) * scale;
+    const float q = lq[i];
+    lqs[i] = q * scale;
+    lqs[total + i] = fabsf(q) * scale;
+  }
+}
+
+// constants of the planes: cst[b][h][plane][i][j] = -scale * sum_d lq[i,d] * {(lk+uk)/2, (uk-lk)/2}[j,d]
+__global__ void qk_const_kernel(const float *lq, const float *lk, const float *uk, int B, int L, int H, int dh,
+                                float scale, float *cst) {
+  const int D = H * dh;
+  const long total = (long)B * H * L * L;
+  for (long t = (long)blockIdx.x * blockDim.x + threadIdx.x; t < total; t += (long)gridDim.x * blockDim.x) {
+    const int j = (int)(t % L);
+    long r = t / L;
+    const int i = (int)(r % L); r /= L;
+    const int h = (int)(r % H), b = (int)(r / H);
+    const float *pq = lq + ((long)b * L + i) * D + h * dh;
+    const float *pl = lk + ((long)b * L + j) * D + h * dh;
+    const float *pu = uk + ((long)b * L + j) * D + h * dh;
+    float s = 0.f, rr = 0.f;
+    for (int d = 0; d < dh; ++d) {
+      s = fmaf(pq[d], 0.5f * (pl[d] + pu[d]), s);
+      rr = fmaf(pq[d], 0.5f * (pu[d] - pl[d]), rr);
+    }
+    float *o = cst + (((long)b * H + h) * 2) * L * L + (long)i * L + j;
+    o[0] = -scale * s;
+    o[(long)L * L] = -scale * rr;
+  }
+}
+
+// coefficient matrices for p v:  coef[b][h][plane][d][kk]  (kk < L: on S_p[.., j=kk] ; kk >= L: on R_p)
+__global__ void pv_prep_kernel(const float *lv, const float *uv, int B, int L, int H, int dh, float *coef) {
+  const int D = H * dh;
+  const long total = (long)B * L * D;
+  for (long i = (long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long)gridDim.x * blockDim.x) {
+    const int dfull = (int)(i % D);
+    const long bj = i / D;
+    const int j = (int)(bj % L), b = (int)(bj / L);
+    const int h = dfull / dh, d = dfull % dh;
+    const float l = lv[i], u = uv[i];
+    float *c0 = coef + ((((long)b * H + h) * 2 + 0) * dh + d) * (2 * L);
+    float *c1 = coef + ((((long)b * H + h) * 2 + 1) * dh + d) * (2 * L);
+    c0[j] = 0.5f * (l + u);
+    c0[L + j] = 0.5f * (fabsf(u) - fabsf(l));
+    c1[j] = 0.5f * (u - l);
+    c1[L + j] = 0.5f * (fabsf(u) + fabsf(l));
+  }
+}
+
+// cst[plane][b][i][D] = - sum_j lp[b,h,i,j] * {(lv+uv)/2, (uv-lv)/2}[b,j,dfull]
+__global__ void pv_const_kernel(const float *lp, const float *lv, const float *uv, int B, int L, int H, int dh,
+                                float *cst) {
+  const int D = H * dh;
+  const long total = (long)B * L * D;
+  for (long t = (long)blockIdx.x * blockDim.x + threadIdx.x; t < total; t += (long)gridDim.x * blockDim.x) {
+    const int dfull = (int)(t % D);
+    const long bi = t / D;
+    const int i = (int)(bi % L), b = (int)(bi / L);
+    const int h = dfull / dh;
+    const float *pp = lp + (((long)b * H + h) * L + i) * L;
+    float s = 0.f, rr = 0.f;
+    for (int j = 0; j < L; ++j) {
+      const long k = ((long)b * L + j) * D + dfull;
+      const float l = lv[k], u = uv[k];
+      s = fmaf(pp[j], 0.5f * (l + u), s);
+      rr = fmaf(pp[j], 0.5f * (u - l), rr);
+    }
+    cst[t] = -s;
+    cst[total + t] = -rr;
+  }
+}
+
+unsigned blocks_for(long total) {
+  long b = (total + 255) / 256;
+  return (unsigned)(b > 16384 ? 16384 : (b < 1 ? 1 : b));
+}
+
+size_t align_up(size_t x) { return (x + 63) & ~(size_t)63; }   // in floats: keeps 256-byte alignment
+
+struct AttnLayout {
+  size_t lq, uq, lk, uk, lv, uv, coef_qk, lqs, cst_qk, sS, sR, lp, coef_pv, cst_pv, total;
+  AttnLayout(int B, int L, int H, int D, int P, bool own_scores) {
+    const size_t bld = (size_t)B * L * D, C = (size_t)P * D + 1;
+    size_t o = 0;
+    auto take = [&](size_t n) { size_t r = o; o += align_up(n); return r; };
+    lq = take(bld); uq = take(bld); lk = take(bld); uk = take(bld); lv = take(bld); uv = take(bld);
+    coef_qk = take(4 * bld); lqs = take(2 * bld); cst_qk = take((size_t)2 * B * H * L * L);
+    lp = take((size_t)B * H * L * L); coef_pv = take(4 * bld); cst_pv = take(2 * bld);
+    const size_t plane = (size_t)B * H * L * C * L;
+    sS = take(own_scores ? plane : 0); sR = take(own_scores ? plane : 0);
+    total = o;
+  }
+};
+
+}  // namespace
+
+size_t attention_workspace_ext(int B, int L, int H, int D, int P, bool own_scores) {
+  return AttnLayout(B, L, H, D, P, own_scores).total * sizeof(float);
+}
+
+int attention(CState q, CState k, CState v, int ld, int B, int L, int H, int D, int P, int pn, const float *eps, State o,
+              State s, int stop_after, int32_t *status, void *ws, size_t ws_bytes, hipStream_t st) {
+  TV_REQUIRE(q.S && q.R && k.S && k.R && v.S && v.R && eps && status && ws, TV_E_NULL, "attention: null pointer");
+  TV_REQUIRE(B > 0 && L > 0 && H > 0 && D > 0 && P >= 0 && D % H == 0 && (D / H) % 4 == 0 && L % 4 == 0, TV_E_SHAPE,
+             "attention: need D %% H == 0, head width and L multiples of 4 (B=%d L=%d H=%d D=%d)", B, L, H, D);
+  TV_REQUIRE(norm_ok(pn), TV_E_NORM, "p_norm must be 1, 2 or TV_NORM_INF, got %d", pn);
+  TV_REQUIRE(stop_after >= 0 && stop_after <= 2, TV_E_ARG, "stop_after must be 0, 1 or 2");
+  TV_REQUIRE(stop_after == 0 ? (o.S && o.R) : (s.S && s.R), TV_E_NULL, "attention: null output state");
+  const bool own = !(s.S && s.R);
+  const AttnLayout lay(B, L, H, D, P, own);
+  TV_REQUIRE(ws_bytes >= lay.total * sizeof(float), TV_E_WORKSPACE, "attention: workspace %zu < %zu bytes", ws_bytes,
+             lay.total * sizeof(float));
+  float *w = static_cast<float *>(ws);
+  const int dh = D / H, C = P * D + 1;
+  const int rows = B * L;
+  const float scale = 1.0f / sqrtf((float)dh);
+  float *lq = w + lay.lq, *uq = w + lay.uq, *lk = w + lay.lk, *uk = w + lay.uk, *lv = w + lay.lv, *uv = w + lay.uv;
+  if (own) { s.S = w + lay.sS; s.R = w + lay.sR; }
+
+  TV_REQUIRE(ld >= D && ld % 4 == 0, TV_E_SHAPE, "attention: bad row stride %d", ld);
+  if (int rc = concretize(q, rows, P, D, D, ld, L, pn, eps, lq, uq, st)) return rc;
+  if (int rc = concretize(k, rows, P, D, D, ld, L, pn, eps, lk, uk, st)) return rc;
+  if (int rc = concretize(v, rows, P, D, D, ld, L, pn, eps, lv, uv, st)) return rc;
+  const long bld = (long)B * L * D;
+  hipLaunchKernelGGL(qk_prep_kernel, dim3(blocks_for(bld)), dim3(256), 0, st, lq, lk, uk, B, L, H, dh, scale,
+                     w + lay.coef_qk, w + lay.lqs);
+  hipLaunchKernelGGL(qk_const_kernel, dim3(blocks_for((long)B * H * L * L)), dim3(256), 0, st, lq, lk, uk, B, L, H, dh,
+                     scale, w + lay.cst_qk);
+  TV_HIP(hipGetLastError());
+
+  const long lcd = (long)L * C * D, lcl = (long)L * C * L, lcx = (long)L * C * ld;   // lcx: per-sentence stride of q/k/v
+  {  // scores, part 1: [S_q | R_q] x coefficients from k's range  -> both planes of s
+    GemmArgs g;
+    g.A = q.S; g.A2 = q.R; g.K1 = dh; g.lda = ld;
+    g.B = w + lay.coef_qk; g.ldb = 2 * dh; g.b_mode = 0;
+    g.C = s.S; g.ldc = L;
+    g.bias = w + lay.cst_qk; g.bias_ld = L; g.bias_period = C;
+    g.M = L * C; g.N = L; g.K = 2 * dh;
+    g.nz0 = 2; g.nz1 = H; g.nz2 = B;
+    g.sA[0] = 0; g.sA[1] = dh; g.sA[2] = lcx;
+    g.sA2[0] = 0; g.sA2[1] = dh; g.sA2[2] = lcx;
+    g.sB[0] = (long)L * 2 * dh; g.sB[1] = 2L * L * 2 * dh; g.sB[2] = (long)H * 2 * L * 2 * dh;
+    g.sC[0] = s.R - s.S; g.sC[1] = lcl; g.sC[2] = (long)H * lcl;
+    g.sBias[0] = (long)L * L; g.sBias[1] = 2L * L * L; g.sBias[2] = (long)H * 2 * L * L;
+    if (int rc = gemm(g, st)) return rc;
+  }
+  {  // scores, part 2: coefficients from q's range x the state of k, accumulated
+    GemmArgs g;
+    g.A = w + lay.lqs; g.lda = D;
+    g.B = k.S; g.ldb = ld; g.b_mode = 0; g.b_q = L; g.b_m1 = C; g.b_m2 = 1;   // n = (r, j) -> row j*C + r
+    g.C = s.S; g.Cadd = s.S; g.ldc = (long)C * L;
+    g.M = L; g.N = C * L; g.K = dh;
+    g.nz0 = 2; g.nz1 = H; g.nz2 = B;
+    g.sA[0] = bld; g.sA[1] = dh; g.sA[2] = (long)L * D;
+    g.sB[0] = k.R - k.S; g.sB[1] = dh; g.sB[2] = lcx;
+    g.sC[0] = s.R - s.S; g.sC[1] = lcl; g.sC[2] = (long)H * lcl;
+    g.sAdd[0] = g.sC[0]; g.sAdd[1] = g.sC[1]; g.sAdd[2] = g.sC[2];
+    if (int rc = gemm(g, st)) return rc;
+  }
+  if (stop_after == 1) return TV_OK;
+
+  float *lp = w + lay.lp;
+  if (int rc = softmax(s, B * H * L, P, D, L, H * L, pn, eps, lp, status, st)) return rc;
+  if (stop_after == 2) return TV_OK;
+
+  hipLaunchKernelGGL(pv_prep_kernel, dim3(blocks_for(bld)), dim3(256), 0, st, lv, uv, B, L, H, dh, w + lay.coef_pv);
+  hipLaunchKernelGGL(pv_const_kernel, dim3(blocks_for(bld)), dim3(256), 0, st, lp, lv, uv, B, L, H, dh,
+                     w + lay.cst_pv);
+  TV_HIP(hipGetLastError());
+  {  // o, part 1: [S_p | R_p] x coefficients from v's range
+    GemmArgs g;
+    g.A = s.S; g.A2 = s.R; g.K1 = L; g.lda = L;
+    g.B = w + lay.coef_pv; g.ldb = 2 * L; g.b_mode = 0;
+    g.C = o.S; g.ldc = D;
+    g.bias = w + lay.cst_pv; g.bias_ld = D; g.bias_period = C;
+    g.M = L * C; g.N = dh; g.K = 2 * L;
+    g.nz0 = 2; g.nz1 = H; g.nz2 = B;
+    g.sA[0] = 0; g.sA[1] = lcl; g.sA[2] = (long)H * lcl;
+    g.sA2[0] = 0; g.sA2[1] = lcl; g.sA2[2] = (long)H * lcl;
+    g.sB[0] = (long)dh * 2 * L; g.sB[1] = 2L * dh * 2 * L; g.sB[2] = (long)H * 2 * dh * 2 * L;
+    g.sC[0] = o.R - o.S; g.sC[1] = dh; g.sC[2] = lcd;
+    g.sBias[0] = bld; g.sBias[1] = dh; g.sBias[2] = (long)L * D;
+    if (int rc = gemm(g, st)) return rc;
+  }
+  {  // o, part 2: lp x the state of v, accumulated (lp >= 0 after the clamp, so |lp| = lp)
+    GemmArgs g;
+    g.A = lp; g.lda = L;
+    g.B = v.S; g.ldb = (long)C * ld; g.b_mode = 1; g.cq = dh; g.cstride = D; g.b_cstride = ld;   // n = (r, d) -> column r*D + d
+    g.C = o.S; g.Cadd = o.S; g.ldc = (long)C * D;
+    g.M = L; g.N = C * dh; g.K = L;
+    g.nz0 = 2; g.nz1 = H; g.nz2 = B;
+    g.sA[0] = 0; g.sA[1] = (long)L * L; g.sA[2] = (long)H * L * L;
+    g.sB[0] = v.R - v.S; g.sB[1] = dh; g.sB[2] = lcx;
+    g.sC[0] = o.R - o.S; g.sC[1] = dh; g.sC[2] = lcd;
+    g.sAdd[0] = g.sC[0]; g.sAdd[1] = g.sC[1]; g.sAdd[2] = g.sC[2];
+    if (int rc = gemm(g, st)) return rc;
+  }
+  return TV_OK;
+}
+
+}  // namespace tv

@@ -1,0 +1,81 @@
+// Shared declarations of libtv (host + device helpers).  gfx950 only.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include "../../include/tv.h"
+
+namespace tv {
+
+constexpr int kWave = 64;
+constexpr int kMaxP = 8;          // perturbed positions supported by the reduction kernels
+
+// ---- error plumbing -------------------------------------------------------------------------
+int fail(int code, const char *fmt, ...);
+#define TV_HIP(call)                                                                   \
+  do {                                                                                 \
+    hipError_t e_ = (call);                                                            \
+    if (e_ != hipSuccess) return tv::fail(TV_E_HIP, "%s: %s", #call, hipGetErrorString(e_)); \
+  } while (0)
+#define TV_REQUIRE(cond, code, ...) \
+  do { if (!(cond)) return tv::fail(code, __VA_ARGS__); } while (0)
+
+inline bool norm_ok(int p) { return p == 1 || p == 2 || p == TV_NORM_INF; }
+
+// A bound state: two planes [rows][C][n].
+struct State {
+  float *S, *R;
+};
+struct CState {
+  const float *S, *R;
+};
+
+// ---- GEMM (gemm.hip) ------------------------------------------------------------------------
+// C[z][m][col(n)] (+)= sum_k A[z][m][k] * B[z](k, n)  (+ bias on bias rows) (+ Cadd)
+// Batch index z = z0 + nz0 * (z1 + nz1 * z2); every operand has one stride per level.
+struct GemmArgs {
+  const float *A = nullptr;   // [M][lda], k contiguous
+  const float *A2 = nullptr;  // second K segment (k >= K1) or nullptr
+  int K1 = 0;                 // split point (multiple of 4); K1 == K when A2 is unused
+  long lda = 0;
+  const float *B = nullptr;
+  long ldb = 0;
+  int b_mode = 0;   // 0: B[n][k] (k contiguous), row(n) = (n % b_q) * b_m1 + (n / b_q) * b_m2 (b_q = 0: row = n)
+                    // 1: B[k][col(n)] (n contiguous in groups of cq)
+  int b_q = 0; long b_m1 = 0, b_m2 = 0;
+  int cq = 0; long cstride = 0;   // col(n) = (n / cq) * cstride + n % cq   (cq = 0: col = n) for C, Cadd and bias
+  long b_cstride = 0;             // the same map with its own stride for B in mode 1
+  float *C = nullptr;
+  const float *Cadd = nullptr;    // same layout as C; may equal C (accumulate)
+  long ldc = 0;
+  const float *bias = nullptr;    // added on rows m with m % bias_period == bias_period - 1:
+  long bias_ld = 0;               //   bias[(m / bias_period) * bias_ld + col(n)]
+  int bias_period = 0;
+  int M = 0, N = 0, K = 0;
+  int nz0 = 1, nz1 = 1, nz2 = 1;
+  long sA[3] = {0, 0, 0}, sA2[3] = {0, 0, 0}, sB[3] = {0, 0, 0}, sC[3] = {0, 0, 0}, sAdd[3] = {0, 0, 0},
+       sBias[3] = {0, 0, 0};
+};
+int gemm(const GemmArgs &g, hipStream_t st);
+
+// ---- elementwise / reduction kernels (rowops.hip) ------------------------------------------
+// ld: floats between consecutive coefficient rows of the input state (n when densely packed)
+int concretize(CState x, int rows, int P, int E, int n, int ld, int rps, int p_norm, const float *eps, float *l,
+               float *u, hipStream_t st);
+int activation(int act, CState x, int rows, int P, int E, int n, int rps, int p_norm, const float *eps,
+               State y, int32_t *status, hipStream_t st);
+int layernorm(CState x, int rows, int P, int E, int n, int rps, int p_norm, const float *eps,
+              const float *gamma, const float *beta, float ln_eps, State y, int32_t *status, hipStream_t st);
+int softmax(State s, int rows, int P, int E, int L, int rps, int p_norm, const float *eps, float *lp,
+            int32_t *status, hipStream_t st);
+int vec_abs(const float *in, float *out, size_t count, hipStream_t st);
+int fill_zero(float *p, size_t count, hipStream_t st);
+
+// ---- attention (attention.hip) --------------------------------------------------------------
+// own_scores: the workspace also holds the score / softmax state (when the caller passes none)
+size_t attention_workspace_ext(int B, int L, int H, int D, int P, bool own_scores);
+// ld: row stride of the q, k, v states (D when separate, 3D when they are column slices of one tensor)
+int attention(CState q, CState k, CState v, int ld, int B, int L, int H, int D, int P, int p_norm, const float *eps,
+              State o, State s, int stop_after, int32_t *status, void *ws, size_t ws_bytes, hipStream_t st);
+
+}  // namespace tv

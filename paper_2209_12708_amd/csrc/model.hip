@@ -1,0 +1,560 @@
+// Host side of libtv: model handle, workspace plan, per-layer schedule, verify / certify, and the
+// small kernels around the sweep (input state, head weights, outputs, bisection state).
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+#include <vector>
+#include "common.h"
+
+namespace tv {
+
+static thread_local char g_err[512] = "";
+
+int fail(int code, const char *fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+namespace {
+
+// ---- small kernels -----------------------------------------------------------------------------
+
+// Input state (paper Sec. 2.1, input neurons): bias row = clean embedding; the coefficient rows of
+// perturbed position r hold the identity in block r; everything else is zero (planes pre-zeroed).
+__global__ void init_state_kernel(const int32_t *tokens, const int32_t *positions, const float *tok_emb,
+                                  const float *pos_emb, int B, int L, int D, int P, float *S) {
+  const int C = P * D + 1;
+  const long total = (long)B * L * D;
+  for (long i = (long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long)gridDim.x * blockDim.x) {
+    const int d = (int)(i % D);
+    const long bt = i / D;
+    const int t = (int)(bt % L), b = (int)(bt / L);
+    const int tok = tokens[bt];
+    float *blk = S + bt * (long)C * D;
+    blk[(long)(C - 1) * D + d] = tok_emb[(long)tok * D + d] + pos_emb[(long)t * D + d];
+    for (int r = 0; r < P; ++r)
+      if (positions[b * P + r] == t) blk[(long)(r * D + d) * D + d] = 1.f;
+  }
+}
+
+// Head rows per sentence: classes 0..n_cls-1, then margins w[label] - w[j] (j != label, increasing j);
+// padded with zero rows to NP.  Wh: [2][B][NP][D] (weights, then their absolute values); bh: [2][B][NP].
+__global__ void head_prep_kernel(const float *Wc, const float *bc, const int32_t *labels, int B, int n_cls, int NP,
+                                 int D, float *Wh, float *bh) {
+  const long total = (long)B * NP * D;
+  for (long i = (long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long)gridDim.x * blockDim.x) {
+    const int d = (int)(i % D);
+    const long bo = i / D;
+    const int o = (int)(bo % NP), b = (int)(bo / NP);
+    const int lab = labels[b];
+    float w = 0.f, c = 0.f;
+    if (o < n_cls) { w = Wc[(long)o * D + d]; c = bc[o]; }
+    else if (o < 2 * n_cls - 1) {
+      int j = o - n_cls; if (j >= lab) ++j;
+      w = Wc[(long)lab * D + d] - Wc[(long)j * D + d];
+      c = bc[lab] - bc[j];
+    }
+    Wh[i] = w;
+    Wh[total + i] = fabsf(w);
+    if (d == 0) { bh[bo] = c; bh[(long)B * NP + bo] = 0.f; }
+  }
+}
+
+__global__ void argmax_kernel(const float *l, const float *u, int B, int n_cls, int NP, int32_t *labels) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= B) return;
+  int best = 0; float bv = -INFINITY;
+  for (int c = 0; c < n_cls; ++c) {
+    const float v = 0.5f * (l[b * NP + c] + u[b * NP + c]);
+    if (v > bv) { bv = v; best = c; }
+  }
+  labels[b] = best;
+}
+
+__global__ void head_out_kernel(const float *l, const float *u, const int32_t *status, const int32_t *labels, int B,
+                                int n_cls, int NP, float *out_lower, float *out_upper, float *out_margin,
+                                int32_t *out_labels, int32_t *out_status, float *margin_ws) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= B) return;
+  bool bad = status[b] != 0;
+  for (int o = 0; o < 2 * n_cls - 1; ++o)
+    bad |= !(fabsf(l[b * NP + o]) <= 3.4028234663852886e38f) || !(fabsf(u[b * NP + o]) <= 3.4028234663852886e38f);
+  for (int c = 0; c < n_cls; ++c) {
+    if (out_lower) out_lower[b * n_cls + c] = bad ? -INFINITY : l[b * NP + c];
+    if (out_upper) out_upper[b * n_cls + c] = bad ? INFINITY : u[b * NP + c];
+  }
+  for (int j = 0; j < n_cls - 1; ++j) {
+    const float m = bad ? -INFINITY : l[b * NP + n_cls + j];
+    if (out_margin) out_margin[b * (n_cls - 1) + j] = m;
+    margin_ws[b * (n_cls - 1) + j] = m;
+  }
+  if (out_labels) out_labels[b] = labels[b];
+  if (out_status) out_status[b] = bad ? 1 : 0;
+}
+
+__global__ void fill_i32_kernel(int32_t *p, int n, int32_t v) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+__global__ void copy_f32_kernel(const float *in, float *out, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) out[i] = in[i];
+}
+__global__ void copy_i32_kernel(const int32_t *in, int32_t *out, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) out[i] = in[i];
+}
+// bisection state: st[0][b] = lo, st[1][b] = hi
+__global__ void search_init_kernel(float *lohi, int B, float lo, float hi, int32_t *cnt) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b < B) { lohi[b] = lo; lohi[B + b] = hi; cnt[b] = 0; }
+}
+__global__ void search_mid_kernel(const float *lohi, int B, float *eps) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b < B) eps[b] = 0.5f * (lohi[b] + lohi[B + b]);
+}
+__global__ void search_update_kernel(float *lohi, int B, const float *eps, const float *margin, int nm,
+                                     const int32_t *status, int32_t *cnt) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= B) return;
+  bool ok = status[b] == 0;
+  for (int j = 0; j < nm; ++j) ok &= margin[b * nm + j] > 0.f;
+  if (ok) lohi[b] = eps[b]; else lohi[B + b] = eps[b];
+  cnt[b] += status[b] != 0 ? 1 : 0;
+}
+
+__global__ void zero_eps_kernel(float *p, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0.f;
+}
+
+unsigned nblk(long total, int per = 256, long cap = 16384) {
+  long b = (total + per - 1) / per;
+  return (unsigned)(b > cap ? cap : (b < 1 ? 1 : b));
+}
+
+size_t align_up(size_t x) { return (x + 63) & ~(size_t)63; }
+
+}  // namespace
+}  // namespace tv
+
+using namespace tv;
+
+// ---- model -------------------------------------------------------------------------------------
+struct tv_layer_dev {
+  float *Wqkv, *bqkv;   // [2][3D][D], [2][3D]  (second copy: |W| / zeros)
+  float *Wo, *bo;       // [2][D][D], [2][D]
+  float *W1, *b1;       // [2][F][D], [2][F]
+  float *W2, *b2;       // [2][D][F], [2][D]
+  float *ln1_g, *ln1_b, *ln2_g, *ln2_b;
+};
+struct tv_model {
+  tv_config cfg;
+  float *blob = nullptr;    // one device allocation holding every array below
+  size_t blob_floats = 0;
+  float *tok_emb, *pos_emb, *Wc, *bc;
+  std::vector<tv_layer_dev> layers;
+};
+
+namespace {
+
+struct Plan {      // workspace offsets in floats for a chunk of Bc sentences
+  size_t x, qkv, t1, big, attn, attn_floats, wh, bh, hy, hl, hu, eps, margin, lohi, labels, status, cnt, total;
+  int NP;
+};
+
+Plan make_plan(const tv_config &c, int Bc, int L, int P) {
+  const size_t D = c.hidden, F = c.ffn, H = c.n_heads;
+  const size_t C = (size_t)P * D + 1;
+  const size_t rows = (size_t)Bc * L;
+  size_t o = 0;
+  auto take = [&](size_t n) { size_t r = o; o += align_up(n); return r; };
+  Plan p;
+  p.NP = (2 * c.n_classes - 1 + 3) / 4 * 4;
+  p.x = take(2 * rows * C * D);
+  p.qkv = take(2 * rows * C * 3 * D);
+  p.t1 = take(2 * rows * C * D);
+  const size_t bigcols = F > H * (size_t)L ? F : H * (size_t)L;
+  p.big = take(2 * rows * C * bigcols);
+  p.attn_floats = attention_workspace_ext(Bc, L, (int)H, (int)D, P, false) / sizeof(float);
+  p.attn = take(p.attn_floats);
+  p.wh = take((size_t)2 * Bc * p.NP * D);
+  p.bh = take((size_t)2 * Bc * p.NP);
+  p.hy = take((size_t)2 * Bc * C * p.NP);
+  p.hl = take((size_t)Bc * p.NP);
+  p.hu = take((size_t)Bc * p.NP);
+  p.eps = take(Bc);
+  p.margin = take((size_t)Bc * (c.n_classes - 1) + 1);
+  p.lohi = take(2 * (size_t)Bc);
+  p.labels = take(Bc);
+  p.status = take(Bc);
+  p.cnt = take(Bc);
+  p.total = o;
+  return p;
+}
+
+int chunk_size(const tv_config &c, int B, int L, int P, size_t ws_bytes) {
+  // largest Bc <= B whose plan fits (plan size is monotone in Bc)
+  if (make_plan(c, 1, L, P).total * sizeof(float) > ws_bytes) return 0;
+  int lo = 1, hi = B;
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) / 2;
+    if (make_plan(c, mid, L, P).total * sizeof(float) <= ws_bytes) lo = mid; else hi = mid - 1;
+  }
+  return lo;
+}
+
+// Eq. (2) in centre/radius form: y = x W^T (+ bias on bias rows of the S plane) (+ add).  Wpair =
+// [W ; |W|], bpair = [b ; 0].  x planes are `xplane` floats apart, y planes `yplane`.
+int affine(const float *xS, long xplane, long M, int C, int K, int N, const float *Wpair, const float *bpair,
+           const float *addS, long addplane, float *yS, long yplane, hipStream_t st) {
+  GemmArgs g;
+  g.A = xS; g.lda = K;
+  g.B = Wpair; g.ldb = K; g.b_mode = 0;
+  g.C = yS; g.ldc = N;
+  g.Cadd = addS;
+  g.bias = bpair; g.bias_ld = 0; g.bias_period = C;
+  TV_REQUIRE(M < (1L << 31), TV_E_SHAPE, "affine: %ld rows exceed the kernel's 32-bit row index", M);
+  g.M = (int)M; g.N = N; g.K = K;
+  g.nz0 = 2;
+  g.sA[0] = xplane; g.sB[0] = (long)N * K; g.sC[0] = yplane; g.sAdd[0] = addplane; g.sBias[0] = N;
+  return gemm(g, st);
+}
+
+int sweep(const tv_model *m, const Plan &pl, float *w, const int32_t *tokens, const int32_t *positions, int Bc, int L,
+          int P, int pn, const float *eps, int32_t *status, hipStream_t st) {
+  const tv_config &c = m->cfg;
+  const int D = c.hidden, F = c.ffn, H = c.n_heads;
+  const int C = P * D + 1;
+  const long rows = (long)Bc * L;
+  const long M = rows * C;
+  const long pD = M * D, p3D = M * 3 * D, pF = M * F, pS = (long)Bc * H * L * C * L;
+  float *X = w + pl.x, *QKV = w + pl.qkv, *T1 = w + pl.t1, *BIG = w + pl.big;
+  void *attn_ws = w + pl.attn;
+  const size_t attn_bytes = pl.attn_floats * sizeof(float);
+
+  if (int rc = fill_zero(X, (size_t)2 * pD, st)) return rc;
+  hipLaunchKernelGGL(init_state_kernel, dim3(nblk(rows * D)), dim3(256), 0, st, tokens, positions, m->tok_emb,
+                     m->pos_emb, Bc, L, D, P, X);
+  TV_HIP(hipGetLastError());
+
+  for (int l = 0; l < c.n_layers; ++l) {
+    const tv_layer_dev &lw = m->layers[l];
+    // q, k, v in one product: columns [0,D) q, [D,2D) k, [2D,3D) v
+    if (int rc = affine(X, pD, M, C, D, 3 * D, lw.Wqkv, lw.bqkv, nullptr, 0, QKV, p3D, st)) return rc;
+    CState q{QKV, QKV + p3D}, k{QKV + D, QKV + p3D + D}, v{QKV + 2 * D, QKV + p3D + 2 * D};
+    State o{T1, T1 + pD}, s{BIG, BIG + pS};
+    if (int rc = attention(q, k, v, 3 * D, Bc, L, H, D, P, pn, eps, o, s, 0, status, attn_ws, attn_bytes, st))
+      return rc;
+    // a = o Wo^T + bo + x   (written over the dead q/k/v region), x' = LN(a) (over the dead x)
+    float *A = QKV;
+    if (int rc = affine(T1, pD, M, C, D, D, lw.Wo, lw.bo, X, pD, A, pD, st)) return rc;
+    if (int rc = layernorm(CState{A, A + pD}, (int)rows, P, D, D, L, pn, eps, lw.ln1_g, lw.ln1_b, c.ln_eps,
+                           State{X, X + pD}, status, st)) return rc;
+    // feed-forward: h = x' W1^T + b1 ; act ; f = act W2^T + b2 + x' ; x'' = LN(f)
+    if (int rc = affine(X, pD, M, C, D, F, lw.W1, lw.b1, nullptr, 0, BIG, pF, st)) return rc;
+    if (int rc = activation(c.activation, CState{BIG, BIG + pF}, (int)rows, P, D, F, L, pn, eps,
+                            State{BIG, BIG + pF}, status, st)) return rc;
+    if (int rc = affine(BIG, pF, M, C, F, D, lw.W2, lw.b2, X, pD, T1, pD, st)) return rc;
+    if (int rc = layernorm(CState{T1, T1 + pD}, (int)rows, P, D, D, L, pn, eps, lw.ln2_g, lw.ln2_b, c.ln_eps,
+                           State{X, X + pD}, status, st)) return rc;
+  }
+  return TV_OK;
+}
+
+// Head on token 0 of every sentence: class rows and margin rows through Eq. (2), then Eq. (1).
+int head(const tv_model *m, const Plan &pl, float *w, int Bc, int L, int P, int pn, const float *eps,
+         const int32_t *labels, hipStream_t st) {
+  const tv_config &c = m->cfg;
+  const int D = c.hidden, C = P * D + 1, NP = pl.NP;
+  const long pD = (long)Bc * L * C * D;
+  float *Wh = w + pl.wh, *bh = w + pl.bh, *Y = w + pl.hy;
+  hipLaunchKernelGGL(head_prep_kernel, dim3(nblk((long)Bc * NP * D)), dim3(256), 0, st, m->Wc, m->bc, labels, Bc,
+                     c.n_classes, NP, D, Wh, bh);
+  TV_HIP(hipGetLastError());
+  GemmArgs g;
+  g.A = w + pl.x; g.lda = D;
+  g.B = Wh; g.ldb = D; g.b_mode = 0;
+  g.C = Y; g.ldc = NP;
+  g.bias = bh; g.bias_ld = 0; g.bias_period = C;
+  g.M = C; g.N = NP; g.K = D;
+  g.nz0 = 2; g.nz1 = Bc;
+  g.sA[0] = pD; g.sA[1] = (long)L * C * D;
+  g.sB[0] = (long)Bc * NP * D; g.sB[1] = (long)NP * D;
+  g.sC[0] = (long)Bc * C * NP; g.sC[1] = (long)C * NP;
+  g.sBias[0] = (long)Bc * NP; g.sBias[1] = NP;
+  if (int rc = gemm(g, st)) return rc;
+  return concretize(CState{Y, Y + (long)Bc * C * NP}, Bc, P, D, NP, NP, 1, pn, eps, w + pl.hl, w + pl.hu, st);
+}
+
+int check_call(const tv_model *m, const int32_t *tokens, int B, int L, const int32_t *positions, int P, int pn,
+               const void *ws) {
+  TV_REQUIRE(m && tokens && positions && ws, TV_E_NULL, "null model, tokens, positions or workspace");
+  TV_REQUIRE(B > 0 && L > 0 && L % 4 == 0 && L <= m->cfg.max_len, TV_E_SHAPE,
+             "need B > 0 and 0 < L <= max_len with L %% 4 == 0 (B=%d L=%d max_len=%d)", B, L, m->cfg.max_len);
+  TV_REQUIRE(P >= 1 && P <= kMaxP && P <= L, TV_E_SHAPE, "P must be in [1, %d] and <= L, got %d", kMaxP, P);
+  TV_REQUIRE(norm_ok(pn), TV_E_NORM, "p_norm must be 1, 2 or TV_NORM_INF, got %d", pn);
+  return TV_OK;
+}
+
+// labels of a chunk: given, or the clean prediction from a bias-only sweep (P = 0: every state has
+// the bias row only, so the kernels compute the plain forward pass)
+int chunk_labels(const tv_model *m, float *w, const Plan &pl, const int32_t *tokens, const int32_t *positions,
+                 int Bc, int L, int pn, const int32_t *labels, hipStream_t st) {
+  int32_t *lab = reinterpret_cast<int32_t *>(w + pl.labels), *status = reinterpret_cast<int32_t *>(w + pl.status);
+  if (labels) {
+    hipLaunchKernelGGL(copy_i32_kernel, dim3(nblk(Bc)), dim3(256), 0, st, labels, lab, Bc);
+    TV_HIP(hipGetLastError());
+    return TV_OK;
+  }
+  const Plan p0 = make_plan(m->cfg, Bc, L, 0);
+  float *eps0 = w + p0.eps;
+  hipLaunchKernelGGL(zero_eps_kernel, dim3(nblk(Bc)), dim3(256), 0, st, eps0, Bc);
+  hipLaunchKernelGGL(fill_i32_kernel, dim3(nblk(Bc)), dim3(256), 0, st, reinterpret_cast<int32_t *>(w + p0.labels),
+                     Bc, 0);
+  hipLaunchKernelGGL(fill_i32_kernel, dim3(nblk(Bc)), dim3(256), 0, st, reinterpret_cast<int32_t *>(w + p0.status),
+                     Bc, 0);
+  TV_HIP(hipGetLastError());
+  if (int rc = sweep(m, p0, w, tokens, positions, Bc, L, 0, pn, eps0, reinterpret_cast<int32_t *>(w + p0.status), st))
+    return rc;
+  if (int rc = head(m, p0, w, Bc, L, 0, pn, eps0, reinterpret_cast<int32_t *>(w + p0.labels), st)) return rc;
+  // p0's small arrays sit below pl's (its big regions are smaller), so writing pl.labels last is safe
+  hipLaunchKernelGGL(argmax_kernel, dim3(nblk(Bc)), dim3(256), 0, st, w + p0.hl, w + p0.hu, Bc, m->cfg.n_classes,
+                     p0.NP, lab);
+  TV_HIP(hipGetLastError());
+  (void)status;
+  return TV_OK;
+}
+
+}  // namespace
+
+// ---- exported API ------------------------------------------------------------------------------
+extern "C" {
+
+const char *tv_version(void) { return "libtv 0.1 (gfx950)"; }
+const char *tv_last_error(void) { return tv::g_err; }
+
+int tv_model_create(const tv_config *cfg, const tv_weights *w, tv_model **out) {
+  TV_REQUIRE(cfg && w && out && w->layers, TV_E_NULL, "tv_model_create: null argument");
+  const tv_config &c = *cfg;
+  TV_REQUIRE(c.n_layers > 0 && c.hidden > 0 && c.n_heads > 0 && c.ffn > 0 && c.vocab > 0 && c.max_len > 0,
+             TV_E_SHAPE, "tv_model_create: sizes must be positive");
+  TV_REQUIRE(c.hidden % c.n_heads == 0 && c.hidden % 4 == 0 && c.ffn % 4 == 0 && (c.hidden / c.n_heads) % 4 == 0,
+             TV_E_SHAPE, "tv_model_create: hidden %% n_heads == 0 and hidden, ffn, head width multiples of 4 required");
+  TV_REQUIRE(c.hidden <= 1024, TV_E_SHAPE, "tv_model_create: hidden > 1024 not supported");
+  TV_REQUIRE(c.n_classes >= 2 && c.n_classes <= 16, TV_E_SHAPE, "tv_model_create: n_classes must be in [2, 16]");
+  TV_REQUIRE(c.activation == TV_ACT_RELU || c.activation == TV_ACT_TANH || c.activation == TV_ACT_GELU, TV_E_ARG,
+             "tv_model_create: unknown activation %d", c.activation);
+  TV_REQUIRE(c.ln_eps > 0.f, TV_E_ARG, "tv_model_create: ln_eps must be positive");
+  TV_REQUIRE(w->tok_emb && w->pos_emb && w->Wc && w->bc, TV_E_NULL, "tv_model_create: null weight array");
+  for (int l = 0; l < c.n_layers; ++l) {
+    const tv_layer_weights &lw = w->layers[l];
+    TV_REQUIRE(lw.Wq && lw.bq && lw.Wk && lw.bk && lw.Wv && lw.bv && lw.Wo && lw.bo && lw.ln1_g && lw.ln1_b && lw.W1 &&
+                   lw.b1 && lw.W2 && lw.b2 && lw.ln2_g && lw.ln2_b,
+               TV_E_NULL, "tv_model_create: null weight array in layer %d", l);
+  }
+  const size_t D = c.hidden, F = c.ffn;
+  tv_model *m = new tv_model;
+  m->cfg = c;
+  m->layers.resize(c.n_layers);
+  size_t o = 0;
+  auto take = [&](size_t n) { size_t r = o; o += align_up(n); return r; };
+  const size_t o_tok = take((size_t)c.vocab * D), o_pos = take((size_t)c.max_len * D);
+  const size_t o_wc = take((size_t)c.n_classes * D), o_bc = take(c.n_classes);
+  struct Off { size_t Wqkv, bqkv, Wo, bo, W1, b1, W2, b2, g1, be1, g2, be2; };
+  std::vector<Off> off(c.n_layers);
+  for (int l = 0; l < c.n_layers; ++l) {
+    Off &f = off[l];
+    f.Wqkv = take(2 * 3 * D * D); f.bqkv = take(2 * 3 * D);
+    f.Wo = take(2 * D * D); f.bo = take(2 * D);
+    f.W1 = take(2 * F * D); f.b1 = take(2 * F);
+    f.W2 = take(2 * D * F); f.b2 = take(2 * D);
+    f.g1 = take(D); f.be1 = take(D); f.g2 = take(D); f.be2 = take(D);
+  }
+  m->blob_floats = o;
+  hipError_t e = hipMalloc(&m->blob, o * sizeof(float));
+  if (e != hipSuccess) { delete m; return tv::fail(TV_E_HIP, "hipMalloc(%zu bytes): %s", o * sizeof(float), hipGetErrorString(e)); }
+  e = hipMemset(m->blob, 0, o * sizeof(float));
+  const hipMemcpyKind kind = w->on_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice;
+  auto put = [&](size_t dst, const float *src, size_t n) {
+    if (e == hipSuccess) e = hipMemcpy(m->blob + dst, src, n * sizeof(float), kind);
+  };
+  auto put_abs = [&](size_t base, size_t n) {   // second copy = |first copy|
+    if (e == hipSuccess && tv::vec_abs(m->blob + base, m->blob + base + n, n, nullptr) != TV_OK) e = hipErrorUnknown;
+  };
+  put(o_tok, w->tok_emb, (size_t)c.vocab * D); put(o_pos, w->pos_emb, (size_t)c.max_len * D);
+  put(o_wc, w->Wc, (size_t)c.n_classes * D); put(o_bc, w->bc, c.n_classes);
+  m->tok_emb = m->blob + o_tok; m->pos_emb = m->blob + o_pos; m->Wc = m->blob + o_wc; m->bc = m->blob + o_bc;
+  for (int l = 0; l < c.n_layers; ++l) {
+    const tv_layer_weights &lw = w->layers[l];
+    const Off &f = off[l];
+    put(f.Wqkv, lw.Wq, D * D); put(f.Wqkv + D * D, lw.Wk, D * D); put(f.Wqkv + 2 * D * D, lw.Wv, D * D);
+    put_abs(f.Wqkv, 3 * D * D);
+    put(f.bqkv, lw.bq, D); put(f.bqkv + D, lw.bk, D); put(f.bqkv + 2 * D, lw.bv, D);
+    put(f.Wo, lw.Wo, D * D); put_abs(f.Wo, D * D); put(f.bo, lw.bo, D);
+    put(f.W1, lw.W1, F * D); put_abs(f.W1, F * D); put(f.b1, lw.b1, F);
+    put(f.W2, lw.W2, D * F); put_abs(f.W2, D * F); put(f.b2, lw.b2, D);
+    put(f.g1, lw.ln1_g, D); put(f.be1, lw.ln1_b, D); put(f.g2, lw.ln2_g, D); put(f.be2, lw.ln2_b, D);
+    tv_layer_dev &d = m->layers[l];
+    d.Wqkv = m->blob + f.Wqkv; d.bqkv = m->blob + f.bqkv; d.Wo = m->blob + f.Wo; d.bo = m->blob + f.bo;
+    d.W1 = m->blob + f.W1; d.b1 = m->blob + f.b1; d.W2 = m->blob + f.W2; d.b2 = m->blob + f.b2;
+    d.ln1_g = m->blob + f.g1; d.ln1_b = m->blob + f.be1; d.ln2_g = m->blob + f.g2; d.ln2_b = m->blob + f.be2;
+  }
+  if (e == hipSuccess) e = hipDeviceSynchronize();
+  if (e != hipSuccess) {
+    (void)hipFree(m->blob);
+    delete m;
+    return tv::fail(TV_E_HIP, "tv_model_create: weight upload failed: %s", hipGetErrorString(e));
+  }
+  *out = m;
+  return TV_OK;
+}
+
+void tv_model_destroy(tv_model *m) {
+  if (!m) return;
+  (void)hipDeviceSynchronize();
+  (void)hipFree(m->blob);
+  delete m;
+}
+
+int tv_workspace_query(const tv_model *m, int B, int L, int P, size_t *bytes_full, size_t *bytes_min) {
+  TV_REQUIRE(m, TV_E_NULL, "tv_workspace_query: null model");
+  TV_REQUIRE(B > 0 && L > 0 && L % 4 == 0 && P >= 1 && P <= kMaxP, TV_E_SHAPE, "tv_workspace_query: bad sizes");
+  if (bytes_full) *bytes_full = make_plan(m->cfg, B, L, P).total * sizeof(float);
+  if (bytes_min) *bytes_min = make_plan(m->cfg, 1, L, P).total * sizeof(float);
+  return TV_OK;
+}
+
+int tv_verify(const tv_model *m, const int32_t *tokens, int B, int L, const int32_t *positions, int P, int pn,
+              const float *eps, const int32_t *labels, float *out_lower, float *out_upper, float *out_margin_lower,
+              int32_t *out_labels, int32_t *status, void *workspace, size_t workspace_bytes, void *stream) {
+  if (int rc = check_call(m, tokens, B, L, positions, P, pn, workspace)) return rc;
+  TV_REQUIRE(eps && out_lower && out_upper && status, TV_E_NULL, "tv_verify: null eps or output pointer");
+  const int Bmax = chunk_size(m->cfg, B, L, P, workspace_bytes);
+  TV_REQUIRE(Bmax >= 1, TV_E_WORKSPACE, "tv_verify: workspace of %zu bytes cannot hold one sentence (%zu needed)",
+             workspace_bytes, make_plan(m->cfg, 1, L, P).total * sizeof(float));
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  float *w = static_cast<float *>(workspace);
+  const int nc = m->cfg.n_classes;
+  for (int b0 = 0; b0 < B; b0 += Bmax) {
+    const int Bc = B - b0 < Bmax ? B - b0 : Bmax;
+    const Plan pl = make_plan(m->cfg, Bc, L, P);
+    int32_t *lab = reinterpret_cast<int32_t *>(w + pl.labels), *stat = reinterpret_cast<int32_t *>(w + pl.status);
+    const int32_t *tok = tokens + (size_t)b0 * L, *pos = positions + (size_t)b0 * P;
+    if (int rc = chunk_labels(m, w, pl, tok, pos, Bc, L, pn, labels ? labels + b0 : nullptr, st)) return rc;
+    hipLaunchKernelGGL(fill_i32_kernel, dim3(nblk(Bc)), dim3(256), 0, st, stat, Bc, 0);
+    TV_HIP(hipGetLastError());
+    if (int rc = sweep(m, pl, w, tok, pos, Bc, L, P, pn, eps + b0, stat, st)) return rc;
+    if (int rc = head(m, pl, w, Bc, L, P, pn, eps + b0, lab, st)) return rc;
+    hipLaunchKernelGGL(head_out_kernel, dim3(nblk(Bc)), dim3(256), 0, st, w + pl.hl, w + pl.hu, stat, lab, Bc, nc,
+                       pl.NP, out_lower + (size_t)b0 * nc, out_upper + (size_t)b0 * nc,
+                       out_margin_lower ? out_margin_lower + (size_t)b0 * (nc - 1) : nullptr,
+                       out_labels ? out_labels + b0 : nullptr, status + b0, w + pl.margin);
+    TV_HIP(hipGetLastError());
+  }
+  return TV_OK;
+}
+
+int tv_certify(const tv_model *m, const int32_t *tokens, int B, int L, const int32_t *positions, int P, int pn,
+               float eps_lo, float eps_hi, int steps, const int32_t *labels, float *out_eps, int32_t *out_labels,
+               int32_t *status, void *workspace, size_t workspace_bytes, void *stream) {
+  if (int rc = check_call(m, tokens, B, L, positions, P, pn, workspace)) return rc;
+  TV_REQUIRE(out_eps && status, TV_E_NULL, "tv_certify: null output pointer");
+  TV_REQUIRE(steps >= 1 && steps <= 64, TV_E_ARG, "tv_certify: steps must be in [1, 64], got %d", steps);
+  TV_REQUIRE(eps_lo >= 0.f && eps_hi > eps_lo && eps_hi <= 3.0e38f, TV_E_ARG,
+             "tv_certify: need 0 <= eps_lo < eps_hi (finite)");
+  const int Bmax = chunk_size(m->cfg, B, L, P, workspace_bytes);
+  TV_REQUIRE(Bmax >= 1, TV_E_WORKSPACE, "tv_certify: workspace of %zu bytes cannot hold one sentence (%zu needed)",
+             workspace_bytes, make_plan(m->cfg, 1, L, P).total * sizeof(float));
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  float *w = static_cast<float *>(workspace);
+  const int nc = m->cfg.n_classes;
+  for (int b0 = 0; b0 < B; b0 += Bmax) {
+    const int Bc = B - b0 < Bmax ? B - b0 : Bmax;
+    const Plan pl = make_plan(m->cfg, Bc, L, P);
+    int32_t *lab = reinterpret_cast<int32_t *>(w + pl.labels), *stat = reinterpret_cast<int32_t *>(w + pl.status);
+    int32_t *cnt = reinterpret_cast<int32_t *>(w + pl.cnt);
+    float *eps = w + pl.eps, *lohi = w + pl.lohi, *margin = w + pl.margin;
+    const int32_t *tok = tokens + (size_t)b0 * L, *pos = positions + (size_t)b0 * P;
+    if (int rc = chunk_labels(m, w, pl, tok, pos, Bc, L, pn, labels ? labels + b0 : nullptr, st)) return rc;
+    hipLaunchKernelGGL(search_init_kernel, dim3(nblk(Bc)), dim3(256), 0, st, lohi, Bc, eps_lo, eps_hi, cnt);
+    TV_HIP(hipGetLastError());
+    for (int it = 0; it < steps; ++it) {
+      hipLaunchKernelGGL(search_mid_kernel, dim3(nblk(Bc)), dim3(256), 0, st, lohi, Bc, eps);
+      hipLaunchKernelGGL(fill_i32_kernel, dim3(nblk(Bc)), dim3(256), 0, st, stat, Bc, 0);
+      TV_HIP(hipGetLastError());
+      if (int rc = sweep(m, pl, w, tok, pos, Bc, L, P, pn, eps, stat, st)) return rc;
+      if (int rc = head(m, pl, w, Bc, L, P, pn, eps, lab, st)) return rc;
+      hipLaunchKernelGGL(head_out_kernel, dim3(nblk(Bc)), dim3(256), 0, st, w + pl.hl, w + pl.hu, stat, lab, Bc, nc,
+                         pl.NP, (float *)nullptr, (float *)nullptr, (float *)nullptr, (int32_t *)nullptr, stat, margin);
+      hipLaunchKernelGGL(search_update_kernel, dim3(nblk(Bc)), dim3(256), 0, st, lohi, Bc, eps, margin, nc - 1, stat,
+                         cnt);
+      TV_HIP(hipGetLastError());
+    }
+    hipLaunchKernelGGL(copy_f32_kernel, dim3(nblk(Bc)), dim3(256), 0, st, lohi, out_eps + b0, Bc);
+    hipLaunchKernelGGL(copy_i32_kernel, dim3(nblk(Bc)), dim3(256), 0, st, cnt, status + b0, Bc);
+    if (out_labels) hipLaunchKernelGGL(copy_i32_kernel, dim3(nblk(Bc)), dim3(256), 0, st, lab, out_labels + b0, Bc);
+    TV_HIP(hipGetLastError());
+  }
+  return TV_OK;
+}
+
+// ---- single operators --------------------------------------------------------------------------
+int tv_op_concretize(const float *S, const float *R, int rows, int P, int E, int n, int rps, int pn, const float *eps,
+                     float *l, float *u, void *stream) {
+  return concretize(CState{S, R}, rows, P, E, n, n, rps, pn, eps, l, u, static_cast<hipStream_t>(stream));
+}
+
+int tv_op_abs(const float *in, float *out, size_t count, void *stream) {
+  return vec_abs(in, out, count, static_cast<hipStream_t>(stream));
+}
+
+int tv_op_affine(const float *Sx, const float *Rx, int rows, int P, int E, int K, int N, const float *W,
+                 const float *Wabs, const float *bias, const float *Sadd, const float *Radd, float *Sy, float *Ry,
+                 void *stream) {
+  TV_REQUIRE(Sx && Rx && W && Wabs && Sy && Ry, TV_E_NULL, "tv_op_affine: null pointer");
+  TV_REQUIRE((Sadd == nullptr) == (Radd == nullptr), TV_E_NULL, "tv_op_affine: Sadd and Radd must both be given or both NULL");
+  TV_REQUIRE(rows > 0 && P >= 0 && E > 0 && K > 0 && N > 0 && K % 4 == 0 && N % 4 == 0, TV_E_SHAPE,
+             "tv_op_affine: bad shape rows=%d P=%d E=%d K=%d N=%d", rows, P, E, K, N);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int C = P * E + 1;
+  const long M = (long)rows * C;
+  TV_REQUIRE(M < (1L << 31), TV_E_SHAPE, "tv_op_affine: too many rows");
+  // the two planes use unrelated buffers here: one launch per plane
+  GemmArgs g;
+  g.lda = K; g.ldb = K; g.b_mode = 0; g.ldc = N; g.M = (int)M; g.N = N; g.K = K;
+  g.A = Sx; g.B = W; g.C = Sy; g.Cadd = Sadd; g.bias = bias; g.bias_ld = 0; g.bias_period = C;
+  if (int rc = gemm(g, st)) return rc;
+  g.A = Rx; g.B = Wabs; g.C = Ry; g.Cadd = Radd; g.bias = nullptr;
+  return gemm(g, st);
+}
+
+int tv_op_activation(int act, const float *Sx, const float *Rx, int rows, int P, int E, int n, int rps, int pn,
+                     const float *eps, float *Sy, float *Ry, int32_t *status, void *stream) {
+  return activation(act, CState{Sx, Rx}, rows, P, E, n, rps, pn, eps, State{Sy, Ry}, status,
+                    static_cast<hipStream_t>(stream));
+}
+
+int tv_op_layernorm(const float *Sx, const float *Rx, int rows, int P, int E, int n, int rps, int pn, const float *eps,
+                    const float *gamma, const float *beta, float ln_eps, float *Sy, float *Ry, int32_t *status,
+                    void *stream) {
+  TV_REQUIRE(Sx != Sy && Rx != Ry, TV_E_ARG, "tv_op_layernorm: output must not alias the input");
+  return layernorm(CState{Sx, Rx}, rows, P, E, n, rps, pn, eps, gamma, beta, ln_eps, State{Sy, Ry}, status,
+                   static_cast<hipStream_t>(stream));
+}
+
+size_t tv_attention_workspace(int B, int L, int H, int D, int P) { return attention_workspace_ext(B, L, H, D, P, true); }
+
+int tv_op_attention(const float *Sq, const float *Rq, const float *Sk, const float *Rk, const float *Sv,
+                    const float *Rv, int B, int L, int H, int D, int P, int pn, const float *eps, float *So, float *Ro,
+                    float *Ss, float *Rs, int stop_after, int32_t *status, void *workspace, size_t workspace_bytes,
+                    void *stream) {
+  return attention(CState{Sq, Rq}, CState{Sk, Rk}, CState{Sv, Rv}, D, B, L, H, D, P, pn, eps, State{So, Ro},
+                   State{Ss, Rs}, stop_after, status, workspace, workspace_bytes, static_cast<hipStream_t>(stream));
+}
+
+}  // extern "C"

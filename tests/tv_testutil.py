@@ -1,0 +1,72 @@
+"""Helpers shared by the GPU parity tests: random bound states, oracle <-> plane conversion, tolerances."""
+import numpy as np
+
+from oracle import bounds as B
+
+
+def random_state(rng, shape, P, E, eps, p, wscale=1.0, slack=0.2, offset=0.0, bscale=1.0, spread=0.3):
+    """An oracle Bounds with unordered lw/uw and lb <= ub wide enough that lower(delta) <= upper(delta)."""
+    PE = P * E
+    w = rng.standard_normal(shape + (PE,)) * wscale
+    lw = w + rng.standard_normal(shape + (PE,)) * spread * wscale
+    uw = w + rng.standard_normal(shape + (PE,)) * spread * wscale
+    b = rng.standard_normal(shape) * bscale + offset
+    s = np.abs(rng.standard_normal(shape)) * slack
+    gap = eps * B.block_dual_norm(uw - lw, P, p) if P > 0 else 0.0
+    return B.Bounds(lw, b - s - 0.5 * gap, uw, b + s + 0.5 * gap)
+
+
+def to_planes(X):
+    """Oracle state (neuron shape [rows..., n]) -> fp32 centre/radius planes [rows, C, n] (bias row last)."""
+    lw, uw, lb, ub = X.lw, X.uw, X.lb, X.ub
+    n = lb.shape[-1]
+    rows = int(np.prod(lb.shape[:-1]))
+    PE = lw.shape[-1]
+    lw = lw.reshape(rows, n, PE).transpose(0, 2, 1)
+    uw = uw.reshape(rows, n, PE).transpose(0, 2, 1)
+    L = np.concatenate([lw, lb.reshape(rows, 1, n)], 1)
+    U = np.concatenate([uw, ub.reshape(rows, 1, n)], 1)
+    return (0.5 * (U + L)).astype(np.float32), (0.5 * (U - L)).astype(np.float32)
+
+
+def from_planes(S, R):
+    """fp32 planes [rows, C, n] -> oracle-style (lw [rows,n,PE], lb [rows,n], uw, ub) in float64."""
+    S = S.astype(np.float64); R = R.astype(np.float64)
+    L, U = S - R, S + R
+    return (L[:, :-1].transpose(0, 2, 1), L[:, -1], U[:, :-1].transpose(0, 2, 1), U[:, -1])
+
+
+def quantize(X):
+    """Round an oracle state to what the fp32 planes hold, so that both sides start from identical inputs."""
+    S, R = to_planes(X)
+    lw, lb, uw, ub = from_planes(S, R)
+    shp = X.lb.shape
+    return B.Bounds(lw.reshape(shp + (-1,)), lb.reshape(shp), uw.reshape(shp + (-1,)), ub.reshape(shp))
+
+
+def assert_close(got, ref, what, rtol=1e-4, atol_scale=1e-6):
+    """|g - o| <= rtol*|o| + atol_scale*max|o| elementwise."""
+    got = np.asarray(got, np.float64); ref = np.asarray(ref, np.float64)
+    assert got.shape == ref.shape, (what, got.shape, ref.shape)
+    S = np.abs(ref).max() if ref.size else 0.0
+    err = np.abs(got - ref)
+    tol = rtol * np.abs(ref) + atol_scale * S
+    bad = err > tol
+    if bad.any():
+        i = np.unravel_index(np.argmax(err - tol), err.shape)
+        raise AssertionError(f"{what}: {bad.sum()} of {bad.size} off; worst at {i}: got {got[i]!r} ref {ref[i]!r} "
+                             f"(scale {S:.3e})")
+
+
+def assert_state_close(planes, X, what, rtol=1e-4, atol_scale=2e-6):
+    """Compare GPU planes with an oracle state on the lower / upper lines (weights and biases)."""
+    lw, lb, uw, ub = from_planes(*planes)
+    shp = X.lb.shape
+    rows = int(np.prod(shp[:-1]))
+    n = shp[-1]
+    scale_ref = np.concatenate([X.lw.reshape(rows, n, -1), X.uw.reshape(rows, n, -1)], -1)
+    assert_close(lw, X.lw.reshape(rows, n, -1), what + ".lw", rtol, atol_scale * max(1.0, 0))
+    assert_close(uw, X.uw.reshape(rows, n, -1), what + ".uw", rtol, atol_scale)
+    assert_close(lb, X.lb.reshape(rows, n), what + ".lb", rtol, atol_scale)
+    assert_close(ub, X.ub.reshape(rows, n), what + ".ub", rtol, atol_scale)
+    del scale_ref
