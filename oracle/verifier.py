@@ -205,11 +205,15 @@ def verify(m, tokens, positions, p, eps, label=None, trace=None):
         Mg = B.affine(X[0], Wc[label][None, :] - Wc[others], bc[label] - bc[others])
         ml, _ = ctx.conc(Mg)
         status = 0
+        # magnitude of the head's terms before cancellation (a scale for comparing bounds near zero)
+        lh, uh = ctx.conc(X[0])
+        scale = float((np.abs(Wc) @ np.maximum(np.abs(lh), np.abs(uh)) + np.abs(bc)).max())
     except NotFinite:
         lo = np.full(n_cls, -np.inf); up = np.full(n_cls, np.inf)
         ml = np.full(n_cls - 1, -np.inf)
         status = 1
-    return {"lower": lo, "upper": up, "margin_lower": ml, "status": status, "label": label}
+        scale = float("inf")
+    return {"lower": lo, "upper": up, "margin_lower": ml, "status": status, "label": label, "head_scale": scale}
 
 
 def is_verified(res):

@@ -17,8 +17,18 @@ namespace {
 
 // coefficient matrices for q k^T from the concretized ranges of q and k
 //   coef[b][h][plane][j][kk]   (kk < dh: on S_q ; kk >= dh: on R_q),  lqs[plane][b][i][D]
-__global__ void qk_prep_kernel(const float *lq, const float *lk, const float *uk, int B, int L, int H, int dh,
-                               float scale, float *coef, float *lqs) {
+// Ranges arrive as (mid, half) so that narrow intervals keep their width in fp32; with l = mid - half,
+// u = mid + half:  (l+u)/2 = mid, (u-l)/2 = half, and (|u| -+ |l|)/2 is half / mid, -half / -mid or
+// mid / half for l >= 0, u <= 0 or a crossing interval.
+__device__ __forceinline__ void abs_parts(float mid, float half, float &dif, float &sum) {
+  const float l = mid - half, u = mid + half;
+  if (l >= 0.f) { dif = half; sum = mid; }
+  else if (u <= 0.f) { dif = -half; sum = -mid; }
+  else { dif = mid; sum = half; }
+}
+
+__global__ void qk_prep_kernel(const float *mq, const float *hq, const float *mk, const float *hk, int B, int L, int H,
+                               int dh, float scale, float *coef, float *lqs) {
   const int D = H * dh;
   const long total = (long)B * L * D;
   for (long i = (long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long)gridDim.x * blockDim.x) {
@@ -26,22 +36,23 @@ __global__ void qk_prep_kernel(const float *lq, const float *lk, const float *uk
     const long bj = i / D;
     const int j = (int)(bj % L), b = (int)(bj / L);
     const int h = dfull / dh, d = dfull % dh;
-    const float l = lk[i], u = uk[i];
+    float dif, sum;
+    abs_parts(mk[i], hk[i], dif, sum);
     float *c0 = coef + ((((long)b * H + h) * 2 + 0) * L + j) * (2 * dh);
     float *c1 = coef + ((((long)b * H + h) * 2 + 1) * L + j) * (2 * dh);
-    c0[d] = 0.5f * (l + u) * scale;
-    c0[dh + d] = 0.5f * (fabsf(u) - fabsf(l)) * scale;
-    c1[d] = 0.5f * (u - l) * scale;
-    c1[dh + d] = 0.5f * (fabsf(u) + fabsf(l)) * scale;
-    const float q = lq[i];
+    c0[d] = mk[i] * scale;
+    c0[dh + d] = dif * scale;
+    c1[d] = hk[i] * scale;
+    c1[dh + d] = sum * scale;
+    const float q = mq[i] - hq[i];
     lqs[i] = q * scale;
     lqs[total + i] = fabsf(q) * scale;
   }
 }
 
 // constants of the planes: cst[b][h][plane][i][j] = -scale * sum_d lq[i,d] * {(lk+uk)/2, (uk-lk)/2}[j,d]
-__global__ void qk_const_kernel(const float *lq, const float *lk, const float *uk, int B, int L, int H, int dh,
-                                float scale, float *cst) {
+__global__ void qk_const_kernel(const float *mq, const float *hq, const float *mk, const float *hk, int B, int L,
+                                int H, int dh, float scale, float *cst) {
   const int D = H * dh;
   const long total = (long)B * H * L * L;
   for (long t = (long)blockIdx.x * blockDim.x + threadIdx.x; t < total; t += (long)gridDim.x * blockDim.x) {
@@ -49,13 +60,12 @@ __global__ void qk_const_kernel(const float *lq, const float *lk, const float *u
     long r = t / L;
     const int i = (int)(r % L); r /= L;
     const int h = (int)(r % H), b = (int)(r / H);
-    const float *pq = lq + ((long)b * L + i) * D + h * dh;
-    const float *pl = lk + ((long)b * L + j) * D + h * dh;
-    const float *pu = uk + ((long)b * L + j) * D + h * dh;
+    const long oq = ((long)b * L + i) * D + h * dh, ok = ((long)b * L + j) * D + h * dh;
     float s = 0.f, rr = 0.f;
     for (int d = 0; d < dh; ++d) {
-      s = fmaf(pq[d], 0.5f * (pl[d] + pu[d]), s);
-      rr = fmaf(pq[d], 0.5f * (pu[d] - pl[d]), rr);
+      const float q = mq[oq + d] - hq[oq + d];
+      s = fmaf(q, mk[ok + d], s);
+      rr = fmaf(q, hk[ok + d], rr);
     }
     float *o = cst + (((long)b * H + h) * 2) * L * L + (long)i * L + j;
     o[0] = -scale * s;
@@ -64,7 +74,7 @@ __global__ void qk_const_kernel(const float *lq, const float *lk, const float *u
 }
 
 // coefficient matrices for p v:  coef[b][h][plane][d][kk]  (kk < L: on S_p[.., j=kk] ; kk >= L: on R_p)
-__global__ void pv_prep_kernel(const float *lv, const float *uv, int B, int L, int H, int dh, float *coef) {
+__global__ void pv_prep_kernel(const float *mv, const float *hv, int B, int L, int H, int dh, float *coef) {
   const int D = H * dh;
   const long total = (long)B * L * D;
   for (long i = (long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long)gridDim.x * blockDim.x) {
@@ -72,18 +82,19 @@ __global__ void pv_prep_kernel(const float *lv, const float *uv, int B, int L, i
     const long bj = i / D;
     const int j = (int)(bj % L), b = (int)(bj / L);
     const int h = dfull / dh, d = dfull % dh;
-    const float l = lv[i], u = uv[i];
+    float dif, sum;
+    abs_parts(mv[i], hv[i], dif, sum);
     float *c0 = coef + ((((long)b * H + h) * 2 + 0) * dh + d) * (2 * L);
     float *c1 = coef + ((((long)b * H + h) * 2 + 1) * dh + d) * (2 * L);
-    c0[j] = 0.5f * (l + u);
-    c0[L + j] = 0.5f * (fabsf(u) - fabsf(l));
-    c1[j] = 0.5f * (u - l);
-    c1[L + j] = 0.5f * (fabsf(u) + fabsf(l));
+    c0[j] = mv[i];
+    c0[L + j] = dif;
+    c1[j] = hv[i];
+    c1[L + j] = sum;
   }
 }
 
 // cst[plane][b][i][D] = - sum_j lp[b,h,i,j] * {(lv+uv)/2, (uv-lv)/2}[b,j,dfull]
-__global__ void pv_const_kernel(const float *lp, const float *lv, const float *uv, int B, int L, int H, int dh,
+__global__ void pv_const_kernel(const float *lp, const float *mv, const float *hv, int B, int L, int H, int dh,
                                 float *cst) {
   const int D = H * dh;
   const long total = (long)B * L * D;
@@ -96,9 +107,8 @@ __global__ void pv_const_kernel(const float *lp, const float *lv, const float *u
     float s = 0.f, rr = 0.f;
     for (int j = 0; j < L; ++j) {
       const long k = ((long)b * L + j) * D + dfull;
-      const float l = lv[k], u = uv[k];
-      s = fmaf(pp[j], 0.5f * (l + u), s);
-      rr = fmaf(pp[j], 0.5f * (u - l), rr);
+      s = fmaf(pp[j], mv[k], s);
+      rr = fmaf(pp[j], hv[k], rr);
     }
     cst[t] = -s;
     cst[total + t] = -rr;
@@ -153,14 +163,15 @@ int attention(CState q, CState k, CState v, int ld, int B, int L, int H, int D, 
   if (own) { s.S = w + lay.sS; s.R = w + lay.sR; }
 
   TV_REQUIRE(ld >= D && ld % 4 == 0, TV_E_SHAPE, "attention: bad row stride %d", ld);
-  if (int rc = concretize(q, rows, P, D, D, ld, L, pn, eps, lq, uq, st)) return rc;
-  if (int rc = concretize(k, rows, P, D, D, ld, L, pn, eps, lk, uk, st)) return rc;
-  if (int rc = concretize(v, rows, P, D, D, ld, L, pn, eps, lv, uv, st)) return rc;
+  // ranges as (mid, half): lq/uq etc. name the two output arrays of each call
+  if (int rc = concretize(q, rows, P, D, D, ld, L, pn, eps, lq, uq, 1, st)) return rc;
+  if (int rc = concretize(k, rows, P, D, D, ld, L, pn, eps, lk, uk, 1, st)) return rc;
+  if (int rc = concretize(v, rows, P, D, D, ld, L, pn, eps, lv, uv, 1, st)) return rc;
   const long bld = (long)B * L * D;
-  hipLaunchKernelGGL(qk_prep_kernel, dim3(blocks_for(bld)), dim3(256), 0, st, lq, lk, uk, B, L, H, dh, scale,
+  hipLaunchKernelGGL(qk_prep_kernel, dim3(blocks_for(bld)), dim3(256), 0, st, lq, uq, lk, uk, B, L, H, dh, scale,
                      w + lay.coef_qk, w + lay.lqs);
-  hipLaunchKernelGGL(qk_const_kernel, dim3(blocks_for((long)B * H * L * L)), dim3(256), 0, st, lq, lk, uk, B, L, H, dh,
-                     scale, w + lay.cst_qk);
+  hipLaunchKernelGGL(qk_const_kernel, dim3(blocks_for((long)B * H * L * L)), dim3(256), 0, st, lq, uq, lk, uk, B, L, H,
+                     dh, scale, w + lay.cst_qk);
   TV_HIP(hipGetLastError());
 
   const long lcd = (long)L * C * D, lcl = (long)L * C * L, lcx = (long)L * C * ld;   // lcx: per-sentence stride of q/k/v

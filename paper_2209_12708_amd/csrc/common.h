@@ -60,8 +60,9 @@ int gemm(const GemmArgs &g, hipStream_t st);
 
 // ---- elementwise / reduction kernels (rowops.hip) ------------------------------------------
 // ld: floats between consecutive coefficient rows of the input state (n when densely packed)
+// mode 0: outputs are (l, u); mode 1: outputs are (mid, half) = ((u+l)/2, (u-l)/2), each accurate in fp32
 int concretize(CState x, int rows, int P, int E, int n, int ld, int rps, int p_norm, const float *eps, float *l,
-               float *u, hipStream_t st);
+               float *u, int mode, hipStream_t st);
 int activation(int act, CState x, int rows, int P, int E, int n, int rps, int p_norm, const float *eps,
                State y, int32_t *status, hipStream_t st);
 int layernorm(CState x, int rows, int P, int E, int n, int rps, int p_norm, const float *eps,

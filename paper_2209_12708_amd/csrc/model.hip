@@ -288,7 +288,7 @@ int head(const tv_model *m, const Plan &pl, float *w, int Bc, int L, int P, int 
   g.sC[0] = (long)Bc * C * NP; g.sC[1] = (long)C * NP;
   g.sBias[0] = (long)Bc * NP; g.sBias[1] = NP;
   if (int rc = gemm(g, st)) return rc;
-  return concretize(CState{Y, Y + (long)Bc * C * NP}, Bc, P, D, NP, NP, 1, pn, eps, w + pl.hl, w + pl.hu, st);
+  return concretize(CState{Y, Y + (long)Bc * C * NP}, Bc, P, D, NP, NP, 1, pn, eps, w + pl.hl, w + pl.hu, 0, st);
 }
 
 int check_call(const tv_model *m, const int32_t *tokens, int B, int L, const int32_t *positions, int P, int pn,
@@ -506,7 +506,7 @@ int tv_certify(const tv_model *m, const int32_t *tokens, int B, int L, const int
 // ---- single operators --------------------------------------------------------------------------
 int tv_op_concretize(const float *S, const float *R, int rows, int P, int E, int n, int rps, int pn, const float *eps,
                      float *l, float *u, void *stream) {
-  return concretize(CState{S, R}, rows, P, E, n, n, rps, pn, eps, l, u, static_cast<hipStream_t>(stream));
+  return concretize(CState{S, R}, rows, P, E, n, n, rps, pn, eps, l, u, 0, static_cast<hipStream_t>(stream));
 }
 
 int tv_op_abs(const float *in, float *out, size_t count, void *stream) {

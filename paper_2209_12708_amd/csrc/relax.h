@@ -3,141 +3,146 @@
 // with intercepts.  ReLU: two lower-bound designs selected by the range (Sec. 2.1), slope 1 when
 // l >= 0 (Sec. 4.1).  tanh: tangent / chord lines between the concretized bounds (Sec. 4.1).
 // The remaining functions (exp, reciprocal, sqrt, square) are needed by softmax, LayerNorm and GELU.
+//
+// Precision.  This is per-neuron work (1/C of the traffic), done in double: the radius plane of an
+// output state is driven by differences such as (k_U - k_L)/2 and (u - l)/2, which are far below the
+// fp32 resolution of k or of l, u themselves when an interval is narrow.  Intervals therefore enter
+// as (mid, half), both accurate in fp32, and the lines leave as centre/radius map coefficients that
+// are rounded to fp32 only at the end; the per-coefficient streaming arithmetic stays in fp32.
 #pragma once
 #include <hip/hip_runtime.h>
 
 namespace tv {
 
-struct Line2 { float kL, cL, kU, cU; };
+struct Line2 { double kL, cL, kU, cU; };
 
-constexpr float kTau = 1e-6f;          // relative width under which an interval counts as a point
-constexpr float kExpCap = 0.99f;       // exp lower tangent at min(mid, l + 0.99): stays positive on [l, u]
-constexpr float kRecipMin = 1e-12f;    // domain guard of the reciprocal
+constexpr double kTau = 1e-12;         // relative width under which an interval counts as a point
+constexpr double kExpCap = 0.99;       // exp lower tangent at min(mid, l + 0.99): stays positive on [l, u]
+constexpr double kRecipMin = 1e-12;    // domain guard of the reciprocal
 
-__device__ __forceinline__ bool is_point(float l, float u) {
-  return (u - l) <= kTau * fmaxf(1.f, fmaxf(fabsf(l), fabsf(u)));
+__device__ __forceinline__ bool is_point(double l, double u) {
+  return (u - l) <= kTau * fmax(1.0, fmax(fabs(l), fabs(u)));
 }
 
 // slope f'(m) for both lines, intercepts min / max of f(x) - k x over {l, m, u}
-__device__ __forceinline__ Line2 point_rule(float k, float fl, float fm, float fu, float l, float m, float u) {
-  const float a = fl - k * l, b = fm - k * m, c = fu - k * u;
+__device__ __forceinline__ Line2 point_rule(double k, double fl, double fm, double fu, double l, double m, double u) {
+  const double a = fl - k * l, b = fm - k * m, c = fu - k * u;
   Line2 r;
   r.kL = r.kU = k;
-  r.cL = fminf(a, fminf(b, c));
-  r.cU = fmaxf(a, fmaxf(b, c));
+  r.cL = fmin(a, fmin(b, c));
+  r.cU = fmax(a, fmax(b, c));
   return r;
 }
 
-__device__ __forceinline__ Line2 relax_relu(float l, float u) {
+__device__ __forceinline__ Line2 relax_relu(double l, double u) {
   Line2 r;
-  if (l >= 0.f) { r.kL = r.kU = 1.f; r.cL = r.cU = 0.f; }
-  else if (u <= 0.f) { r.kL = r.kU = 0.f; r.cL = r.cU = 0.f; }
+  if (l >= 0.0) { r.kL = r.kU = 1.0; r.cL = r.cU = 0.0; }
+  else if (u <= 0.0) { r.kL = r.kU = 0.0; r.cL = r.cU = 0.0; }
   else {
-    const float inv = 1.f / (u - l);
+    const double inv = 1.0 / (u - l);
     r.kU = u * inv; r.cU = -l * u * inv;
-    r.kL = (u >= -l) ? 1.f : 0.f; r.cL = 0.f;
+    r.kL = (u >= -l) ? 1.0 : 0.0; r.cL = 0.0;
   }
   return r;
 }
 
-__device__ __forceinline__ float dtanh(float x) { const float t = tanhf(x); return 1.f - t * t; }
-
 // tangent point d in [lo, hi] whose tangent passes through (end, tanh end); returns the bracket end on
 // the sound side (lower end for the lower line, upper end for the upper line)
-__device__ __forceinline__ float tanh_tangent_through(float end, float lo, float hi, bool sound_lo) {
-  const float te = tanhf(end);
-  auto g = [&](float d) { const float t = tanhf(d); return t + (1.f - t * t) * (end - d) - te; };
-  const bool neg_lo = g(lo) < 0.f;
-  for (int it = 0; it < 32; ++it) {
-    const float mid = 0.5f * (lo + hi);
-    if ((g(mid) < 0.f) == neg_lo) lo = mid; else hi = mid;
+__device__ __forceinline__ double tanh_tangent_through(double end, double lo, double hi, bool sound_lo) {
+  const double te = tanh(end);
+  auto g = [&](double d) { const double t = tanh(d); return t + (1.0 - t * t) * (end - d) - te; };
+  const bool neg_lo = g(lo) < 0.0;
+  for (int it = 0; it < 48; ++it) {
+    const double mid = 0.5 * (lo + hi);
+    if ((g(mid) < 0.0) == neg_lo) lo = mid; else hi = mid;
   }
   return sound_lo ? lo : hi;
 }
 
-__device__ __forceinline__ Line2 relax_tanh(float l, float u) {
-  const float m = 0.5f * (l + u);
-  const float tl = tanhf(l), tu = tanhf(u), tm = tanhf(m);
-  if (is_point(l, u)) return point_rule(1.f - tm * tm, tl, tm, tu, l, m, u);
-  const float kap = (tu - tl) / (u - l);
-  const float chord_c = tl - kap * l;
+__device__ __forceinline__ Line2 relax_tanh(double l, double u) {
+  const double m = 0.5 * (l + u);
+  const double tl = tanh(l), tu = tanh(u), tm = tanh(m);
+  if (is_point(l, u)) return point_rule(1.0 - tm * tm, tl, tm, tu, l, m, u);
+  const double kap = (tu - tl) / (u - l);
+  const double chord_c = tl - kap * l;
   Line2 r;
-  if (l >= 0.f) {
-    r.kL = kap; r.cL = chord_c; r.kU = 1.f - tm * tm; r.cU = tm - r.kU * m;
-  } else if (u <= 0.f) {
-    r.kU = kap; r.cU = chord_c; r.kL = 1.f - tm * tm; r.cL = tm - r.kL * m;
+  if (l >= 0.0) {
+    r.kL = kap; r.cL = chord_c; r.kU = 1.0 - tm * tm; r.cU = tm - r.kU * m;
+  } else if (u <= 0.0) {
+    r.kU = kap; r.cU = chord_c; r.kL = 1.0 - tm * tm; r.cL = tm - r.kL * m;
   } else {
-    if (kap <= 1.f - tl * tl) { r.kL = kap; r.cL = chord_c; }
+    if (kap <= 1.0 - tl * tl) { r.kL = kap; r.cL = chord_c; }
     else {
-      const float d = tanh_tangent_through(u, l, 0.f, true);
-      const float td = tanhf(d);
-      r.kL = 1.f - td * td; r.cL = td - r.kL * d;
+      const double d = tanh_tangent_through(u, l, 0.0, true);
+      const double td = tanh(d);
+      r.kL = 1.0 - td * td; r.cL = td - r.kL * d;
     }
-    if (kap <= 1.f - tu * tu) { r.kU = kap; r.cU = chord_c; }
+    if (kap <= 1.0 - tu * tu) { r.kU = kap; r.cU = chord_c; }
     else {
-      const float d = tanh_tangent_through(l, 0.f, u, false);
-      const float td = tanhf(d);
-      r.kU = 1.f - td * td; r.cU = td - r.kU * d;
+      const double d = tanh_tangent_through(l, 0.0, u, false);
+      const double td = tanh(d);
+      r.kU = 1.0 - td * td; r.cU = td - r.kU * d;
     }
   }
   return r;
 }
 
-__device__ __forceinline__ Line2 relax_exp(float l, float u) {
-  const float m = 0.5f * (l + u);
-  const float el = expf(l), eu = expf(u);
-  if (is_point(l, u)) { const float em = expf(m); return point_rule(em, el, em, eu, l, m, u); }
+__device__ __forceinline__ Line2 relax_exp(double l, double u) {
+  const double m = 0.5 * (l + u);
+  const double el = exp(l), eu = exp(u);
+  if (is_point(l, u)) { const double em = exp(m); return point_rule(em, el, em, eu, l, m, u); }
   Line2 r;
   r.kU = (eu - el) / (u - l); r.cU = el - r.kU * l;
-  const float d = fminf(m, l + kExpCap);
-  r.kL = expf(d); r.cL = r.kL * (1.f - d);
+  const double d = fmin(m, l + kExpCap);
+  r.kL = exp(d); r.cL = r.kL * (1.0 - d);
   return r;
 }
 
-__device__ __forceinline__ Line2 relax_recip(float l, float u) {   // requires l > 0
-  const float m = 0.5f * (l + u);
-  if (is_point(l, u)) return point_rule(-1.f / (m * m), 1.f / l, 1.f / m, 1.f / u, l, m, u);
+__device__ __forceinline__ Line2 relax_recip(double l, double u) {   // requires l > 0
+  const double m = 0.5 * (l + u);
+  if (is_point(l, u)) return point_rule(-1.0 / (m * m), 1.0 / l, 1.0 / m, 1.0 / u, l, m, u);
   Line2 r;
-  r.kL = -1.f / (m * m); r.cL = 2.f / m;
-  r.kU = -1.f / (l * u); r.cU = 1.f / l + 1.f / u;
+  r.kL = -1.0 / (m * m); r.cL = 2.0 / m;
+  r.kU = -1.0 / (l * u); r.cU = 1.0 / l + 1.0 / u;
   return r;
 }
 
-__device__ __forceinline__ Line2 relax_sqrt(float l, float u) {    // requires l > 0
-  const float m = 0.5f * (l + u);
-  const float sl = sqrtf(l), su = sqrtf(u), sm = sqrtf(m);
-  if (is_point(l, u)) return point_rule(0.5f / sm, sl, sm, su, l, m, u);
+__device__ __forceinline__ Line2 relax_sqrt(double l, double u) {    // requires l > 0
+  const double m = 0.5 * (l + u);
+  const double sl = sqrt(l), su = sqrt(u), sm = sqrt(m);
+  if (is_point(l, u)) return point_rule(0.5 / sm, sl, sm, su, l, m, u);
   Line2 r;
-  r.kU = 0.5f / sm; r.cU = 0.5f * sm;
-  r.kL = 1.f / (sl + su); r.cL = sl * su / (sl + su);
+  r.kU = 0.5 / sm; r.cU = 0.5 * sm;
+  r.kL = 1.0 / (sl + su); r.cL = sl * su / (sl + su);
   return r;
 }
 
-__device__ __forceinline__ Line2 relax_square(float l, float u) {
-  const float m = 0.5f * (l + u);
-  if (is_point(l, u)) return point_rule(2.f * m, l * l, m * m, u * u, l, m, u);
+__device__ __forceinline__ Line2 relax_square(double l, double u) {
+  const double m = 0.5 * (l + u);
+  if (is_point(l, u)) return point_rule(2.0 * m, l * l, m * m, u * u, l, m, u);
   Line2 r;
-  r.kL = 2.f * m; r.cL = -m * m;
+  r.kL = 2.0 * m; r.cL = -m * m;
   r.kU = l + u; r.cU = -l * u;
   return r;
 }
 
 // ---- linear forms relative to a base neuron x with bound lines (x_L, x_U):
 //   lower = pL * x_L + qL * x_U + cL   (pL >= 0 >= qL),   upper = pU * x_U + qU * x_L + cU   (pU >= 0 >= qU)
-struct Form { float pL, qL, cL, pU, qU, cU; };
+struct Form { double pL, qL, cL, pU, qU, cU; };
 
-__device__ __forceinline__ Form form_identity() { return Form{1.f, 0.f, 0.f, 1.f, 0.f, 0.f}; }
+__device__ __forceinline__ Form form_identity() { return Form{1.0, 0.0, 0.0, 1.0, 0.0, 0.0}; }
 
 // z with k_L y + c_L <= z <= k_U y + c_U: each line takes y's own side for a non-negative slope, the
 // other side for a negative one (sign rule of Eq. (2) applied to a per-neuron scalar)
-__device__ __forceinline__ Form form_sub(const Form &y, float kL, float cL, float kU, float cU) {
+__device__ __forceinline__ Form form_sub(const Form &y, double kL, double cL, double kU, double cU) {
   Form z;
-  if (kL >= 0.f) { z.pL = kL * y.pL; z.qL = kL * y.qL; z.cL = kL * y.cL + cL; }
+  if (kL >= 0.0) { z.pL = kL * y.pL; z.qL = kL * y.qL; z.cL = kL * y.cL + cL; }
   else           { z.pL = kL * y.qU; z.qL = kL * y.pU; z.cL = kL * y.cU + cL; }
-  if (kU >= 0.f) { z.pU = kU * y.pU; z.qU = kU * y.qU; z.cU = kU * y.cU + cU; }
+  if (kU >= 0.0) { z.pU = kU * y.pU; z.qU = kU * y.qU; z.cU = kU * y.cU + cU; }
   else           { z.pU = kU * y.qL; z.qU = kU * y.pL; z.cU = kU * y.cL + cU; }
   return z;
 }
+__device__ __forceinline__ Form form_sub(const Form &y, const Line2 &ln) { return form_sub(y, ln.kL, ln.cL, ln.kU, ln.cU); }
 
 __device__ __forceinline__ Form form_add(const Form &a, const Form &b) {
   return Form{a.pL + b.pL, a.qL + b.qL, a.cL + b.cL, a.pU + b.pU, a.qU + b.qU, a.cU + b.cU};
@@ -145,9 +150,9 @@ __device__ __forceinline__ Form form_add(const Form &a, const Form &b) {
 
 // z = x * y (both relative to the same base), McCormick planes
 //   z >= ly x + lx y - lx ly ,   z <= uy x + lx y - lx uy
-__device__ __forceinline__ Form form_mul(const Form &x, const Form &y, float lx, float ly, float uy) {
-  const Form ax = form_sub(x, ly, 0.f, uy, 0.f);
-  const Form by = form_sub(y, lx, 0.f, lx, 0.f);
+__device__ __forceinline__ Form form_mul(const Form &x, const Form &y, double lx, double ly, double uy) {
+  const Form ax = form_sub(x, ly, 0.0, uy, 0.0);
+  const Form by = form_sub(y, lx, 0.0, lx, 0.0);
   Form z = form_add(ax, by);
   z.cL -= lx * ly;
   z.cU -= lx * uy;
@@ -156,22 +161,35 @@ __device__ __forceinline__ Form form_mul(const Form &x, const Form &y, float lx,
 
 // concretized bounds of z = relaxation of y on [ly, uy] (single-input chain: the norm of z's
 // coefficients is |k| times the norm of one side of y)
-__device__ __forceinline__ void line_range(float kL, float cL, float kU, float cU, float ly, float uy, float &lz,
-                                           float &uz) {
-  lz = (kL >= 0.f ? kL * ly : kL * uy) + cL;
-  uz = (kU >= 0.f ? kU * uy : kU * ly) + cU;
+__device__ __forceinline__ void line_range(const Line2 &ln, double ly, double uy, double &lz, double &uz) {
+  lz = (ln.kL >= 0.0 ? ln.kL * ly : ln.kL * uy) + ln.cL;
+  uz = (ln.kU >= 0.0 ? ln.kU * uy : ln.kU * ly) + ln.cU;
 }
 
-// centre/radius map of a form:  S_y = sS*S + sR*R + sC [bias row],  R_y = rS*S + rR*R + rC [bias row]
+// centre/radius map of a form:  S_y = sS*S + sR*R + sC [bias row],  R_y = rS*S + rR*R + rC [bias row].
+// The differences are taken in double and rounded once.
 struct Map2 { float sS, sR, sC, rS, rR, rC; };
 __device__ __forceinline__ Map2 form_map(const Form &f) {
   Map2 m;
-  m.sS = 0.5f * (f.pL + f.qL + f.pU + f.qU);
-  m.sR = 0.5f * (-f.pL + f.qL + f.pU - f.qU);
-  m.sC = 0.5f * (f.cL + f.cU);
-  m.rS = 0.5f * (f.pU + f.qU - f.pL - f.qL);
-  m.rR = 0.5f * (f.pU - f.qU + f.pL - f.qL);
-  m.rC = 0.5f * (f.cU - f.cL);
+  m.sS = (float)(0.5 * (f.pL + f.qL + f.pU + f.qU));
+  m.sR = (float)(0.5 * (-f.pL + f.qL + f.pU - f.qU));
+  m.sC = (float)(0.5 * (f.cL + f.cU));
+  m.rS = (float)(0.5 * (f.pU + f.qU - f.pL - f.qL));
+  m.rR = (float)(0.5 * (f.pU - f.qU + f.pL - f.qL));
+  m.rC = (float)(0.5 * (f.cU - f.cL));
+  return m;
+}
+
+// product z = x * y with x a state (S_x, R_x) and y a state (S_y, R_y), in centre/radius form:
+//   S_z = a1 S_x + a2 R_x + b S_y - b a1 [bias],   R_z = a3 S_x + a4 R_x + |b| R_y - b a3 [bias]
+// with the multiplier range [ly, uy] of y and b = lx.
+struct Mul2 { float a1, a2, a3, a4; };
+__device__ __forceinline__ Mul2 mul_coeffs(double ly, double uy) {
+  Mul2 m;
+  m.a1 = (float)(0.5 * (ly + uy));
+  m.a2 = (float)(0.5 * (fabs(uy) - fabs(ly)));
+  m.a3 = (float)(0.5 * (uy - ly));
+  m.a4 = (float)(0.5 * (fabs(uy) + fabs(ly)));
   return m;
 }
 

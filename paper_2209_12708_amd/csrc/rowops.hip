@@ -98,15 +98,16 @@ __device__ __forceinline__ float4 *row_ptr(float *base, long row, int C, int r, 
 #define CF4(v, c) (reinterpret_cast<const float *>(&(v))[c])
 
 // ------------------------------------------------------------------------------------------------
-// Norms of two linear forms of the state down the coefficient axis, for this thread's columns:
-//   NL = N(pL * lo + qL * up),  NU = N(pU * up + qU * lo),   lo = S - R, up = S + R,
-// N = sum over the P blocks of the dual norm.  forms == nullptr means the state itself (pL = pU = 1).
-// Also returns the bias-row values of lo / up mapped the same way (without the forms' constants).
+// Norms of a lower and an upper line of the state down the coefficient axis, for this thread's columns:
+//   NL = N(aS * S + aR * R),  NU = N(bS * S + bR * R),    N = sum over the P blocks of the dual norm.
+// lines == nullptr means the state's own lines (S - R, S + R).  Also returns the bias-row S and R.
+struct LineCoef { float aS, aR, bS, bR; };
+
 template <int VEC>
 __device__ __forceinline__ void column_norms(const float *S, const float *R, long row, int P, int E, int n, int c0,
-                                             const Geo &ge, int pn, const Form *forms, float *red,
-                                             float (&NL)[4 * VEC], float (&NU)[4 * VEC], float (&bL)[4 * VEC],
-                                             float (&bU)[4 * VEC]) {
+                                             const Geo &ge, int pn, const LineCoef *lines, float *red,
+                                             float (&NL)[4 * VEC], float (&NU)[4 * VEC], float (&bS)[4 * VEC],
+                                             float (&bR)[4 * VEC]) {
   const int C = P * E + 1;
 #pragma unroll
   for (int i = 0; i < 4 * VEC; ++i) NL[i] = NU[i] = 0.f;
@@ -125,12 +126,11 @@ __device__ __forceinline__ void column_norms(const float *S, const float *R, lon
           const float4 s = ps[f], rr = pr[f];
 #pragma unroll
           for (int c = 0; c < 4; ++c) {
-            const float lo = CF4(s, c) - CF4(rr, c), up = CF4(s, c) + CF4(rr, c);
-            float a = lo, b = up;
-            if (forms) {
-              const Form &fm = forms[4 * v + c];
-              a = fm.pL * lo + fm.qL * up;
-              b = fm.pU * up + fm.qU * lo;
+            float a = CF4(s, c) - CF4(rr, c), b = CF4(s, c) + CF4(rr, c);
+            if (lines) {
+              const LineCoef &lc = lines[4 * v + c];
+              a = lc.aS * CF4(s, c) + lc.aR * CF4(rr, c);
+              b = lc.bS * CF4(s, c) + lc.bR * CF4(rr, c);
             }
             acc[8 * v + c] = norm_acc(acc[8 * v + c], a, pn);
             acc[8 * v + 4 + c] = norm_acc(acc[8 * v + 4 + c], b, pn);
@@ -154,18 +154,18 @@ __device__ __forceinline__ void column_norms(const float *S, const float *R, lon
     float4 s = make_float4(0, 0, 0, 0), rr = s;
     if (f < ge.n4) { s = ps[f]; rr = pr[f]; }
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      const float lo = CF4(s, c) - CF4(rr, c), up = CF4(s, c) + CF4(rr, c);
-      float a = lo, b = up;
-      if (forms) {
-        const Form &fm = forms[4 * v + c];
-        a = fm.pL * lo + fm.qL * up;
-        b = fm.pU * up + fm.qU * lo;
-      }
-      bL[4 * v + c] = a; bU[4 * v + c] = b;
-    }
+    for (int c = 0; c < 4; ++c) { bS[4 * v + c] = CF4(s, c); bR[4 * v + c] = CF4(rr, c); }
   }
 }
+
+// Concretized range as (mid, half) in double from centre / radius biases and the two norms:
+//   l = (bS - bR) - e NL,  u = (bS + bR) + e NU   =>   mid = bS + e (NU - NL)/2,  half = bR + e (NU + NL)/2.
+// Both are sums of quantities that fp32 holds accurately, so narrow intervals keep their width.
+__device__ __forceinline__ void range_of(double bS, double bR, double e, double NL, double NU, double &l, double &u) {
+  const double mid = bS + 0.5 * e * (NU - NL), half = bR + 0.5 * e * (NU + NL);
+  l = mid - half; u = mid + half;
+}
+__device__ __forceinline__ bool finite_d(double x) { return fabs(x) <= 3.4028234663852886e38; }
 
 // Write y = map(x) for every row of the block (bias constants on the last row).
 template <int VEC>
@@ -197,31 +197,37 @@ __device__ __forceinline__ void apply_maps(const float *S, const float *R, float
 }
 
 // ------------------------------------------------------------------------------------------------
-// Eq. (1).  grid = (rows, column chunks).
+// Eq. (1).  grid = (rows, column chunks).  mode 0 writes (l, u); mode 1 writes (mid, half).
 template <int VEC>
 __global__ __launch_bounds__(kThreads) void concretize_kernel(const float *S, const float *R, int P, int E, int n,
                                                               int ld, int G, int rps, int pn, const float *eps,
-                                                              float *l, float *u) {
+                                                              float *o0, float *o1, int mode) {
   __shared__ float red[4 * kWave * 8 * VEC];
   const long row = blockIdx.x;
   const int chunk = 4 * G * VEC, c0 = blockIdx.y * chunk;
   const Geo ge(G, min(chunk, n - c0) / 4);
-  float NL[4 * VEC], NU[4 * VEC], bL[4 * VEC], bU[4 * VEC];
-  column_norms<VEC>(S, R, row, P, E, ld, c0, ge, pn, nullptr, red, NL, NU, bL, bU);
+  float NL[4 * VEC], NU[4 * VEC], bS[4 * VEC], bR[4 * VEC];
+  column_norms<VEC>(S, R, row, P, E, ld, c0, ge, pn, nullptr, red, NL, NU, bS, bR);
   if (ge.slot == 0) {
     const float e = eps[row / rps];
 #pragma unroll
     for (int v = 0; v < VEC; ++v) {
       const int f = ge.g + ge.G * v;
       if (f < ge.n4) {
-        float4 lo, up;
+        float4 a, b;
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-          F4(lo, c) = bL[4 * v + c] - e * NL[4 * v + c];
-          F4(up, c) = bU[4 * v + c] + e * NU[4 * v + c];
+          const int i = 4 * v + c;
+          if (mode == 0) {
+            F4(a, c) = (bS[i] - bR[i]) - e * NL[i];
+            F4(b, c) = (bS[i] + bR[i]) + e * NU[i];
+          } else {
+            F4(a, c) = bS[i] + 0.5f * e * (NU[i] - NL[i]);
+            F4(b, c) = bR[i] + 0.5f * e * (NU[i] + NL[i]);
+          }
         }
-        reinterpret_cast<float4 *>(l + row * n + c0)[f] = lo;
-        reinterpret_cast<float4 *>(u + row * n + c0)[f] = up;
+        reinterpret_cast<float4 *>(o0 + row * n + c0)[f] = a;
+        reinterpret_cast<float4 *>(o1 + row * n + c0)[f] = b;
       }
     }
   }
@@ -230,13 +236,13 @@ __global__ __launch_bounds__(kThreads) void concretize_kernel(const float *S, co
 // ------------------------------------------------------------------------------------------------
 // Activation: concretize, relax, substitute - one workgroup reads its coefficients for the norm and
 // again (from cache) for the rescale.  GELU adds one mapped-norm pass for the inner product.
-__device__ __forceinline__ Form gelu_inner(float lx, float ux, float &lb, float &ub) {
+__device__ __forceinline__ Form gelu_inner(double lx, double ux, double &lb, double &ub) {
   // a = x^2 ; b = k (1 + c3 a) ; returns the form of b and its range
-  const float k = 0.7978845608028654f, c3 = 0.044715f;
+  const double k = 0.7978845608028654, c3 = 0.044715;
   const Line2 sq = relax_square(lx, ux);
-  Form a = form_sub(form_identity(), sq.kL, sq.cL, sq.kU, sq.cU);
-  float la, ua;
-  line_range(sq.kL, sq.cL, sq.kU, sq.cU, lx, ux, la, ua);
+  const Form a = form_sub(form_identity(), sq);
+  double la, ua;
+  line_range(sq, lx, ux, la, ua);
   lb = k * c3 * la + k; ub = k * c3 * ua + k;
   return form_sub(a, k * c3, k, k * c3, k);
 }
@@ -250,40 +256,51 @@ __global__ __launch_bounds__(kThreads) void activation_kernel(const float *S, co
   const int C = P * E + 1;
   const int chunk = 4 * G * VEC, c0 = blockIdx.y * chunk;
   const Geo ge(G, min(chunk, n - c0) / 4);
-  const float e = eps[row / rps];
-  float NL[4 * VEC], NU[4 * VEC], bL[4 * VEC], bU[4 * VEC];
-  column_norms<VEC>(S, R, row, P, E, n, c0, ge, pn, nullptr, red, NL, NU, bL, bU);
+  const double e = eps[row / rps];
+  float NL[4 * VEC], NU[4 * VEC], bS[4 * VEC], bR[4 * VEC];
+  column_norms<VEC>(S, R, row, P, E, n, c0, ge, pn, nullptr, red, NL, NU, bS, bR);
   Map2 maps[4 * VEC];
   bool bad = false;
   if (ACT != TV_ACT_GELU) {
 #pragma unroll
     for (int i = 0; i < 4 * VEC; ++i) {
-      const float l = bL[i] - e * NL[i], u = bU[i] + e * NU[i];
-      bad |= !(finite_f(l) && finite_f(u));
+      double l, u;
+      range_of(bS[i], bR[i], e, NL[i], NU[i], l, u);
+      bad |= !(finite_d(l) && finite_d(u));
       const Line2 ln = ACT == TV_ACT_RELU ? relax_relu(l, u) : relax_tanh(l, u);
-      maps[i] = form_map(form_sub(form_identity(), ln.kL, ln.cL, ln.kU, ln.cU));
+      maps[i] = form_map(form_sub(form_identity(), ln));
     }
   } else {
     Form fg[4 * VEC];
-    float lx[4 * VEC], ux[4 * VEC];
+    LineCoef lc[4 * VEC];
+    double lx[4 * VEC], ux[4 * VEC];
+    float xS[4 * VEC], xR[4 * VEC];
 #pragma unroll
     for (int i = 0; i < 4 * VEC; ++i) {
-      lx[i] = bL[i] - e * NL[i]; ux[i] = bU[i] + e * NU[i];
-      bad |= !(finite_f(lx[i]) && finite_f(ux[i]));
-      float lb, ub;
+      range_of(bS[i], bR[i], e, NL[i], NU[i], lx[i], ux[i]);
+      bad |= !(finite_d(lx[i]) && finite_d(ux[i]));
+      double lb, ub;
       const Form b = gelu_inner(lx[i], ux[i], lb, ub);
       fg[i] = form_mul(form_identity(), b, lx[i], lb, ub);     // g = x * b
+      lc[i] = LineCoef{(float)(fg[i].pL + fg[i].qL), (float)(fg[i].qL - fg[i].pL), (float)(fg[i].pU + fg[i].qU),
+                       (float)(fg[i].pU - fg[i].qU)};
+      xS[i] = bS[i]; xR[i] = bR[i];
     }
-    column_norms<VEC>(S, R, row, P, E, n, c0, ge, pn, fg, red, NL, NU, bL, bU);
+    column_norms<VEC>(S, R, row, P, E, n, c0, ge, pn, lc, red, NL, NU, bS, bR);
 #pragma unroll
     for (int i = 0; i < 4 * VEC; ++i) {
-      const float lg = bL[i] + fg[i].cL - e * NL[i], ug = bU[i] + fg[i].cU + e * NU[i];
-      bad |= !(finite_f(lg) && finite_f(ug));
+      // bias values of g's two lines, as centre / radius in double
+      const Form &f = fg[i];
+      const double gS = 0.5 * ((f.pL + f.qL + f.pU + f.qU) * xS[i] + (-f.pL + f.qL + f.pU - f.qU) * xR[i] + f.cL + f.cU);
+      const double gR = 0.5 * ((f.pU + f.qU - f.pL - f.qL) * xS[i] + (f.pU - f.qU + f.pL - f.qL) * xR[i] + f.cU - f.cL);
+      double lg, ug;
+      range_of(gS, gR, e, NL[i], NU[i], lg, ug);
+      bad |= !(finite_d(lg) && finite_d(ug));
       const Line2 th = relax_tanh(lg, ug);
-      float lt, ut;
-      line_range(th.kL, th.cL, th.kU, th.cU, lg, ug, lt, ut);
-      Form h = form_sub(form_sub(fg[i], th.kL, th.cL, th.kU, th.cU), 0.5f, 0.5f, 0.5f, 0.5f);
-      maps[i] = form_map(form_mul(form_identity(), h, lx[i], 0.5f * lt + 0.5f, 0.5f * ut + 0.5f));
+      double lt, ut;
+      line_range(th, lg, ug, lt, ut);
+      const Form h = form_sub(form_sub(f, th), 0.5, 0.5, 0.5, 0.5);
+      maps[i] = form_map(form_mul(form_identity(), h, lx[i], 0.5 * lt + 0.5, 0.5 * ut + 0.5));
     }
   }
   if (bad) status[row / rps] = 1;
@@ -294,7 +311,8 @@ __global__ __launch_bounds__(kThreads) void activation_kernel(const float *S, co
 // LayerNorm bound.  One workgroup per token; lanes cover all n columns (VEC float4 per lane).
 //   c = x - mean(x)                 one affine map (I - 11^T/n): S_c = S - mean S, R_c = (1-2/n) R + mean R
 //   q = c^2 (relaxed) ; v = mean q + ln_eps ; s = sqrt v ; rho = 1/s ; y = c * rho ; out = gamma y + beta
-// Three sweeps over the block: norms of c; norm of v; output.
+// Three sweeps over the block: norms of c; norm of v; output.  All streaming arithmetic is on centre
+// and radius planes (never on lower / upper values, whose difference fp32 cannot hold).
 template <int VEC>
 struct LnRow {
   float sc[4 * VEC], rc[4 * VEC];   // centred centre / radius planes of one coefficient row
@@ -329,13 +347,14 @@ __device__ __forceinline__ void ln_load_row(const float *S, const float *R, long
 template <int VEC>
 __global__ __launch_bounds__(kThreads) void layernorm_kernel(const float *S, const float *R, int P, int E, int n,
                                                              int G, int rps, int pn, const float *eps,
-                                                             const float *gamma, const float *beta, float ln_eps,
+                                                             const float *gamma, const float *beta, float ln_eps_f,
                                                              float *So, float *Ro, int32_t *status) {
   __shared__ float red[4 * kWave * 8 * VEC];
   const long row = blockIdx.x;
   const int C = P * E + 1;
   const Geo ge(G, n / 4);
-  const float e = eps[row / rps];
+  const double e = eps[row / rps];
+  const double ln_eps = ln_eps_f;
   const float inv = 1.f / (float)n;
   bool colon[VEC];
 #pragma unroll
@@ -343,7 +362,8 @@ __global__ __launch_bounds__(kThreads) void layernorm_kernel(const float *S, con
   bool bad = false;
 
   // ---- sweep 1: concretize c
-  float lc[4 * VEC], uc[4 * VEC];
+  float lc[4 * VEC];         // lower end of c's range (the McCormick multiplier on rho)
+  Map2 mq[4 * VEC];          // centre / radius map of the square relaxation, relative to c
   {
     float NL[4 * VEC], NU[4 * VEC];
 #pragma unroll
@@ -372,38 +392,32 @@ __global__ __launch_bounds__(kThreads) void layernorm_kernel(const float *S, con
     ln_load_row<VEC>(S, R, row, C, C - 1, n, ge, x);
 #pragma unroll
     for (int i = 0; i < 4 * VEC; ++i) {
-      lc[i] = (x.sc[i] - x.rc[i]) - e * NL[i];
-      uc[i] = (x.sc[i] + x.rc[i]) + e * NU[i];
-      if (colon[i / 4]) bad |= !(finite_f(lc[i]) && finite_f(uc[i]));
+      double l, u;
+      range_of(x.sc[i], x.rc[i], e, NL[i], NU[i], l, u);
+      if (colon[i / 4]) bad |= !(finite_d(l) && finite_d(u));
+      lc[i] = (float)l;
+      mq[i] = form_map(form_sub(form_identity(), relax_square(l, u)));
+      if (!colon[i / 4]) mq[i] = Map2{0, 0, 0, 0, 0, 0};
     }
   }
-  // square relaxation per column: q_L = kL c_(L|U) + cL etc.  (forms relative to c)
-  Form fq[4 * VEC];
-#pragma unroll
-  for (int i = 0; i < 4 * VEC; ++i) {
-    const Line2 sq = relax_square(lc[i], uc[i]);
-    fq[i] = form_sub(form_identity(), sq.kL, sq.cL, sq.kU, sq.cU);
-    if (!colon[i / 4]) fq[i] = Form{0, 0, 0, 0, 0, 0};
-  }
-  // v_L[r] = mean_d (pL c_L + qL c_U)[r, d],  v_U[r] = mean_d (pU c_U + qU c_L)[r, d]
-  auto v_row = [&](const LnRow<VEC> &x, float &vl, float &vu) {
+  // v = mean_d q + ln_eps, as centre / radius per coefficient row
+  auto v_row = [&](const LnRow<VEC> &x, float &vS, float &vR) {
     float a = 0.f, b = 0.f;
 #pragma unroll
     for (int i = 0; i < 4 * VEC; ++i) {
-      const float lo = x.sc[i] - x.rc[i], up = x.sc[i] + x.rc[i];
-      a += fq[i].pL * lo + fq[i].qL * up;
-      b += fq[i].pU * up + fq[i].qU * lo;
+      a += mq[i].sS * x.sc[i] + mq[i].sR * x.rc[i];
+      b += mq[i].rS * x.sc[i] + mq[i].rR * x.rc[i];
     }
-    vl = row_sum(a, ge.G) * inv;
-    vu = row_sum(b, ge.G) * inv;
+    vS = row_sum(a, ge.G) * inv;
+    vR = row_sum(b, ge.G) * inv;
   };
-  float cql = 0.f, cqu = 0.f;   // mean of the square relaxation's intercepts
+  float cvS = 0.f, cvR = 0.f;   // constants of v on the bias row
 #pragma unroll
-  for (int i = 0; i < 4 * VEC; ++i) { cql += fq[i].cL; cqu += fq[i].cU; }
-  cql = row_sum(cql, ge.G) * inv; cqu = row_sum(cqu, ge.G) * inv;
+  for (int i = 0; i < 4 * VEC; ++i) { cvS += mq[i].sC; cvR += mq[i].rC; }
+  cvS = row_sum(cvS, ge.G) * inv + ln_eps_f; cvR = row_sum(cvR, ge.G) * inv;
 
   // ---- sweep 2: concretize v (one neuron per token: each slot accumulates whole rows)
-  float lv, uv;
+  double lv, uv;
   {
     float NLv = 0.f, NUv = 0.f;
     for (int pb = 0; pb < P; ++pb) {
@@ -411,10 +425,10 @@ __global__ __launch_bounds__(kThreads) void layernorm_kernel(const float *S, con
       for (int r = pb * E + ge.slot; r < (pb + 1) * E; r += ge.NS) {
         LnRow<VEC> x;
         ln_load_row<VEC>(S, R, row, C, r, n, ge, x);
-        float vl, vu;
-        v_row(x, vl, vu);
-        acc[0] = norm_acc(acc[0], vl, pn);
-        acc[1] = norm_acc(acc[1], vu, pn);
+        float vS, vR;
+        v_row(x, vS, vR);
+        acc[0] = norm_acc(acc[0], vS - vR, pn);
+        acc[1] = norm_acc(acc[1], vS + vR, pn);
       }
       slot_reduce<2>(acc, ge, pn == 1, red);
       NLv += norm_fin(acc[0], pn);
@@ -422,36 +436,25 @@ __global__ __launch_bounds__(kThreads) void layernorm_kernel(const float *S, con
     }
     LnRow<VEC> x;
     ln_load_row<VEC>(S, R, row, C, C - 1, n, ge, x);
-    float vl, vu;
-    v_row(x, vl, vu);
-    lv = vl + cql + ln_eps - e * NLv;
-    uv = vu + cqu + ln_eps + e * NUv;
-    bad |= !(finite_f(lv) && finite_f(uv));
+    float vS, vR;
+    v_row(x, vS, vR);
+    range_of((double)vS + cvS, (double)vR + cvR, e, NLv, NUv, lv, uv);
+    bad |= !(finite_d(lv) && finite_d(uv));
   }
-  // sqrt and reciprocal on the scalar v: rho_L = a_L v_U + g_L, rho_U = a_U v_L + g_U
-  const float lvc = fmaxf(lv, ln_eps), uvc = fmaxf(uv, lvc);
+  // sqrt and reciprocal on the scalar v (double): ranges from the states, clamped where the true value allows
+  const double lvc = fmax(lv, ln_eps), uvc = fmax(uv, lvc);
   const Line2 sq = relax_sqrt(lvc, uvc);
-  float ls, us;
-  line_range(sq.kL, sq.cL, sq.kU, sq.cU, lv, uv, ls, us);       // range of the sqrt state (unclamped v state)
-  ls = fmaxf(ls, sqrtf(ln_eps)); us = fmaxf(us, ls);
+  double ls0, us0;
+  line_range(sq, lv, uv, ls0, us0);                 // range of the sqrt state (from the unclamped v state)
+  const double ls = fmax(ls0, sqrt(ln_eps)), us = fmax(us0, ls);
   const Line2 rc = relax_recip(ls, us);
-  float lr, ur;
-  line_range(rc.kL, rc.cL, rc.kU, rc.cU, ls, us, lr, ur);
-  // (the reciprocal's range uses the clamped sqrt range; its slopes are negative, so it reads the
-  //  opposite side of the sqrt state)
-  {
-    // range of rho from the *state* of s: s_L = kLs v_L + cLs (range [ls_state, us_state]); the state
-    // range before clamping is what the norm of rho's coefficients scales with
-    float ls0, us0;
-    line_range(sq.kL, sq.cL, sq.kU, sq.cU, lv, uv, ls0, us0);
-    lr = rc.kL * us0 + rc.cL;
-    ur = rc.kU * ls0 + rc.cU;
-  }
-  const float aL = rc.kL * sq.kU, gL = rc.kL * (sq.cU + sq.kU * (cqu + ln_eps)) + rc.cL;   // on v_U (without intercepts)
-  const float aU = rc.kU * sq.kL, gU = rc.kU * (sq.cL + sq.kL * (cql + ln_eps)) + rc.cU;   // on v_L
+  double lr, ur;
+  line_range(rc, ls0, us0, lr, ur);                 // range of rho's state
+  const Map2 mr = form_map(form_sub(form_sub(form_identity(), sq), rc));   // rho relative to v
+  const Mul2 mc = mul_coeffs(lr, ur);
   if (bad) status[row / rps] = 1;
 
-  // ---- sweep 3: y = c * rho (McCormick, x = c_d, y = rho), then gamma / beta
+  // ---- sweep 3: y = c * rho (x = c_d with multiplier range of rho; y = rho with multiplier lc_d), gamma / beta
   float gm[4 * VEC], bt[4 * VEC];
 #pragma unroll
   for (int v = 0; v < VEC; ++v) {
@@ -464,11 +467,12 @@ __global__ __launch_bounds__(kThreads) void layernorm_kernel(const float *S, con
   for (int r = ge.slot; r < C; r += ge.NS) {
     LnRow<VEC> x;
     ln_load_row<VEC>(S, R, row, C, r, n, ge, x);
-    float vl, vu;
-    v_row(x, vl, vu);
+    float vS, vR;
+    v_row(x, vS, vR);
     const bool last = r == C - 1;
-    float rhoL = aL * vu, rhoU = aU * vl;          // rho's lower / upper linear forms at coefficient row r
-    if (last) { rhoL += gL; rhoU += gU; }
+    if (last) { vS += cvS; vR += cvR; }
+    float rhoS = mr.sS * vS + mr.sR * vR, rhoR = mr.rS * vS + mr.rR * vR;
+    if (last) { rhoS += mr.sC; rhoR += mr.rC; }
     float4 *qs = row_ptr(So, row, C, r, n, 0), *qr = row_ptr(Ro, row, C, r, n, 0);
 #pragma unroll
     for (int v = 0; v < VEC; ++v) {
@@ -477,16 +481,13 @@ __global__ __launch_bounds__(kThreads) void layernorm_kernel(const float *S, con
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
         const int i = 4 * v + c;
-        const float lo = x.sc[i] - x.rc[i], up = x.sc[i] + x.rc[i];
-        // lower: lr * c + lc * rho - lc lr ; upper: ur * c + lc * rho - lc ur  (sign rule per slope)
-        float yl = (lr >= 0.f ? lr * lo : lr * up) + (lc[i] >= 0.f ? lc[i] * rhoL : lc[i] * rhoU);
-        float yu = (ur >= 0.f ? ur * up : ur * lo) + (lc[i] >= 0.f ? lc[i] * rhoU : lc[i] * rhoL);
-        if (last) { yl -= lc[i] * lr; yu -= lc[i] * ur; }
-        float ol = gm[i] >= 0.f ? gm[i] * yl : gm[i] * yu;
-        float ou = gm[i] >= 0.f ? gm[i] * yu : gm[i] * yl;
-        if (last) { ol += bt[i]; ou += bt[i]; }
-        F4(os, c) = 0.5f * (ou + ol);
-        F4(orr, c) = 0.5f * (ou - ol);
+        float yS = mc.a1 * x.sc[i] + mc.a2 * x.rc[i] + lc[i] * rhoS;
+        float yR = mc.a3 * x.sc[i] + mc.a4 * x.rc[i] + fabsf(lc[i]) * rhoR;
+        if (last) { yS -= lc[i] * mc.a1; yR -= lc[i] * mc.a3; }
+        float oS = gm[i] * yS, oR = fabsf(gm[i]) * yR;
+        if (last) oS += bt[i];
+        F4(os, c) = oS;
+        F4(orr, c) = oR;
       }
       if (f < ge.n4) { qs[f] = os; qr[f] = orr; }
     }
@@ -496,7 +497,7 @@ __global__ __launch_bounds__(kThreads) void layernorm_kernel(const float *S, con
 // ------------------------------------------------------------------------------------------------
 // Softmax bound over the last axis of the score state, in place.  One workgroup per attention row.
 //   shift by max_j u_j ; e = exp (relaxed) ; sigma = sum_j e ; rho = 1 / sigma ; p = e * rho.
-// Sweeps: norms of s; norm of sigma; output p (and the norm of p for its concretized bounds).
+// Sweeps: norms of s; norm of sigma; output p (and the norm of p's lower line for its concretized bound).
 template <int VEC>
 __global__ __launch_bounds__(kThreads) void softmax_kernel(float *S, float *R, int P, int E, int n, int G, int rps,
                                                            int pn, const float *eps, float *lp_out,
@@ -505,38 +506,41 @@ __global__ __launch_bounds__(kThreads) void softmax_kernel(float *S, float *R, i
   const long row = blockIdx.x;
   const int C = P * E + 1;
   const Geo ge(G, n / 4);
-  const float e = eps[row / rps];
+  const double e = eps[row / rps];
   bool colon[VEC];
 #pragma unroll
   for (int v = 0; v < VEC; ++v) colon[v] = ge.g + ge.G * v < ge.n4;
   bool bad = false;
 
-  float NL[4 * VEC], NU[4 * VEC], bL[4 * VEC], bU[4 * VEC];
-  column_norms<VEC>(S, R, row, P, E, n, 0, ge, pn, nullptr, red, NL, NU, bL, bU);
-  float ls[4 * VEC], us[4 * VEC];
+  float NL[4 * VEC], NU[4 * VEC], bS[4 * VEC], bR[4 * VEC];
+  column_norms<VEC>(S, R, row, P, E, n, 0, ge, pn, nullptr, red, NL, NU, bS, bR);
+  double ls[4 * VEC], us[4 * VEC];
   float mx = -FLT_MAX;
 #pragma unroll
   for (int i = 0; i < 4 * VEC; ++i) {
-    ls[i] = bL[i] - e * NL[i]; us[i] = bU[i] + e * NU[i];
-    if (colon[i / 4]) { bad |= !(finite_f(ls[i]) && finite_f(us[i])); mx = fmaxf(mx, us[i]); }
+    range_of(bS[i], bR[i], e, NL[i], NU[i], ls[i], us[i]);
+    if (colon[i / 4]) { bad |= !(finite_d(ls[i]) && finite_d(us[i])); mx = fmaxf(mx, (float)us[i]); }
   }
-  const float shift = cols_max(mx, ge.G);
-  // exp relaxation per column on the shifted range; slopes are positive
-  float kLe[4 * VEC], kUe[4 * VEC], cLe[4 * VEC], cUe[4 * VEC], le[4 * VEC];
-  float sumcl = 0.f, sumcu = 0.f;
+  const double shift = cols_max(mx, ge.G);
+  // exp relaxation per column on the shifted range (slopes positive); the shift moves s's bias, which
+  // is folded into the constants of the map
+  Map2 me[4 * VEC];
+  float le[4 * VEC];
 #pragma unroll
   for (int i = 0; i < 4 * VEC; ++i) {
     const Line2 ex = relax_exp(ls[i] - shift, us[i] - shift);
-    const bool on = colon[i / 4];
-    kLe[i] = on ? ex.kL : 0.f; kUe[i] = on ? ex.kU : 0.f;
-    // the shift moves the bias of s: fold -shift * k into the intercepts
-    cLe[i] = on ? ex.cL - ex.kL * shift : 0.f; cUe[i] = on ? ex.cU - ex.kU * shift : 0.f;
-    le[i] = on ? ex.kL * (ls[i] - shift) + ex.cL : 0.f;
-    sumcl += cLe[i]; sumcu += cUe[i];
+    Line2 sh = ex;
+    sh.cL = ex.cL - ex.kL * shift; sh.cU = ex.cU - ex.kU * shift;
+    me[i] = form_map(form_sub(form_identity(), sh));
+    le[i] = (float)(ex.kL * (ls[i] - shift) + ex.cL);
+    if (!colon[i / 4]) { me[i] = Map2{0, 0, 0, 0, 0, 0}; le[i] = 0.f; }
   }
-  sumcl = row_sum(sumcl, ge.G); sumcu = row_sum(sumcu, ge.G);
+  float csS = 0.f, csR = 0.f;   // constants of sigma on the bias row
+#pragma unroll
+  for (int i = 0; i < 4 * VEC; ++i) { csS += me[i].sC; csR += me[i].rC; }
+  csS = row_sum(csS, ge.G); csR = row_sum(csR, ge.G);
 
-  auto load_row = [&](int r, float (&lo)[4 * VEC], float (&up)[4 * VEC]) {
+  auto load_row = [&](int r, float (&xs)[4 * VEC], float (&xr)[4 * VEC]) {
     const float4 *ps = row_ptr((const float *)S, row, C, r, n, 0), *pr = row_ptr((const float *)R, row, C, r, n, 0);
 #pragma unroll
     for (int v = 0; v < VEC; ++v) {
@@ -544,64 +548,70 @@ __global__ __launch_bounds__(kThreads) void softmax_kernel(float *S, float *R, i
       float4 s = make_float4(0, 0, 0, 0), rr = s;
       if (f < ge.n4) { s = ps[f]; rr = pr[f]; }
 #pragma unroll
-      for (int c = 0; c < 4; ++c) { lo[4 * v + c] = CF4(s, c) - CF4(rr, c); up[4 * v + c] = CF4(s, c) + CF4(rr, c); }
+      for (int c = 0; c < 4; ++c) { xs[4 * v + c] = CF4(s, c); xr[4 * v + c] = CF4(rr, c); }
     }
   };
-  auto sigma_row = [&](const float (&lo)[4 * VEC], const float (&up)[4 * VEC], float &sl, float &su) {
+  // e's planes for one coefficient row (without bias constants) and sigma's planes
+  auto e_row = [&](const float (&xs)[4 * VEC], const float (&xr)[4 * VEC], float (&eS)[4 * VEC], float (&eR)[4 * VEC],
+                   float &sgS, float &sgR) {
     float a = 0.f, b = 0.f;
 #pragma unroll
-    for (int i = 0; i < 4 * VEC; ++i) { a += kLe[i] * lo[i]; b += kUe[i] * up[i]; }
-    sl = row_sum(a, ge.G); su = row_sum(b, ge.G);
+    for (int i = 0; i < 4 * VEC; ++i) {
+      eS[i] = me[i].sS * xs[i] + me[i].sR * xr[i];
+      eR[i] = me[i].rS * xs[i] + me[i].rR * xr[i];
+      a += eS[i]; b += eR[i];
+    }
+    sgS = row_sum(a, ge.G); sgR = row_sum(b, ge.G);
   };
 
   // ---- sweep 2: concretize sigma
-  float lsg, usg;
+  double lsg, usg;
   {
     float NLs = 0.f, NUs = 0.f;
-    float lo[4 * VEC], up[4 * VEC];
+    float xs[4 * VEC], xr[4 * VEC], eS[4 * VEC], eR[4 * VEC];
     for (int pb = 0; pb < P; ++pb) {
       float acc[2] = {0.f, 0.f};
       for (int r = pb * E + ge.slot; r < (pb + 1) * E; r += ge.NS) {
-        load_row(r, lo, up);
-        float sl, su;
-        sigma_row(lo, up, sl, su);
-        acc[0] = norm_acc(acc[0], sl, pn);
-        acc[1] = norm_acc(acc[1], su, pn);
+        load_row(r, xs, xr);
+        float sgS, sgR;
+        e_row(xs, xr, eS, eR, sgS, sgR);
+        acc[0] = norm_acc(acc[0], sgS - sgR, pn);
+        acc[1] = norm_acc(acc[1], sgS + sgR, pn);
       }
       slot_reduce<2>(acc, ge, pn == 1, red);
       NLs += norm_fin(acc[0], pn); NUs += norm_fin(acc[1], pn);
     }
-    load_row(C - 1, lo, up);
-    float sl, su;
-    sigma_row(lo, up, sl, su);
-    lsg = sl + sumcl - e * NLs;
-    usg = su + sumcu + e * NUs;
+    load_row(C - 1, xs, xr);
+    float sgS, sgR;
+    e_row(xs, xr, eS, eR, sgS, sgR);
+    range_of((double)sgS + csS, (double)sgR + csR, e, NLs, NUs, lsg, usg);
   }
-  bad |= !(finite_f(lsg) && finite_f(usg)) || !(lsg >= kRecipMin);
+  bad |= !(finite_d(lsg) && finite_d(usg)) || !(lsg >= kRecipMin);
   const Line2 rc = relax_recip(lsg, usg);
-  float lr, ur;
-  line_range(rc.kL, rc.cL, rc.kU, rc.cU, lsg, usg, lr, ur);
-  // rho_L[r] = kLr * sigma_U[r] (+ kLr * sumcu + cLr on the bias row); rho_U[r] = kUr * sigma_L[r] (+ ...)
-  const float gL = rc.kL * sumcu + rc.cL, gU = rc.kU * sumcl + rc.cU;
+  double lr, ur;
+  line_range(rc, lsg, usg, lr, ur);
+  const Map2 mr = form_map(form_sub(form_identity(), rc));      // rho relative to sigma
+  const Mul2 mc = mul_coeffs(lr, ur);
   if (bad) status[row / rps] = 1;
 
-  // ---- sweep 3: p = e * rho (x = e_j, y = rho): lower lr e + le rho - le lr ; upper ur e + le rho - le ur
-  float NLp[4 * VEC], NUp[4 * VEC], pbl[4 * VEC], pbu[4 * VEC];
+  // ---- sweep 3: p = e * rho (x = e_j with multiplier range of rho; y = rho with multiplier le_j)
+  float NLp[4 * VEC], pbl[4 * VEC];
 #pragma unroll
-  for (int i = 0; i < 4 * VEC; ++i) NLp[i] = NUp[i] = pbl[i] = pbu[i] = 0.f;
+  for (int i = 0; i < 4 * VEC; ++i) NLp[i] = pbl[i] = 0.f;
   for (int pb = 0; pb <= P; ++pb) {          // block P is the bias row
-    float acc[8 * VEC];
+    float acc[4 * VEC];
 #pragma unroll
-    for (int i = 0; i < 8 * VEC; ++i) acc[i] = 0.f;
+    for (int i = 0; i < 4 * VEC; ++i) acc[i] = 0.f;
     const int rbeg = pb < P ? pb * E : C - 1, rend = pb < P ? (pb + 1) * E : C;
     for (int r = rbeg + ge.slot; r < rend; r += ge.NS) {
-      float lo[4 * VEC], up[4 * VEC];
-      load_row(r, lo, up);
-      float sl, su;
-      sigma_row(lo, up, sl, su);
+      float xs[4 * VEC], xr[4 * VEC], eS[4 * VEC], eR[4 * VEC];
+      load_row(r, xs, xr);
+      float sgS, sgR;
+      e_row(xs, xr, eS, eR, sgS, sgR);
       const bool last = r == C - 1;
-      float rhoL = rc.kL * su, rhoU = rc.kU * sl;
-      if (last) { rhoL += gL; rhoU += gU; }
+      if (last) { sgS += csS; sgR += csR; }
+      float rhoS = mr.sS * sgS + mr.sR * sgR, rhoR = mr.rS * sgS + mr.rR * sgR;
+      if (last) { rhoS += mr.sC; rhoR += mr.rC; }
       float4 *qs = row_ptr(S, row, C, r, n, 0), *qr = row_ptr(R, row, C, r, n, 0);
 #pragma unroll
       for (int v = 0; v < VEC; ++v) {
@@ -610,30 +620,27 @@ __global__ __launch_bounds__(kThreads) void softmax_kernel(float *S, float *R, i
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
           const int i = 4 * v + c;
-          float eL = kLe[i] * lo[i], eU = kUe[i] * up[i];
-          if (last) { eL += cLe[i]; eU += cUe[i]; }
-          float pl = (lr >= 0.f ? lr * eL : lr * eU) + (le[i] >= 0.f ? le[i] * rhoL : le[i] * rhoU);
-          float pu = (ur >= 0.f ? ur * eU : ur * eL) + (le[i] >= 0.f ? le[i] * rhoU : le[i] * rhoL);
-          if (last) { pl -= le[i] * lr; pu -= le[i] * ur; pbl[i] = pl; pbu[i] = pu; }
-          else { acc[2 * i] = norm_acc(acc[2 * i], pl, pn); acc[2 * i + 1] = norm_acc(acc[2 * i + 1], pu, pn); }
-          F4(os, c) = 0.5f * (pu + pl);
-          F4(orr, c) = 0.5f * (pu - pl);
+          float es = eS[i], er = eR[i];
+          if (last) { es += me[i].sC; er += me[i].rC; }
+          float pS = mc.a1 * es + mc.a2 * er + le[i] * rhoS;
+          float pR = mc.a3 * es + mc.a4 * er + fabsf(le[i]) * rhoR;
+          if (last) { pS -= le[i] * mc.a1; pR -= le[i] * mc.a3; pbl[i] = pS - pR; }
+          else acc[i] = norm_acc(acc[i], pS - pR, pn);
+          F4(os, c) = pS;
+          F4(orr, c) = pR;
         }
         if (f < ge.n4) { qs[f] = os; qr[f] = orr; }
       }
     }
     if (pb < P) {
-      slot_reduce<8 * VEC>(acc, ge, pn == 1, red);
+      slot_reduce<4 * VEC>(acc, ge, pn == 1, red);
 #pragma unroll
-      for (int i = 0; i < 4 * VEC; ++i) { NLp[i] += norm_fin(acc[2 * i], pn); NUp[i] += norm_fin(acc[2 * i + 1], pn); }
+      for (int i = 0; i < 4 * VEC; ++i) NLp[i] += norm_fin(acc[i], pn);
     }
   }
   // concretized lower bound of p, clamped to [0, 1]; the bias row was handled by slot 0
   {
-    float bb[8 * VEC];
-#pragma unroll
-    for (int i = 0; i < 4 * VEC; ++i) { bb[2 * i] = pbl[i]; bb[2 * i + 1] = pbu[i]; }
-    slot_reduce<8 * VEC>(bb, ge, false, red);      // only one slot holds non-zero values
+    slot_reduce<4 * VEC>(pbl, ge, false, red);      // only one slot holds non-zero values
     if (ge.slot == 0) {
 #pragma unroll
       for (int v = 0; v < VEC; ++v) {
@@ -642,7 +649,7 @@ __global__ __launch_bounds__(kThreads) void softmax_kernel(float *S, float *R, i
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
           const int i = 4 * v + c;
-          const float l = bb[2 * i] - e * NLp[i];
+          const float l = pbl[i] - (float)e * NLp[i];
           F4(o, c) = fminf(fmaxf(l, 0.f), 1.f);
         }
         if (f < ge.n4) reinterpret_cast<float4 *>(lp_out + row * n)[f] = o;
@@ -689,14 +696,14 @@ int check_common(const void *S, const void *R, int rows, int P, int E, int n, in
 }  // namespace
 
 int concretize(CState x, int rows, int P, int E, int n, int ld, int rps, int pn, const float *eps, float *l,
-               float *u, hipStream_t st) {
+               float *u, int mode, hipStream_t st) {
   if (int rc = check_common(x.S, x.R, rows, P, E, n, rps, pn, eps)) return rc;
   TV_REQUIRE(l && u, TV_E_NULL, "null output");
   TV_REQUIRE(ld >= n && ld % 4 == 0, TV_E_SHAPE, "concretize: row stride %d must be a multiple of 4 and >= %d", ld, n);
   int G, nch;
   chunk_geo(n, G, nch);
   hipLaunchKernelGGL((concretize_kernel<1>), dim3(rows, nch), dim3(kThreads), 0, st, x.S, x.R, P, E, n, ld, G, rps,
-                     pn, eps, l, u);
+                     pn, eps, l, u, mode);
   TV_HIP(hipGetLastError());
   return TV_OK;
 }

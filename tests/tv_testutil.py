@@ -59,14 +59,23 @@ def assert_close(got, ref, what, rtol=1e-4, atol_scale=1e-6):
 
 
 def assert_state_close(planes, X, what, rtol=1e-4, atol_scale=2e-6):
-    """Compare GPU planes with an oracle state on the lower / upper lines (weights and biases)."""
-    lw, lb, uw, ub = from_planes(*planes)
+    """Compare GPU planes with an oracle state in the representation the library stores: centre and
+    radius planes, coefficient rows and bias row separately (they live on different scales).  The
+    absolute allowance is atol_scale times the largest |centre| or |radius| entry of that part, i.e.
+    fp32 rounding of the terms a lower / upper line is the sum or difference of."""
+    Sg, Rg = (np.asarray(a, np.float64) for a in planes)
     shp = X.lb.shape
-    rows = int(np.prod(shp[:-1]))
-    n = shp[-1]
-    scale_ref = np.concatenate([X.lw.reshape(rows, n, -1), X.uw.reshape(rows, n, -1)], -1)
-    assert_close(lw, X.lw.reshape(rows, n, -1), what + ".lw", rtol, atol_scale * max(1.0, 0))
-    assert_close(uw, X.uw.reshape(rows, n, -1), what + ".uw", rtol, atol_scale)
-    assert_close(lb, X.lb.reshape(rows, n), what + ".lb", rtol, atol_scale)
-    assert_close(ub, X.ub.reshape(rows, n), what + ".ub", rtol, atol_scale)
-    del scale_ref
+    rows = int(np.prod(shp[:-1])); n = shp[-1]
+    lw = X.lw.reshape(rows, n, -1).transpose(0, 2, 1); uw = X.uw.reshape(rows, n, -1).transpose(0, 2, 1)
+    lb = X.lb.reshape(rows, 1, n); ub = X.ub.reshape(rows, 1, n)
+    for nm, g_s, g_r, lo, up in (("weights", Sg[:, :-1], Rg[:, :-1], lw, uw), ("bias", Sg[:, -1:], Rg[:, -1:], lb, ub)):
+        s_ref, r_ref = 0.5 * (up + lo), 0.5 * (up - lo)
+        scale = max(np.abs(s_ref).max(initial=0.0), np.abs(r_ref).max(initial=0.0))
+        for pn, g, o in (("centre", g_s, s_ref), ("radius", g_r, r_ref)):
+            err = np.abs(g - o)
+            tol = rtol * np.abs(o) + atol_scale * scale
+            bad = err > tol
+            if bad.any():
+                k = np.unravel_index(np.argmax(err - tol), err.shape)
+                raise AssertionError(f"{what} {nm} {pn}: {bad.sum()} of {bad.size} off; worst at {k}: got {g[k]!r} "
+                                     f"ref {o[k]!r} (scale {scale:.3e})")
