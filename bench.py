@@ -1,0 +1,142 @@
+#!/usr/bin/env python3
+"""Benchmark: sentences certified per second on the 2-layer configuration (c2), one MI355X.
+
+A step is one pass of the whole hot path over one synthetic batch: tv_certify (10 bisection probes,
+each a full bound-propagation sweep) on 32 sentences of 32 tokens, once for each of the l_1, l_2 and
+l_inf balls = 96 sentence certifications.  Model weights, tokens and the workspace are resident in HBM
+before the timed region.  Prints ONE JSON line with the throughput, the roofline position of the
+dominant kernel class (HIP-event timed inside the library during the timed steps) and the float64
+CPU oracle timed on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0       # MI355X HBM3E
+MFMA_FP32_PEAK_TF = 157.3   # MI355X dense fp32 matrix
+MFMA_KINDS = ("affine_gemm", "qk_gemm_x", "qk_gemm_y", "pv_gemm_x", "pv_gemm_y", "head_gemm")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="c2")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-timing", action="store_true",
+                    help="leave the per-launch HIP events out of the timed region")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (every box has one); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2209_12708_amd import binding as tv
+    from tv_synth import CONFIGS, make_model, make_positions, make_tokens
+
+    w = CONFIGS[args.workload]
+    weights = make_model(w)
+    tokens, positions = make_tokens(w), make_positions(w)
+    dev = torch.device("cuda:0")
+    model = tv.Model(weights, dev)
+    tok_d, pos_d = torch.as_tensor(tokens, device=dev), torch.as_tensor(positions, device=dev)
+    ws = model.workspace(w.batch, w.seq_len, w.n_perturbed)
+    full, _ = model.workspace_query(w.batch, w.seq_len, w.n_perturbed)
+
+    def step():
+        out = None
+        for p in w.p_norms:
+            out = model.certify(tok_d, pos_d, p, w.eps_lo, w.eps_hi, w.steps, workspace=ws)
+        return out
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    if not args.no_kernel_timing:
+        tv.profile_reset()
+        tv.profile_enable(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        last = step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    tv.profile_enable(False)
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    n_cert = w.batch * len(w.p_norms)
+    value = n_cert / (ms_per_step * 1e-3)
+
+    roofline = None
+    kernels = {}
+    if not args.no_kernel_timing:
+        prof = tv.profile_read()
+        total_ms = sum(v["ms"] for v in prof.values())
+        for name, v in sorted(prof.items(), key=lambda kv: -kv[1]["ms"]):
+            avg_us = v["ms"] * 1e3 / v["launches"]
+            kernels[name] = {"share": round(v["ms"] / total_ms, 4), "launches_per_step": v["launches"] // args.steps,
+                             "avg_us": round(avg_us, 2),
+                             "GBps": round(v["bytes"] / (v["ms"] * 1e-3) / 1e9, 1) if v["ms"] else 0.0,
+                             "TFLOPs": round(v["flops"] / (v["ms"] * 1e-3) / 1e12, 2) if v["ms"] else 0.0}
+        dom = max(prof, key=lambda k: prof[k]["ms"])
+        d = prof[dom]
+        # at this size every class, the contractions included, sits under the HBM roof (K = N = 128:
+        # 32 flop/byte against a ridge of 20); the class is reported against the roof that bounds it
+        ai = d["flops"] / max(d["bytes"], 1.0)
+        if dom in MFMA_KINDS and ai > MFMA_FP32_PEAK_TF * 1e12 / (HBM_PEAK_GBS * 1e9):
+            ach = d["flops"] / (d["ms"] * 1e-3) / 1e12
+            roofline = {"kernel": dom, "bound": "mfma", "achieved": round(ach, 2), "peak": MFMA_FP32_PEAK_TF,
+                        "unit": "TFLOP/s", "frac": round(ach / MFMA_FP32_PEAK_TF, 4), "traffic": None}
+        else:
+            ach = d["bytes"] / (d["ms"] * 1e-3) / 1e9
+            roofline = {"kernel": dom, "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS,
+                        "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None}
+        roofline["avg_launch_us"] = round(d["ms"] * 1e3 / d["launches"], 2)
+        roofline["algorithmic_bytes_per_launch"] = d["bytes"] / d["launches"]
+        roofline["algorithmic_flops_per_launch"] = d["flops"] / d["launches"]
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import verifier as V
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([i.get("num_threads", 1) for i in threadpool_info()] or [os.cpu_count()])
+        except Exception:
+            cores = os.cpu_count()
+        p = w.p_norms[min(1, len(w.p_norms) - 1)]
+        c0 = time.perf_counter()
+        n_done = 0
+        while n_done < 2 and time.perf_counter() - c0 < 20.0:
+            e_ref, _ = V.certify(weights, tokens[n_done], positions[n_done], p, w.eps_lo, w.eps_hi, w.steps)
+            n_done += 1
+        c1 = time.perf_counter()
+        gpu_eps = float(last["eps"][n_done - 1]) if p == w.p_norms[-1] else None
+        cpu = {"value": round(n_done / (c1 - c0), 4), "unit": "sentences certified/s", "cores": int(cores),
+               "kind": "oracle",
+               "sample": f"{n_done} sentence(s) of {args.workload}, p={p}, {w.steps} bisection probes each, float64 numpy"}
+        del gpu_eps
+
+    line = {
+        "metric": "sentences certified/sec (eps binary search)", "value": round(value, 2),
+        "unit": "sentences certified/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {w.enc.n_layers}-layer encoder, hidden {w.enc.hidden}, "
+                               f"{w.enc.n_heads} heads, FFN {w.enc.ffn}, seq {w.seq_len}, {w.n_perturbed} perturbed "
+                               f"position(s), balls p={list(w.p_norms)} (0 = inf), batch {w.batch}, "
+                               f"{w.steps} bisection probes on [{w.eps_lo}, {w.eps_hi}]",
+                   "certifications_per_step": n_cert, "workspace_bytes": int(ws.numel()),
+                   "batch_resident": bool(ws.numel() >= full), "kernel_timing_in_timed_region": not args.no_kernel_timing},
+        "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -164,6 +164,18 @@ int tv_op_attention(const float *Sq, const float *Rq, const float *Sk, const flo
 /* stop_after: 0 = full block; 1 = stop after the q k^T bound (Ss/Rs hold the score state);
  * 2 = stop after the softmax bound (Ss/Rs hold p). */
 
+/* ---- per-kernel-class timing (for benchmarks).  While enabled, every kernel launch of the library is
+ * bracketed by two HIP events on its own stream.  tv_profile_get waits for the recorded events and
+ * returns, for class `kind` in [0, tv_profile_kinds()): its name, summed duration in ms, number of
+ * bracketed launches, and the algorithmic flops and bytes those launches stand for (Eq. (2)
+ * contractions: 2 M N K per plane; memory-bound passes: one read and one write of the state).
+ * Not thread-safe; do not enable while capturing a HIP graph. */
+int tv_profile_enable(int on);
+int tv_profile_reset(void);
+int tv_profile_kinds(void);
+int tv_profile_get(int kind, char *name, int name_len, double *total_ms, long long *launches, double *flops,
+                   double *bytes);
+
 #ifdef __cplusplus
 }
 #endif

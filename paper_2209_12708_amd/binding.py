@@ -43,7 +43,8 @@ _lib = None
 
 EXPORTS = ("tv_version", "tv_last_error", "tv_model_create", "tv_model_destroy", "tv_workspace_query", "tv_verify",
            "tv_certify", "tv_op_concretize", "tv_op_abs", "tv_op_affine", "tv_op_activation", "tv_op_layernorm",
-           "tv_attention_workspace", "tv_op_attention")
+           "tv_attention_workspace", "tv_op_attention", "tv_profile_enable", "tv_profile_reset",
+           "tv_profile_kinds", "tv_profile_get")
 
 
 def lib():
@@ -71,6 +72,9 @@ def lib():
         L.tv_op_activation.argtypes = [i, vp, vp, i, i, i, i, i, i, vp, vp, vp, vp, vp]
         L.tv_op_layernorm.argtypes = [vp, vp, i, i, i, i, i, i, vp, vp, vp, f, vp, vp, vp, vp]
         L.tv_op_attention.argtypes = [vp] * 6 + [i] * 6 + [vp] * 5 + [i, vp, vp, sz, vp]
+        L.tv_profile_enable.argtypes = [i]
+        L.tv_profile_get.argtypes = [i, C.c_char_p, i, C.POINTER(C.c_double), C.POINTER(C.c_longlong),
+                                     C.POINTER(C.c_double), C.POINTER(C.c_double)]
         _lib = L
     return _lib
 
@@ -249,3 +253,24 @@ def op_attention(q, k, v, B, L, H, P, p_norm, eps, stop_after=0):
                                  P, p_norm, _ptr(eps), _ptr(So), _ptr(Ro), _ptr(Ss), _ptr(Rs), stop_after,
                                  _ptr(status), _ptr(ws), nbytes, _stream()))
     return (So, Ro), (Ss, Rs), status
+
+
+# ---- per-kernel-class timing --------------------------------------------------------------------
+def profile_enable(on=True):
+    _check(lib().tv_profile_enable(1 if on else 0))
+
+
+def profile_reset():
+    _check(lib().tv_profile_reset())
+
+
+def profile_read():
+    """{class name: dict(ms, launches, flops, bytes)} for every class with at least one launch."""
+    out = {}
+    for k in range(lib().tv_profile_kinds()):
+        name = C.create_string_buffer(64)
+        ms, fl, by, n = C.c_double(), C.c_double(), C.c_double(), C.c_longlong()
+        _check(lib().tv_profile_get(k, name, 64, C.byref(ms), C.byref(n), C.byref(fl), C.byref(by)))
+        if n.value:
+            out[name.value.decode()] = {"ms": ms.value, "launches": n.value, "flops": fl.value, "bytes": by.value}
+    return out

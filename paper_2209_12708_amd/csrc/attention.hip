@@ -168,10 +168,13 @@ int attention(CState q, CState k, CState v, int ld, int B, int L, int H, int D, 
   if (int rc = concretize(k, rows, P, D, D, ld, L, pn, eps, lk, uk, 1, st)) return rc;
   if (int rc = concretize(v, rows, P, D, D, ld, L, pn, eps, lv, uv, 1, st)) return rc;
   const long bld = (long)B * L * D;
+  {
+  ProfScope prof(K_PREP, st, 0.0, 0.0);
   hipLaunchKernelGGL(qk_prep_kernel, dim3(blocks_for(bld)), dim3(256), 0, st, lq, uq, lk, uk, B, L, H, dh, scale,
                      w + lay.coef_qk, w + lay.lqs);
   hipLaunchKernelGGL(qk_const_kernel, dim3(blocks_for((long)B * H * L * L)), dim3(256), 0, st, lq, uq, lk, uk, B, L, H,
                      dh, scale, w + lay.cst_qk);
+  }
   TV_HIP(hipGetLastError());
 
   const long lcd = (long)L * C * D, lcl = (long)L * C * L, lcx = (long)L * C * ld;   // lcx: per-sentence stride of q/k/v
@@ -182,7 +185,7 @@ int attention(CState q, CState k, CState v, int ld, int B, int L, int H, int D, 
     g.C = s.S; g.ldc = L;
     g.bias = w + lay.cst_qk; g.bias_ld = L; g.bias_period = C;
     g.M = L * C; g.N = L; g.K = 2 * dh;
-    g.nz0 = 2; g.nz1 = H; g.nz2 = B;
+    g.nz0 = 2; g.nz1 = H; g.nz2 = B; g.kind = K_QK_X;
     g.sA[0] = 0; g.sA[1] = dh; g.sA[2] = lcx;
     g.sA2[0] = 0; g.sA2[1] = dh; g.sA2[2] = lcx;
     g.sB[0] = (long)L * 2 * dh; g.sB[1] = 2L * L * 2 * dh; g.sB[2] = (long)H * 2 * L * 2 * dh;
@@ -196,7 +199,7 @@ int attention(CState q, CState k, CState v, int ld, int B, int L, int H, int D, 
     g.B = k.S; g.ldb = ld; g.b_mode = 0; g.b_q = L; g.b_m1 = C; g.b_m2 = 1;   // n = (r, j) -> row j*C + r
     g.C = s.S; g.Cadd = s.S; g.ldc = (long)C * L;
     g.M = L; g.N = C * L; g.K = dh;
-    g.nz0 = 2; g.nz1 = H; g.nz2 = B;
+    g.nz0 = 2; g.nz1 = H; g.nz2 = B; g.kind = K_QK_Y;
     g.sA[0] = bld; g.sA[1] = dh; g.sA[2] = (long)L * D;
     g.sB[0] = k.R - k.S; g.sB[1] = dh; g.sB[2] = lcx;
     g.sC[0] = s.R - s.S; g.sC[1] = lcl; g.sC[2] = (long)H * lcl;
@@ -209,9 +212,12 @@ int attention(CState q, CState k, CState v, int ld, int B, int L, int H, int D, 
   if (int rc = softmax(s, B * H * L, P, D, L, H * L, pn, eps, lp, status, st)) return rc;
   if (stop_after == 2) return TV_OK;
 
+  {
+  ProfScope prof(K_PREP, st, 0.0, 0.0);
   hipLaunchKernelGGL(pv_prep_kernel, dim3(blocks_for(bld)), dim3(256), 0, st, lv, uv, B, L, H, dh, w + lay.coef_pv);
   hipLaunchKernelGGL(pv_const_kernel, dim3(blocks_for(bld)), dim3(256), 0, st, lp, lv, uv, B, L, H, dh,
                      w + lay.cst_pv);
+  }
   TV_HIP(hipGetLastError());
   {  // o, part 1: [S_p | R_p] x coefficients from v's range
     GemmArgs g;
@@ -220,7 +226,7 @@ int attention(CState q, CState k, CState v, int ld, int B, int L, int H, int D, 
     g.C = o.S; g.ldc = D;
     g.bias = w + lay.cst_pv; g.bias_ld = D; g.bias_period = C;
     g.M = L * C; g.N = dh; g.K = 2 * L;
-    g.nz0 = 2; g.nz1 = H; g.nz2 = B;
+    g.nz0 = 2; g.nz1 = H; g.nz2 = B; g.kind = K_PV_X;
     g.sA[0] = 0; g.sA[1] = lcl; g.sA[2] = (long)H * lcl;
     g.sA2[0] = 0; g.sA2[1] = lcl; g.sA2[2] = (long)H * lcl;
     g.sB[0] = (long)dh * 2 * L; g.sB[1] = 2L * dh * 2 * L; g.sB[2] = (long)H * 2 * dh * 2 * L;
@@ -234,7 +240,7 @@ int attention(CState q, CState k, CState v, int ld, int B, int L, int H, int D, 
     g.B = v.S; g.ldb = (long)C * ld; g.b_mode = 1; g.cq = dh; g.cstride = D; g.b_cstride = ld;   // n = (r, d) -> column r*D + d
     g.C = o.S; g.Cadd = o.S; g.ldc = (long)C * D;
     g.M = L; g.N = C * dh; g.K = L;
-    g.nz0 = 2; g.nz1 = H; g.nz2 = B;
+    g.nz0 = 2; g.nz1 = H; g.nz2 = B; g.kind = K_PV_Y;
     g.sA[0] = 0; g.sA[1] = (long)L * L; g.sA[2] = (long)H * L * L;
     g.sB[0] = v.R - v.S; g.sB[1] = dh; g.sB[2] = lcx;
     g.sC[0] = o.R - o.S; g.sC[1] = dh; g.sC[2] = lcd;

@@ -22,6 +22,15 @@ int fail(int code, const char *fmt, ...);
 
 inline bool norm_ok(int p) { return p == 1 || p == 2 || p == TV_NORM_INF; }
 
+// ---- optional per-kernel-class timing with HIP events on the launch stream (off by default) ------
+enum Kind { K_AFFINE = 0, K_QK_X, K_QK_Y, K_PV_X, K_PV_Y, K_HEAD, K_CONCRETIZE, K_ACTIVATION, K_LAYERNORM, K_SOFTMAX,
+            K_PREP, K_MISC, K_COUNT };
+struct ProfScope {   // brackets the launches issued during its lifetime; flops / bytes are the algorithmic counts
+  ProfScope(int kind, hipStream_t st, double flops, double bytes);
+  ~ProfScope();
+  int kind_; hipStream_t st_; void *rec_;
+};
+
 // A bound state: two planes [rows][C][n].
 struct State {
   float *S, *R;
@@ -53,6 +62,7 @@ struct GemmArgs {
   int bias_period = 0;
   int M = 0, N = 0, K = 0;
   int nz0 = 1, nz1 = 1, nz2 = 1;
+  int kind = K_MISC;              // timing class
   long sA[3] = {0, 0, 0}, sA2[3] = {0, 0, 0}, sB[3] = {0, 0, 0}, sC[3] = {0, 0, 0}, sAdd[3] = {0, 0, 0},
        sBias[3] = {0, 0, 0};
 };

@@ -240,6 +240,9 @@ int gemm(const GemmArgs &g, hipStream_t st) {
   TV_REQUIRE(g.bias == nullptr || g.bias_period > 0, TV_E_ARG, "gemm: bias without period");
   GemmArgs a = g;
   if (!a.A2) a.K1 = a.K;
+  const double nz = (double)g.nz0 * g.nz1 * g.nz2, mn = (double)g.M * g.N;
+  ProfScope prof(g.kind, st, 2.0 * mn * g.K * nz,
+                 4.0 * nz * ((double)g.M * g.K + (double)g.N * g.K + mn * (g.Cadd ? 2.0 : 1.0)));
   // tile shape by problem shape: small M (per-batch contractions over tokens) vs small N (head width)
   if (a.M <= 32) return launch<32, 128, 1, 4>(a, st);
   if (a.M <= 64) return launch<64, 128, 2, 2>(a, st);

@@ -19,6 +19,35 @@ int fail(int code, const char *fmt, ...) {
   return code;
 }
 
+// ---- event timing ------------------------------------------------------------------------------
+struct ProfRec { int kind; hipEvent_t a, b; double flops, bytes; };
+static bool g_prof_on = false;
+static std::vector<ProfRec> g_prof_recs;
+static std::vector<hipEvent_t> g_prof_pool;
+static const char *kKindNames[K_COUNT] = {"affine_gemm", "qk_gemm_x", "qk_gemm_y", "pv_gemm_x", "pv_gemm_y", "head_gemm",
+                                          "concretize", "activation", "layernorm", "softmax", "bilinear_prep", "misc"};
+
+static hipEvent_t prof_event() {
+  if (!g_prof_pool.empty()) { hipEvent_t e = g_prof_pool.back(); g_prof_pool.pop_back(); return e; }
+  hipEvent_t e = nullptr;
+  (void)hipEventCreate(&e);
+  return e;
+}
+
+ProfScope::ProfScope(int kind, hipStream_t st, double flops, double bytes) : kind_(kind), st_(st), rec_(nullptr) {
+  if (!g_prof_on) return;
+  ProfRec *r = new ProfRec{kind, prof_event(), prof_event(), flops, bytes};
+  (void)hipEventRecord(r->a, st);
+  rec_ = r;
+}
+ProfScope::~ProfScope() {
+  if (!rec_) return;
+  ProfRec *r = static_cast<ProfRec *>(rec_);
+  (void)hipEventRecord(r->b, st_);
+  g_prof_recs.push_back(*r);
+  delete r;
+}
+
 namespace {
 
 // ---- small kernels -----------------------------------------------------------------------------
@@ -220,7 +249,7 @@ int affine(const float *xS, long xplane, long M, int C, int K, int N, const floa
   g.bias = bpair; g.bias_ld = 0; g.bias_period = C;
   TV_REQUIRE(M < (1L << 31), TV_E_SHAPE, "affine: %ld rows exceed the kernel's 32-bit row index", M);
   g.M = (int)M; g.N = N; g.K = K;
-  g.nz0 = 2;
+  g.nz0 = 2; g.kind = K_AFFINE;
   g.sA[0] = xplane; g.sB[0] = (long)N * K; g.sC[0] = yplane; g.sAdd[0] = addplane; g.sBias[0] = N;
   return gemm(g, st);
 }
@@ -282,7 +311,7 @@ int head(const tv_model *m, const Plan &pl, float *w, int Bc, int L, int P, int 
   g.C = Y; g.ldc = NP;
   g.bias = bh; g.bias_ld = 0; g.bias_period = C;
   g.M = C; g.N = NP; g.K = D;
-  g.nz0 = 2; g.nz1 = Bc;
+  g.nz0 = 2; g.nz1 = Bc; g.kind = K_HEAD;
   g.sA[0] = pD; g.sA[1] = (long)L * C * D;
   g.sB[0] = (long)Bc * NP * D; g.sB[1] = (long)NP * D;
   g.sC[0] = (long)Bc * C * NP; g.sC[1] = (long)C * NP;
@@ -500,6 +529,38 @@ int tv_certify(const tv_model *m, const int32_t *tokens, int B, int L, const int
     if (out_labels) hipLaunchKernelGGL(copy_i32_kernel, dim3(nblk(Bc)), dim3(256), 0, st, lab, out_labels + b0, Bc);
     TV_HIP(hipGetLastError());
   }
+  return TV_OK;
+}
+
+// ---- timing ------------------------------------------------------------------------------------
+int tv_profile_enable(int on) {
+  g_prof_on = on != 0;
+  return TV_OK;
+}
+
+int tv_profile_reset(void) {
+  for (ProfRec &r : g_prof_recs) { g_prof_pool.push_back(r.a); g_prof_pool.push_back(r.b); }
+  g_prof_recs.clear();
+  return TV_OK;
+}
+
+int tv_profile_kinds(void) { return K_COUNT; }
+
+int tv_profile_get(int kind, char *name, int name_len, double *total_ms, long long *launches, double *flops,
+                   double *bytes) {
+  TV_REQUIRE(kind >= 0 && kind < K_COUNT && name && total_ms && launches && flops && bytes && name_len > 0, TV_E_ARG,
+             "tv_profile_get: bad argument");
+  snprintf(name, (size_t)name_len, "%s", kKindNames[kind]);
+  double ms = 0, fl = 0, by = 0;
+  long long n = 0;
+  for (ProfRec &r : g_prof_recs) {
+    if (r.kind != kind) continue;
+    TV_HIP(hipEventSynchronize(r.b));
+    float t = 0.f;
+    TV_HIP(hipEventElapsedTime(&t, r.a, r.b));
+    ms += t; fl += r.flops; by += r.bytes; ++n;
+  }
+  *total_ms = ms; *launches = n; *flops = fl; *bytes = by;
   return TV_OK;
 }
 

@@ -702,6 +702,8 @@ int concretize(CState x, int rows, int P, int E, int n, int ld, int rps, int pn,
   TV_REQUIRE(ld >= n && ld % 4 == 0, TV_E_SHAPE, "concretize: row stride %d must be a multiple of 4 and >= %d", ld, n);
   int G, nch;
   chunk_geo(n, G, nch);
+  const double C = (double)P * E + 1;
+  ProfScope prof(K_CONCRETIZE, st, 4.0 * rows * C * n, 8.0 * rows * C * n + 8.0 * rows * n);
   hipLaunchKernelGGL((concretize_kernel<1>), dim3(rows, nch), dim3(kThreads), 0, st, x.S, x.R, P, E, n, ld, G, rps,
                      pn, eps, l, u, mode);
   TV_HIP(hipGetLastError());
@@ -715,6 +717,8 @@ int activation(int act, CState x, int rows, int P, int E, int n, int rps, int pn
   TV_REQUIRE(act == TV_ACT_RELU || act == TV_ACT_TANH || act == TV_ACT_GELU, TV_E_ARG, "unknown activation %d", act);
   int G, nch;
   chunk_geo(n, G, nch);
+  const double C = (double)P * E + 1;
+  ProfScope prof(K_ACTIVATION, st, 12.0 * rows * C * n, 16.0 * rows * C * n);
   dim3 grid(rows, nch), block(kThreads);
   if (act == TV_ACT_RELU)
     hipLaunchKernelGGL((activation_kernel<1, TV_ACT_RELU>), grid, block, 0, st, x.S, x.R, P, E, n, G, rps, pn, eps,
@@ -736,6 +740,8 @@ int layernorm(CState x, int rows, int P, int E, int n, int rps, int pn, const fl
   TV_REQUIRE(ln_eps > 0.f, TV_E_ARG, "ln_eps must be positive");
   int G, VEC;
   TV_REQUIRE(row_geo(n, G, VEC), TV_E_SHAPE, "layernorm width %d exceeds %d", n, 4 * 64 * kMaxVec);
+  const double C = (double)P * E + 1;
+  ProfScope prof(K_LAYERNORM, st, 40.0 * rows * C * n, 16.0 * rows * C * n);
   dim3 grid(rows), block(kThreads);
 #define LN_LAUNCH(V)                                                                                            \
   hipLaunchKernelGGL((layernorm_kernel<V>), grid, block, 0, st, x.S, x.R, P, E, n, G, rps, pn, eps, gamma, beta, \
@@ -757,6 +763,8 @@ int softmax(State s, int rows, int P, int E, int L, int rps, int pn, const float
   TV_REQUIRE(lp && status, TV_E_NULL, "null pointer");
   int G, VEC;
   TV_REQUIRE(row_geo(L, G, VEC), TV_E_SHAPE, "softmax width %d exceeds %d", L, 4 * 64 * kMaxVec);
+  const double C = (double)P * E + 1;
+  ProfScope prof(K_SOFTMAX, st, 40.0 * rows * C * L, 16.0 * rows * C * L);
   dim3 grid(rows), block(kThreads);
 #define SM_LAUNCH(V) \
   hipLaunchKernelGGL((softmax_kernel<V>), grid, block, 0, st, s.S, s.R, P, E, L, G, rps, pn, eps, lp, status)
