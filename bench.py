@@ -31,6 +31,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true",
                     help="leave the per-launch HIP events out of the timed region")
+    ap.add_argument("--probe", action="store_true",
+                    help="counter probe: a 1 GiB device copy (known traffic) followed by one verify sweep, no timing")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (every box has one); use --gpus 1", file=sys.stderr)
@@ -49,6 +51,20 @@ def main():
     tok_d, pos_d = torch.as_tensor(tokens, device=dev), torch.as_tensor(positions, device=dev)
     ws = model.workspace(w.batch, w.seq_len, w.n_perturbed)
     full, _ = model.workspace_query(w.batch, w.seq_len, w.n_perturbed)
+
+    if args.probe:
+        # for `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE`: the copy kernel moves exactly 2^30 bytes each way
+        # and calibrates the counter unit; the sweep's dispatches follow it
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        eps = torch.full((w.batch,), 1e-3, dtype=torch.float32, device=dev)
+        model.verify(tok_d, pos_d, w.p_norms[-1], eps, workspace=ws)
+        torch.cuda.synchronize()
+        print(json.dumps({"probe": "copy of 2^30 bytes, then one verify sweep", "workload": args.workload}))
+        return
 
     def step():
         out = None

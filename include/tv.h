@@ -13,9 +13,10 @@
  * (delta = offsets of the P perturbed embeddings, E = hidden size).  The
  * library stores a state in centre/radius form, two fp32 planes
  *     S = (upper + lower) / 2 ,   R = (upper - lower) / 2       (elementwise)
- * each laid out [rows][C][n] with C = P*E + 1: coefficient rows 0..P*E-1
- * (block r*E..r*E+E-1 belongs to the r-th perturbed position) followed by the
- * bias row; n (the neuron axis) is contiguous.  With W = W+ + W- the sign-split
+ * each laid out [groups][C][T][n]: groups = sentences (or sentence x head for
+ * attention scores), C = P*E + 1 coefficient rows 0..P*E-1 (block r*E..r*E+E-1
+ * belongs to the r-th perturbed position) followed by the bias row, T rows per
+ * group (tokens), n contiguous neurons.  With W = W+ + W- the sign-split
  * affine rule of Eq. (2) becomes  S_y = W S_x + c,  R_y = |W| R_x.
  *
  * Conventions.  All pointers are DEVICE pointers unless a comment says host.
@@ -119,42 +120,42 @@ int tv_certify(const tv_model *m, const int32_t *tokens, int B, int L, const int
                void *stream);
 
 /* ---- single operators on bound states (the kernels behind tv_verify; exported for unit parity
- * tests and per-kernel benchmarks).  S*, R* are the two planes of a state, [rows][C][n]. ---------- */
+ * tests and per-kernel benchmarks).  S*, R* are the two planes of a state, [groups][C][T][n];
+ * eps is indexed by group / groups_per_sentence. -------------------------------------------------- */
 
 /* Eq. (1): l = (S_b - R_b) - eps * N(S - R),  u = (S_b + R_b) + eps * N(S + R), with
- * N = sum over the P blocks of the dual (l_q) norm; eps is indexed by row / rows_per_sentence.
- * l, u: [rows][n].  n % 4 == 0. */
-int tv_op_concretize(const float *S, const float *R, int rows, int P, int E, int n, int rows_per_sentence,
-                     int p_norm, const float *eps, float *l, float *u, void *stream);
+ * N = sum over the P blocks of the dual (l_q) norm.  l, u: [groups][T][n].  n % 4 == 0. */
+int tv_op_concretize(const float *S, const float *R, int groups, int P, int E, int T, int n,
+                     int groups_per_sentence, int p_norm, const float *eps, float *l, float *u, void *stream);
 
 /* out = |in| elementwise (builds |W| for tv_op_affine). */
 int tv_op_abs(const float *in, float *out, size_t count, void *stream);
 
 /* Eq. (2) in centre/radius form on MFMA: Sy = Sx W^T (+ bias on the bias row) (+ Sadd),
- * Ry = Rx |W|^T (+ Radd).  Sx, Rx: [rows][C][K]; W, Wabs: [N][K]; bias [N] or NULL; Sadd/Radd
- * [rows][C][N] or both NULL (residual input, fused strict-elementwise add); Sy, Ry: [rows][C][N]
- * (must not alias the inputs).  K % 4 == 0, N % 4 == 0. */
-int tv_op_affine(const float *Sx, const float *Rx, int rows, int P, int E, int K, int N, const float *W,
+ * Ry = Rx |W|^T (+ Radd).  Sx, Rx: [groups][C][T][K]; W, Wabs: [N][K]; bias [N] or NULL; Sadd/Radd
+ * [groups][C][T][N] or both NULL (residual input, fused strict-elementwise add); Sy, Ry:
+ * [groups][C][T][N] (must not alias the inputs).  K % 4 == 0, N % 4 == 0. */
+int tv_op_affine(const float *Sx, const float *Rx, int groups, int P, int E, int T, int K, int N, const float *W,
                  const float *Wabs, const float *bias, const float *Sadd, const float *Radd, float *Sy,
                  float *Ry, void *stream);
 
 /* Fused concretize + relaxation + substitution for an activation (paper Sec. 4.1 second pattern,
- * Sec. 4.3): act = TV_ACT_*.  In-place allowed (Sy == Sx, Ry == Rx).  status [rows/rows_per_sentence]
- * is OR-ed with 1 on non-finite bounds. */
-int tv_op_activation(int act, const float *Sx, const float *Rx, int rows, int P, int E, int n,
-                     int rows_per_sentence, int p_norm, const float *eps, float *Sy, float *Ry,
+ * Sec. 4.3): act = TV_ACT_*.  In-place allowed (Sy == Sx, Ry == Rx).  status [groups/groups_per_sentence]
+ * is set to 1 on non-finite bounds. */
+int tv_op_activation(int act, const float *Sx, const float *Rx, int groups, int P, int E, int T, int n,
+                     int groups_per_sentence, int p_norm, const float *eps, float *Sy, float *Ry,
                      int32_t *status, void *stream);
 
 /* Full LayerNorm bound over the neuron axis (centre, square, mean, sqrt, reciprocal, product,
- * gamma/beta).  x: [rows][C][n] -> y same shape, must not alias. */
-int tv_op_layernorm(const float *Sx, const float *Rx, int rows, int P, int E, int n, int rows_per_sentence,
-                    int p_norm, const float *eps, const float *gamma, const float *beta, float ln_eps,
+ * gamma/beta).  x: [groups][C][T][n] -> y same shape, must not alias. */
+int tv_op_layernorm(const float *Sx, const float *Rx, int groups, int P, int E, int T, int n,
+                    int groups_per_sentence, int p_norm, const float *eps, const float *gamma, const float *beta, float ln_eps,
                     float *Sy, float *Ry, int32_t *status, void *stream);
 
 /* Self-attention core of one layer, all heads: scores = q k^T / sqrt(d_h) (dot-product bound with
  * both operands perturbed, paper Sec. 2.3), softmax bound, o = p v (dot-product bound).
- * q, k, v: [B*L][C][D]; o: [B*L][C][D] (heads concatenated); must not alias.
- * If Ss/Rs are non-NULL ([B*H*L][C][L]) the softmax output state p is left there, otherwise the
+ * q, k, v: [B][C][L][D]; o: [B][C][L][D] (heads concatenated); must not alias.
+ * If Ss/Rs are non-NULL ([B*H][C][L][L]) the softmax output state p is left there, otherwise the
  * workspace holds it.  workspace >= tv_attention_workspace(B, L, H, D, P) bytes. */
 size_t tv_attention_workspace(int B, int L, int H, int D, int P);
 int tv_op_attention(const float *Sq, const float *Rq, const float *Sk, const float *Rk, const float *Sv,

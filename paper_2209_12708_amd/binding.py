@@ -66,11 +66,11 @@ def lib():
         vp, i, f, sz = C.c_void_p, C.c_int, C.c_float, C.c_size_t
         L.tv_verify.argtypes = [vp, vp, i, i, vp, i, i, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.tv_certify.argtypes = [vp, vp, i, i, vp, i, i, f, f, i, vp, vp, vp, vp, vp, sz, vp]
-        L.tv_op_concretize.argtypes = [vp, vp, i, i, i, i, i, i, vp, vp, vp, vp]
+        L.tv_op_concretize.argtypes = [vp, vp, i, i, i, i, i, i, i, vp, vp, vp, vp]
         L.tv_op_abs.argtypes = [vp, vp, sz, vp]
-        L.tv_op_affine.argtypes = [vp, vp, i, i, i, i, i, vp, vp, vp, vp, vp, vp, vp, vp]
-        L.tv_op_activation.argtypes = [i, vp, vp, i, i, i, i, i, i, vp, vp, vp, vp, vp]
-        L.tv_op_layernorm.argtypes = [vp, vp, i, i, i, i, i, i, vp, vp, vp, f, vp, vp, vp, vp]
+        L.tv_op_affine.argtypes = [vp, vp, i, i, i, i, i, i, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.tv_op_activation.argtypes = [i, vp, vp, i, i, i, i, i, i, i, vp, vp, vp, vp, vp]
+        L.tv_op_layernorm.argtypes = [vp, vp, i, i, i, i, i, i, i, vp, vp, vp, f, vp, vp, vp, vp]
         L.tv_op_attention.argtypes = [vp] * 6 + [i] * 6 + [vp] * 5 + [i, vp, vp, sz, vp]
         L.tv_profile_enable.argtypes = [i]
         L.tv_profile_get.argtypes = [i, C.c_char_p, i, C.POINTER(C.c_double), C.POINTER(C.c_longlong),
@@ -190,13 +190,13 @@ class Model:
         return {"eps": out_eps, "labels": out_labels, "status": status}
 
 
-# ---- single operators (device tensors in, device tensors out) ----------------------------------
-def op_concretize(S, R, P, E, rows_per_sentence, p_norm, eps):
-    rows, Cc, n = S.shape
+# ---- single operators (device tensors in, device tensors out).  States are [G, C, T, n] ------------
+def op_concretize(S, R, P, E, groups_per_sentence, p_norm, eps):
+    G, Cc, T, n = S.shape
     assert Cc == P * E + 1
-    l = torch.empty(rows, n, dtype=torch.float32, device=S.device)
+    l = torch.empty(G, T, n, dtype=torch.float32, device=S.device)
     u = torch.empty_like(l)
-    _check(lib().tv_op_concretize(_ptr(S), _ptr(R), rows, P, E, n, rows_per_sentence, p_norm, _ptr(eps), _ptr(l),
+    _check(lib().tv_op_concretize(_ptr(S), _ptr(R), G, P, E, T, n, groups_per_sentence, p_norm, _ptr(eps), _ptr(l),
                                   _ptr(u), _stream()))
     return l, u
 
@@ -208,45 +208,44 @@ def op_abs(x):
 
 
 def op_affine(S, R, P, E, W, bias=None, add=None):
-    rows, Cc, K = S.shape
+    G, Cc, T, K = S.shape
     N = W.shape[0]
     Wabs = op_abs(W)
-    Sy = torch.empty(rows, Cc, N, dtype=torch.float32, device=S.device)
+    Sy = torch.empty(G, Cc, T, N, dtype=torch.float32, device=S.device)
     Ry = torch.empty_like(Sy)
-    _check(lib().tv_op_affine(_ptr(S), _ptr(R), rows, P, E, K, N, _ptr(W), _ptr(Wabs), _ptr(bias),
+    _check(lib().tv_op_affine(_ptr(S), _ptr(R), G, P, E, T, K, N, _ptr(W), _ptr(Wabs), _ptr(bias),
                               _ptr(add[0]) if add else None, _ptr(add[1]) if add else None, _ptr(Sy), _ptr(Ry),
                               _stream()))
     return Sy, Ry
 
 
-def op_activation(act, S, R, P, E, rows_per_sentence, p_norm, eps, inplace=False):
-    rows, Cc, n = S.shape
+def op_activation(act, S, R, P, E, groups_per_sentence, p_norm, eps, inplace=False):
+    G, Cc, T, n = S.shape
     Sy, Ry = (S, R) if inplace else (torch.empty_like(S), torch.empty_like(R))
-    status = torch.zeros(rows // rows_per_sentence, dtype=torch.int32, device=S.device)
-    _check(lib().tv_op_activation(act, _ptr(S), _ptr(R), rows, P, E, n, rows_per_sentence, p_norm, _ptr(eps),
+    status = torch.zeros(G // groups_per_sentence, dtype=torch.int32, device=S.device)
+    _check(lib().tv_op_activation(act, _ptr(S), _ptr(R), G, P, E, T, n, groups_per_sentence, p_norm, _ptr(eps),
                                   _ptr(Sy), _ptr(Ry), _ptr(status), _stream()))
     return Sy, Ry, status
 
 
-def op_layernorm(S, R, P, E, rows_per_sentence, p_norm, eps, gamma, beta, ln_eps):
-    rows, Cc, n = S.shape
+def op_layernorm(S, R, P, E, groups_per_sentence, p_norm, eps, gamma, beta, ln_eps):
+    G, Cc, T, n = S.shape
     Sy, Ry = torch.empty_like(S), torch.empty_like(R)
-    status = torch.zeros(rows // rows_per_sentence, dtype=torch.int32, device=S.device)
-    _check(lib().tv_op_layernorm(_ptr(S), _ptr(R), rows, P, E, n, rows_per_sentence, p_norm, _ptr(eps), _ptr(gamma),
+    status = torch.zeros(G // groups_per_sentence, dtype=torch.int32, device=S.device)
+    _check(lib().tv_op_layernorm(_ptr(S), _ptr(R), G, P, E, T, n, groups_per_sentence, p_norm, _ptr(eps), _ptr(gamma),
                                  _ptr(beta), ln_eps, _ptr(Sy), _ptr(Ry), _ptr(status), _stream()))
     return Sy, Ry, status
 
 
-def op_attention(q, k, v, B, L, H, P, p_norm, eps, stop_after=0):
-    """q, k, v: (S, R) pairs [B*L, C, D].  Returns (o pair or None, score/softmax state pair, status)."""
-    D = q[0].shape[2]
-    Cc = q[0].shape[1]
+def op_attention(q, k, v, H, P, p_norm, eps, stop_after=0):
+    """q, k, v: (S, R) pairs [B, C, L, D].  Returns (o pair, score / softmax state pair [B*H, C, L, L], status)."""
+    B, Cc, L, D = q[0].shape
     dev = q[0].device
     nbytes = lib().tv_attention_workspace(B, L, H, D, P)
     ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
-    So = torch.empty(B * L, Cc, D, dtype=torch.float32, device=dev)
+    So = torch.empty(B, Cc, L, D, dtype=torch.float32, device=dev)
     Ro = torch.empty_like(So)
-    Ss = torch.empty(B * H * L, Cc, L, dtype=torch.float32, device=dev)
+    Ss = torch.empty(B * H, Cc, L, L, dtype=torch.float32, device=dev)
     Rs = torch.empty_like(Ss)
     status = torch.zeros(B, dtype=torch.int32, device=dev)
     _check(lib().tv_op_attention(_ptr(q[0]), _ptr(q[1]), _ptr(k[0]), _ptr(k[1]), _ptr(v[0]), _ptr(v[1]), B, L, H, D,

@@ -31,7 +31,7 @@ struct ProfScope {   // brackets the launches issued during its lifetime; flops 
   int kind_; hipStream_t st_; void *rec_;
 };
 
-// A bound state: two planes [rows][C][n].
+// A bound state: two planes [groups][C][T][n] (C = P*E + 1 coefficient rows, bias row last).
 struct State {
   float *S, *R;
 };
@@ -49,17 +49,15 @@ struct GemmArgs {
   long lda = 0;
   const float *B = nullptr;
   long ldb = 0;
-  int b_mode = 0;   // 0: B[n][k] (k contiguous), row(n) = (n % b_q) * b_m1 + (n / b_q) * b_m2 (b_q = 0: row = n)
-                    // 1: B[k][col(n)] (n contiguous in groups of cq)
-  int b_q = 0; long b_m1 = 0, b_m2 = 0;
+  int b_mode = 0;   // 0: B[n][k] (k contiguous);  1: B[k][col(n)] (n contiguous in groups of cq)
   int cq = 0; long cstride = 0;   // col(n) = (n / cq) * cstride + n % cq   (cq = 0: col = n) for C, Cadd and bias
   long b_cstride = 0;             // the same map with its own stride for B in mode 1
   float *C = nullptr;
   const float *Cadd = nullptr;    // same layout as C; may equal C (accumulate)
   long ldc = 0;
-  const float *bias = nullptr;    // added on rows m with m % bias_period == bias_period - 1:
-  long bias_ld = 0;               //   bias[(m / bias_period) * bias_ld + col(n)]
-  int bias_period = 0;
+  const float *bias = nullptr;    // rows m = ((group * bias_C) + r) * bias_T + t; added where r == bias_C - 1:
+  long bias_ld = 0;               //   bias[(group * bias_T + t) * bias_ld + col(n)]
+  int bias_T = 0, bias_C = 0;
   int M = 0, N = 0, K = 0;
   int nz0 = 1, nz1 = 1, nz2 = 1;
   int kind = K_MISC;              // timing class
@@ -69,16 +67,18 @@ struct GemmArgs {
 int gemm(const GemmArgs &g, hipStream_t st);
 
 // ---- elementwise / reduction kernels (rowops.hip) ------------------------------------------
-// ld: floats between consecutive coefficient rows of the input state (n when densely packed)
-// mode 0: outputs are (l, u); mode 1: outputs are (mid, half) = ((u+l)/2, (u-l)/2), each accurate in fp32
-int concretize(CState x, int rows, int P, int E, int n, int ld, int rps, int p_norm, const float *eps, float *l,
-               float *u, int mode, hipStream_t st);
-int activation(int act, CState x, int rows, int P, int E, int n, int rps, int p_norm, const float *eps,
+// States are [groups][C][T][n]; eps is indexed by group / gps (groups per sentence).
+// concretize: mode 0 -> (o0, o1) = (l, u); mode 1 -> (mid, half) = ((u+l)/2, (u-l)/2), each accurate in
+// fp32, and o2 (optional) = S_b - l, the slack between the bias centre and the lower bound.
+int concretize(CState x, int groups, int P, int E, int T, int n, int gps, int p_norm, const float *eps, float *o0,
+               float *o1, float *o2, int mode, hipStream_t st);
+int activation(int act, CState x, int groups, int P, int E, int T, int n, int gps, int p_norm, const float *eps,
                State y, int32_t *status, hipStream_t st);
-int layernorm(CState x, int rows, int P, int E, int n, int rps, int p_norm, const float *eps,
+int layernorm(CState x, int groups, int P, int E, int T, int n, int gps, int p_norm, const float *eps,
               const float *gamma, const float *beta, float ln_eps, State y, int32_t *status, hipStream_t st);
-int softmax(State s, int rows, int P, int E, int L, int rps, int p_norm, const float *eps, float *lp,
-            int32_t *status, hipStream_t st);
+// in place; also writes lp = clamp(lower bound of p, 0, 1) and slack = S_p_b - lp, both [groups][T][n]
+int softmax(State s, int groups, int P, int E, int T, int n, int gps, int p_norm, const float *eps, float *lp,
+            float *slack, int32_t *status, hipStream_t st);
 int vec_abs(const float *in, float *out, size_t count, hipStream_t st);
 int fill_zero(float *p, size_t count, hipStream_t st);
 

@@ -11,6 +11,7 @@
 // LDS (one stage; the next stage is prefetched into registers while the matrix cores run).  Each
 // wave owns (BM/WM) x (BN/WN) as 32x32 MFMA tiles.  LDS rows are padded to 36 floats so that the
 // 128-bit fragment reads of 16 consecutive rows hit 16 distinct bank groups.
+#include <stdlib.h>
 #include "common.h"
 
 namespace tv {
@@ -18,19 +19,20 @@ namespace {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-constexpr int BK = 32;   // K per LDS stage
-constexpr int LS = 36;   // padded LDS row length (floats) for [row][k] tiles
 
 __device__ __forceinline__ long remap_col(int n, int cq, long cstride) {
   return cq ? (long)(n / cq) * cstride + (n % cq) : (long)n;
 }
 
-template <int BM, int BN, int WM, int WN, int BMODE>
+template <int BM, int BN, int WM, int WN, int BMODE, int BK>
 __global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs g, int mtiles, int ntiles) {
+  constexpr int LS = BK + 4;              // padded LDS row length (floats) for [row][k] tiles
+  constexpr int KQ = BK / 4;              // float4 groups per row of a stage
+  constexpr int HK = BK / 2;              // k values per lane half
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
-  constexpr int A_F4 = BM * 8 / 256 > 0 ? BM * 8 / 256 : 1;
-  constexpr int B_F4 = BN * 8 / 256 > 0 ? BN * 8 / 256 : 1;
-  constexpr int B1_HALF = 16 * BN + 32;   // mode 1: floats per 16-row half, second half shifted by 32 banks
+  constexpr int A_F4 = BM * KQ / 256 > 0 ? BM * KQ / 256 : 1;
+  constexpr int B_F4 = BN * KQ / 256 > 0 ? BN * KQ / 256 : 1;
+  constexpr int B1_HALF = HK * BN + 32;   // mode 1: floats per half of the stage, second half shifted by 32 banks
   constexpr int A_LDS = BM * LS;
   constexpr int B_LDS = BMODE == 0 ? BN * LS : 2 * B1_HALF;
   __shared__ __attribute__((aligned(16))) float lds[A_LDS + B_LDS];
@@ -40,10 +42,16 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs g, int mtiles,
   // own M tiles and let consecutive ids on one XCD sweep the N tiles of the same M tile, so the A
   // rows are fetched into one L2 only.
   const int wid = blockIdx.x;
-  const int xcd = wid & 7, slot = wid >> 3;
-  const int nt = slot % ntiles;
-  const int mt = (slot / ntiles) * 8 + xcd;
-  if (mt >= mtiles) return;
+  int mt, nt;
+  if (mtiles >= 8) {
+    const int xcd = wid & 7, slot = wid >> 3;
+    nt = slot % ntiles;
+    mt = (slot / ntiles) * 8 + xcd;
+    if (mt >= mtiles) return;
+  } else {            // few M tiles (per-batch contractions over tokens): no padding of the grid
+    mt = wid % mtiles;
+    nt = wid / mtiles;
+  }
   const int m0 = mt * BM, n0 = nt * BN;
 
   int z = blockIdx.y;
@@ -65,7 +73,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs g, int mtiles,
 #pragma unroll
   for (int i = 0; i < A_F4; ++i) {
     const int f = tid + 256 * i;
-    const int row = f >> 3, kq = f & 7;
+    const int row = f / KQ, kq = f % KQ;
     a_on[i] = row < BM;
     int m = m0 + row; if (m >= M) m = M - 1;
     a_ptr[i] = A + (long)m * g.lda;
@@ -78,11 +86,10 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs g, int mtiles,
   for (int i = 0; i < B_F4; ++i) {
     const int f = tid + 256 * i;
     if (BMODE == 0) {
-      const int row = f >> 3, kq = f & 7;
+      const int row = f / KQ, kq = f % KQ;
       b_on[i] = row < BN;
       int n = n0 + row; if (n >= N) n = N - 1;
-      const long brow = g.b_q ? (long)(n % g.b_q) * g.b_m1 + (long)(n / g.b_q) * g.b_m2 : (long)n;
-      b_ptr[i] = B + brow * g.ldb;
+      b_ptr[i] = B + (long)n * g.ldb;
       b_k[i] = kq * 4;
       b_lds[i] = row * LS + kq * 4;
     } else {
@@ -92,7 +99,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs g, int mtiles,
       int n = n0 + nq * 4; if (n >= N) n = N - 4;
       b_ptr[i] = B + remap_col(n, g.cq, g.b_cstride);
       b_k[i] = k;
-      b_lds[i] = (k >> 4) * B1_HALF + (k & 15) * BN + nq * 4;
+      b_lds[i] = (k / HK) * B1_HALF + (k % HK) * BN + nq * 4;
     }
   }
 
@@ -145,13 +152,13 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs g, int mtiles,
   __syncthreads();
   for (int kt = 0; kt < KT; ++kt) {
     if (kt + 1 < KT) load_tile((kt + 1) * BK);
-    // MFMA step s multiplies k = s (lanes 0-31) and k = 16 + s (lanes 32-63) of this stage
+    // MFMA step s multiplies k = s (lanes 0-31) and k = BK/2 + s (lanes 32-63) of this stage
 #pragma unroll
-    for (int hs = 0; hs < 2; ++hs) {
+    for (int hs = 0; hs < HK / 8; ++hs) {
       float4 af[TM][2], bf[TN][2];
 #pragma unroll
       for (int i = 0; i < TM; ++i) {
-        const float *p = As + (wm * (BM / WM) + i * 32 + l32) * LS + half * 16 + hs * 8;
+        const float *p = As + (wm * (BM / WM) + i * 32 + l32) * LS + half * HK + hs * 8;
         af[i][0] = *reinterpret_cast<const float4 *>(p);
         af[i][1] = *reinterpret_cast<const float4 *>(p + 4);
       }
@@ -159,7 +166,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs g, int mtiles,
       for (int j = 0; j < TN; ++j) {
         const int col = wn * (BN / WN) + j * 32 + l32;
         if (BMODE == 0) {
-          const float *p = Bs + col * LS + half * 16 + hs * 8;
+          const float *p = Bs + col * LS + half * HK + hs * 8;
           bf[j][0] = *reinterpret_cast<const float4 *>(p);
           bf[j][1] = *reinterpret_cast<const float4 *>(p + 4);
         } else {
@@ -189,40 +196,67 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs g, int mtiles,
   }
 
   // ---- epilogue.  Accumulator v of lane l holds row 8*(v/4) + 4*(l/32) + v%4, column l%32.
+  // does this tile contain rows of a bias block at all?  (one scalar test; 1 in C row blocks does)
+  bool tile_has_bias = false;
+  if (bias) {
+    const int ba = m0 / g.bias_T, bb = (min(m0 + BM, M) - 1) / g.bias_T;
+    tile_has_bias = (ba % g.bias_C) + (bb - ba) >= g.bias_C - 1;
+  }
+  long col[TN]; bool con[TN];
+#pragma unroll
+  for (int j = 0; j < TN; ++j) {
+    const int n = n0 + wn * (BN / WN) + j * 32 + l32;
+    con[j] = n < N;
+    col[j] = remap_col(con[j] ? n : 0, g.cq, g.cstride);
+  }
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
-#pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const int m = m0 + wm * (BM / WM) + i * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
-      if (m >= M) continue;
-      const float *brow = nullptr;
-      if (bias && (m % g.bias_period) == g.bias_period - 1) brow = bias + (long)(m / g.bias_period) * g.bias_ld;
+    const int mb = m0 + wm * (BM / WM) + i * 32 + 4 * half;
+    if (Cadd) {     // residual / accumulate: issue all the loads of this 32-row tile before using them
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
-        const int n = n0 + wn * (BN / WN) + j * 32 + l32;
-        if (n >= N) continue;
-        const long col = remap_col(n, g.cq, g.cstride);
+        float add[16];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int m = mb + 8 * (v >> 2) + (v & 3);
+          add[v] = (m < M && con[j]) ? Cadd[(long)m * g.ldc + col[j]] : 0.f;
+        }
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][j][v] += add[v];
+      }
+    }
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int m = mb + 8 * (v >> 2) + (v & 3);
+      if (m >= M) continue;
+      const float *brow = nullptr;
+      if (tile_has_bias) {   // rows are ordered (group, coefficient row, t); the last coefficient row is the bias row
+        const int blk = m / g.bias_T;
+        if (blk % g.bias_C == g.bias_C - 1)
+          brow = bias + ((long)(blk / g.bias_C) * g.bias_T + m % g.bias_T) * g.bias_ld;
+      }
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        if (!con[j]) continue;
         float val = acc[i][j][v];
-        if (brow) val += brow[col];
-        const long off = (long)m * g.ldc + col;
-        if (Cadd) val += Cadd[off];
-        C[off] = val;
+        if (brow) val += brow[col[j]];
+        C[(long)m * g.ldc + col[j]] = val;
       }
     }
   }
 }
 
-template <int BM, int BN, int WM, int WN>
+template <int BM, int BN, int WM, int WN, int BK = 32>
 int launch(const GemmArgs &g, hipStream_t st) {
   const int mtiles = (g.M + BM - 1) / BM, ntiles = (g.N + BN - 1) / BN;
-  const long groups = (long)((mtiles + 7) / 8) * 8 * ntiles;
+  const long groups = mtiles >= 8 ? (long)((mtiles + 7) / 8) * 8 * ntiles : (long)mtiles * ntiles;
   const long nz = (long)g.nz0 * g.nz1 * g.nz2;
   TV_REQUIRE(groups < (1L << 31) && nz <= 65535L * 32768L, TV_E_SHAPE, "gemm: grid too large");
   dim3 grid((unsigned)groups, (unsigned)nz, 1), block(256, 1, 1);
   if (g.b_mode == 0)
-    hipLaunchKernelGGL((gemm_kernel<BM, BN, WM, WN, 0>), grid, block, 0, st, g, mtiles, ntiles);
+    hipLaunchKernelGGL((gemm_kernel<BM, BN, WM, WN, 0, BK>), grid, block, 0, st, g, mtiles, ntiles);
   else
-    hipLaunchKernelGGL((gemm_kernel<BM, BN, WM, WN, 1>), grid, block, 0, st, g, mtiles, ntiles);
+    hipLaunchKernelGGL((gemm_kernel<BM, BN, WM, WN, 1, BK>), grid, block, 0, st, g, mtiles, ntiles);
   TV_HIP(hipGetLastError());
   return TV_OK;
 }
@@ -237,7 +271,7 @@ int gemm(const GemmArgs &g, hipStream_t st) {
   TV_REQUIRE(g.A2 ? (g.K1 % 4 == 0 && g.K1 > 0 && g.K1 < g.K) : true, TV_E_SHAPE, "gemm: bad K split");
   TV_REQUIRE(g.b_mode == 0 || (g.N % 4 == 0 && (g.cq == 0 || g.cq % 4 == 0)), TV_E_SHAPE,
              "gemm: column groups must be multiples of 4");
-  TV_REQUIRE(g.bias == nullptr || g.bias_period > 0, TV_E_ARG, "gemm: bias without period");
+  TV_REQUIRE(g.bias == nullptr || (g.bias_T > 0 && g.bias_C > 0), TV_E_ARG, "gemm: bias without row structure");
   GemmArgs a = g;
   if (!a.A2) a.K1 = a.K;
   const double nz = (double)g.nz0 * g.nz1 * g.nz2, mn = (double)g.M * g.N;
@@ -248,6 +282,14 @@ int gemm(const GemmArgs &g, hipStream_t st) {
   if (a.M <= 64) return launch<64, 128, 2, 2>(a, st);
   if (a.N <= 32) return launch<128, 32, 4, 1>(a, st);
   if (a.N <= 64) return launch<128, 64, 2, 2>(a, st);
+  static const int exp_nobias = getenv("TV_GEMM_NOBIAS") ? 1 : 0;   // experiment hook (timing only)
+  if (exp_nobias) a.bias = nullptr;
+  static const int exp_tile = getenv("TV_GEMM_TILE") ? atoi(getenv("TV_GEMM_TILE")) : 0;   // experiment hook
+  if (exp_tile == 1 || (exp_tile == 0 && a.K <= 256 && a.N % 128 == 0)) return launch<64, 128, 2, 2>(a, st);
+  if (exp_tile == 2) return launch<128, 64, 2, 2>(a, st);
+  if (exp_tile == 3) return launch<64, 64, 2, 2>(a, st);
+  if (exp_tile == 4) return launch<128, 128, 2, 2, 64>(a, st);
+  if (exp_tile == 5) return launch<64, 128, 2, 2, 64>(a, st);
   return launch<128, 128, 2, 2>(a, st);
 }
 

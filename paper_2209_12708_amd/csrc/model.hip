@@ -63,10 +63,10 @@ __global__ void init_state_kernel(const int32_t *tokens, const int32_t *position
     const long bt = i / D;
     const int t = (int)(bt % L), b = (int)(bt / L);
     const int tok = tokens[bt];
-    float *blk = S + bt * (long)C * D;
-    blk[(long)(C - 1) * D + d] = tok_emb[(long)tok * D + d] + pos_emb[(long)t * D + d];
+    float *sen = S + (long)b * C * L * D;     // [C][L][D] slab of sentence b
+    sen[((long)(C - 1) * L + t) * D + d] = tok_emb[(long)tok * D + d] + pos_emb[(long)t * D + d];
     for (int r = 0; r < P; ++r)
-      if (positions[b * P + r] == t) blk[(long)(r * D + d) * D + d] = 1.f;
+      if (positions[b * P + r] == t) sen[((long)(r * D + d) * L + t) * D + d] = 1.f;
   }
 }
 
@@ -239,14 +239,14 @@ int chunk_size(const tv_config &c, int B, int L, int P, size_t ws_bytes) {
 
 // Eq. (2) in centre/radius form: y = x W^T (+ bias on bias rows of the S plane) (+ add).  Wpair =
 // [W ; |W|], bpair = [b ; 0].  x planes are `xplane` floats apart, y planes `yplane`.
-int affine(const float *xS, long xplane, long M, int C, int K, int N, const float *Wpair, const float *bpair,
+int affine(const float *xS, long xplane, long M, int C, int T, int K, int N, const float *Wpair, const float *bpair,
            const float *addS, long addplane, float *yS, long yplane, hipStream_t st) {
   GemmArgs g;
   g.A = xS; g.lda = K;
   g.B = Wpair; g.ldb = K; g.b_mode = 0;
   g.C = yS; g.ldc = N;
   g.Cadd = addS;
-  g.bias = bpair; g.bias_ld = 0; g.bias_period = C;
+  g.bias = bpair; g.bias_ld = 0; g.bias_T = T; g.bias_C = C;
   TV_REQUIRE(M < (1L << 31), TV_E_SHAPE, "affine: %ld rows exceed the kernel's 32-bit row index", M);
   g.M = (int)M; g.N = N; g.K = K;
   g.nz0 = 2; g.kind = K_AFFINE;
@@ -274,22 +274,22 @@ int sweep(const tv_model *m, const Plan &pl, float *w, const int32_t *tokens, co
   for (int l = 0; l < c.n_layers; ++l) {
     const tv_layer_dev &lw = m->layers[l];
     // q, k, v in one product: columns [0,D) q, [D,2D) k, [2D,3D) v
-    if (int rc = affine(X, pD, M, C, D, 3 * D, lw.Wqkv, lw.bqkv, nullptr, 0, QKV, p3D, st)) return rc;
+    if (int rc = affine(X, pD, M, C, L, D, 3 * D, lw.Wqkv, lw.bqkv, nullptr, 0, QKV, p3D, st)) return rc;
     CState q{QKV, QKV + p3D}, k{QKV + D, QKV + p3D + D}, v{QKV + 2 * D, QKV + p3D + 2 * D};
     State o{T1, T1 + pD}, s{BIG, BIG + pS};
     if (int rc = attention(q, k, v, 3 * D, Bc, L, H, D, P, pn, eps, o, s, 0, status, attn_ws, attn_bytes, st))
       return rc;
     // a = o Wo^T + bo + x   (written over the dead q/k/v region), x' = LN(a) (over the dead x)
     float *A = QKV;
-    if (int rc = affine(T1, pD, M, C, D, D, lw.Wo, lw.bo, X, pD, A, pD, st)) return rc;
-    if (int rc = layernorm(CState{A, A + pD}, (int)rows, P, D, D, L, pn, eps, lw.ln1_g, lw.ln1_b, c.ln_eps,
+    if (int rc = affine(T1, pD, M, C, L, D, D, lw.Wo, lw.bo, X, pD, A, pD, st)) return rc;
+    if (int rc = layernorm(CState{A, A + pD}, Bc, P, D, L, D, 1, pn, eps, lw.ln1_g, lw.ln1_b, c.ln_eps,
                            State{X, X + pD}, status, st)) return rc;
     // feed-forward: h = x' W1^T + b1 ; act ; f = act W2^T + b2 + x' ; x'' = LN(f)
-    if (int rc = affine(X, pD, M, C, D, F, lw.W1, lw.b1, nullptr, 0, BIG, pF, st)) return rc;
-    if (int rc = activation(c.activation, CState{BIG, BIG + pF}, (int)rows, P, D, F, L, pn, eps,
+    if (int rc = affine(X, pD, M, C, L, D, F, lw.W1, lw.b1, nullptr, 0, BIG, pF, st)) return rc;
+    if (int rc = activation(c.activation, CState{BIG, BIG + pF}, Bc, P, D, L, F, 1, pn, eps,
                             State{BIG, BIG + pF}, status, st)) return rc;
-    if (int rc = affine(BIG, pF, M, C, F, D, lw.W2, lw.b2, X, pD, T1, pD, st)) return rc;
-    if (int rc = layernorm(CState{T1, T1 + pD}, (int)rows, P, D, D, L, pn, eps, lw.ln2_g, lw.ln2_b, c.ln_eps,
+    if (int rc = affine(BIG, pF, M, C, L, F, D, lw.W2, lw.b2, X, pD, T1, pD, st)) return rc;
+    if (int rc = layernorm(CState{T1, T1 + pD}, Bc, P, D, L, D, 1, pn, eps, lw.ln2_g, lw.ln2_b, c.ln_eps,
                            State{X, X + pD}, status, st)) return rc;
   }
   return TV_OK;
@@ -306,18 +306,18 @@ int head(const tv_model *m, const Plan &pl, float *w, int Bc, int L, int P, int 
                      c.n_classes, NP, D, Wh, bh);
   TV_HIP(hipGetLastError());
   GemmArgs g;
-  g.A = w + pl.x; g.lda = D;
+  g.A = w + pl.x; g.lda = (long)L * D;      // token 0 of coefficient row r: rows L*D apart
   g.B = Wh; g.ldb = D; g.b_mode = 0;
   g.C = Y; g.ldc = NP;
-  g.bias = bh; g.bias_ld = 0; g.bias_period = C;
+  g.bias = bh; g.bias_ld = 0; g.bias_T = 1; g.bias_C = C;
   g.M = C; g.N = NP; g.K = D;
   g.nz0 = 2; g.nz1 = Bc; g.kind = K_HEAD;
-  g.sA[0] = pD; g.sA[1] = (long)L * C * D;
+  g.sA[0] = pD; g.sA[1] = (long)C * L * D;
   g.sB[0] = (long)Bc * NP * D; g.sB[1] = (long)NP * D;
   g.sC[0] = (long)Bc * C * NP; g.sC[1] = (long)C * NP;
   g.sBias[0] = (long)Bc * NP; g.sBias[1] = NP;
   if (int rc = gemm(g, st)) return rc;
-  return concretize(CState{Y, Y + (long)Bc * C * NP}, Bc, P, D, NP, NP, 1, pn, eps, w + pl.hl, w + pl.hu, 0, st);
+  return concretize(CState{Y, Y + (long)Bc * C * NP}, Bc, P, D, 1, NP, 1, pn, eps, w + pl.hl, w + pl.hu, nullptr, 0, st);
 }
 
 int check_call(const tv_model *m, const int32_t *tokens, int B, int L, const int32_t *positions, int P, int pn,
@@ -565,46 +565,48 @@ int tv_profile_get(int kind, char *name, int name_len, double *total_ms, long lo
 }
 
 // ---- single operators --------------------------------------------------------------------------
-int tv_op_concretize(const float *S, const float *R, int rows, int P, int E, int n, int rps, int pn, const float *eps,
-                     float *l, float *u, void *stream) {
-  return concretize(CState{S, R}, rows, P, E, n, n, rps, pn, eps, l, u, 0, static_cast<hipStream_t>(stream));
+int tv_op_concretize(const float *S, const float *R, int groups, int P, int E, int T, int n, int gps, int pn,
+                     const float *eps, float *l, float *u, void *stream) {
+  return concretize(CState{S, R}, groups, P, E, T, n, gps, pn, eps, l, u, nullptr, 0, static_cast<hipStream_t>(stream));
 }
 
 int tv_op_abs(const float *in, float *out, size_t count, void *stream) {
   return vec_abs(in, out, count, static_cast<hipStream_t>(stream));
 }
 
-int tv_op_affine(const float *Sx, const float *Rx, int rows, int P, int E, int K, int N, const float *W,
+int tv_op_affine(const float *Sx, const float *Rx, int groups, int P, int E, int T, int K, int N, const float *W,
                  const float *Wabs, const float *bias, const float *Sadd, const float *Radd, float *Sy, float *Ry,
                  void *stream) {
   TV_REQUIRE(Sx && Rx && W && Wabs && Sy && Ry, TV_E_NULL, "tv_op_affine: null pointer");
   TV_REQUIRE((Sadd == nullptr) == (Radd == nullptr), TV_E_NULL, "tv_op_affine: Sadd and Radd must both be given or both NULL");
-  TV_REQUIRE(rows > 0 && P >= 0 && E > 0 && K > 0 && N > 0 && K % 4 == 0 && N % 4 == 0, TV_E_SHAPE,
-             "tv_op_affine: bad shape rows=%d P=%d E=%d K=%d N=%d", rows, P, E, K, N);
+  TV_REQUIRE(groups > 0 && P >= 0 && E > 0 && T > 0 && K > 0 && N > 0 && K % 4 == 0 && N % 4 == 0, TV_E_SHAPE,
+             "tv_op_affine: bad shape groups=%d P=%d E=%d T=%d K=%d N=%d", groups, P, E, T, K, N);
   hipStream_t st = static_cast<hipStream_t>(stream);
   const int C = P * E + 1;
-  const long M = (long)rows * C;
+  const long M = (long)groups * C * T;
   TV_REQUIRE(M < (1L << 31), TV_E_SHAPE, "tv_op_affine: too many rows");
   // the two planes use unrelated buffers here: one launch per plane
   GemmArgs g;
   g.lda = K; g.ldb = K; g.b_mode = 0; g.ldc = N; g.M = (int)M; g.N = N; g.K = K;
-  g.A = Sx; g.B = W; g.C = Sy; g.Cadd = Sadd; g.bias = bias; g.bias_ld = 0; g.bias_period = C;
+  g.A = Sx; g.B = W; g.C = Sy; g.Cadd = Sadd; g.bias = bias; g.bias_ld = 0; g.bias_T = T; g.bias_C = C;
+  g.kind = K_AFFINE;
   if (int rc = gemm(g, st)) return rc;
   g.A = Rx; g.B = Wabs; g.C = Ry; g.Cadd = Radd; g.bias = nullptr;
   return gemm(g, st);
 }
 
-int tv_op_activation(int act, const float *Sx, const float *Rx, int rows, int P, int E, int n, int rps, int pn,
+int tv_op_activation(int act, const float *Sx, const float *Rx, int groups, int P, int E, int T, int n, int gps, int pn,
                      const float *eps, float *Sy, float *Ry, int32_t *status, void *stream) {
-  return activation(act, CState{Sx, Rx}, rows, P, E, n, rps, pn, eps, State{Sy, Ry}, status,
+  return activation(act, CState{Sx, Rx}, groups, P, E, T, n, gps, pn, eps, State{Sy, Ry}, status,
                     static_cast<hipStream_t>(stream));
 }
 
-int tv_op_layernorm(const float *Sx, const float *Rx, int rows, int P, int E, int n, int rps, int pn, const float *eps,
+int tv_op_layernorm(const float *Sx, const float *Rx, int groups, int P, int E, int T, int n, int gps, int pn,
+                    const float *eps,
                     const float *gamma, const float *beta, float ln_eps, float *Sy, float *Ry, int32_t *status,
                     void *stream) {
   TV_REQUIRE(Sx != Sy && Rx != Ry, TV_E_ARG, "tv_op_layernorm: output must not alias the input");
-  return layernorm(CState{Sx, Rx}, rows, P, E, n, rps, pn, eps, gamma, beta, ln_eps, State{Sy, Ry}, status,
+  return layernorm(CState{Sx, Rx}, groups, P, E, T, n, gps, pn, eps, gamma, beta, ln_eps, State{Sy, Ry}, status,
                    static_cast<hipStream_t>(stream));
 }
 

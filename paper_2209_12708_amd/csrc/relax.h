@@ -167,29 +167,39 @@ __device__ __forceinline__ void line_range(const Line2 &ln, double ly, double uy
 }
 
 // centre/radius map of a form:  S_y = sS*S + sR*R + sC [bias row],  R_y = rS*S + rR*R + rC [bias row].
-// The differences are taken in double and rounded once.
-struct Map2 { float sS, sR, sC, rS, rR, rC; };
+// The differences are taken in double; the fp32 copies serve the coefficient rows, the double ones the
+// bias row.
+struct Map2 {
+  float sS, sR, rS, rR;
+  double sSd, sRd, sCd, rSd, rRd, rCd;
+};
 __device__ __forceinline__ Map2 form_map(const Form &f) {
   Map2 m;
-  m.sS = (float)(0.5 * (f.pL + f.qL + f.pU + f.qU));
-  m.sR = (float)(0.5 * (-f.pL + f.qL + f.pU - f.qU));
-  m.sC = (float)(0.5 * (f.cL + f.cU));
-  m.rS = (float)(0.5 * (f.pU + f.qU - f.pL - f.qL));
-  m.rR = (float)(0.5 * (f.pU - f.qU + f.pL - f.qL));
-  m.rC = (float)(0.5 * (f.cU - f.cL));
+  m.sSd = 0.5 * (f.pL + f.qL + f.pU + f.qU);
+  m.sRd = 0.5 * (-f.pL + f.qL + f.pU - f.qU);
+  m.sCd = 0.5 * (f.cL + f.cU);
+  m.rSd = 0.5 * (f.pU + f.qU - f.pL - f.qL);
+  m.rRd = 0.5 * (f.pU - f.qU + f.pL - f.qL);
+  m.rCd = 0.5 * (f.cU - f.cL);
+  m.sS = (float)m.sSd; m.sR = (float)m.sRd; m.rS = (float)m.rSd; m.rR = (float)m.rRd;
   return m;
 }
 
 // product z = x * y with x a state (S_x, R_x) and y a state (S_y, R_y), in centre/radius form:
 //   S_z = a1 S_x + a2 R_x + b S_y - b a1 [bias],   R_z = a3 S_x + a4 R_x + |b| R_y - b a3 [bias]
-// with the multiplier range [ly, uy] of y and b = lx.
-struct Mul2 { float a1, a2, a3, a4; };
+// with the multiplier range [ly, uy] of y and b = lx.  On the bias row a3 S_x - b a3 = a3 (S_x - lx) is
+// formed from the slack S_x - lx = R_x + eps N(lower line of x), which has no cancellation.
+struct Mul2 {
+  float a1, a2, a3, a4;
+  double a1d, a2d, a3d, a4d;
+};
 __device__ __forceinline__ Mul2 mul_coeffs(double ly, double uy) {
   Mul2 m;
-  m.a1 = (float)(0.5 * (ly + uy));
-  m.a2 = (float)(0.5 * (fabs(uy) - fabs(ly)));
-  m.a3 = (float)(0.5 * (uy - ly));
-  m.a4 = (float)(0.5 * (fabs(uy) + fabs(ly)));
+  m.a1d = 0.5 * (ly + uy);
+  m.a2d = 0.5 * (fabs(uy) - fabs(ly));
+  m.a3d = 0.5 * (uy - ly);
+  m.a4d = 0.5 * (fabs(uy) + fabs(ly));
+  m.a1 = (float)m.a1d; m.a2 = (float)m.a2d; m.a3 = (float)m.a3d; m.a4 = (float)m.a4d;
   return m;
 }
 

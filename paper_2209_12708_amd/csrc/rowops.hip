@@ -1,17 +1,27 @@
-// Memory-bound kernels over bound states [rows][C][n]: concretization (Eq. (1)), fused activation
+// Memory-bound kernels over bound states [G][C][T][n]: concretization (Eq. (1)), fused activation
 // relaxation, LayerNorm and softmax bounds.
 //
-// Common geometry.  A workgroup (256 threads) owns one row block (one token, or one attention row)
-// and a chunk of its columns.  Lanes lie along the contiguous neuron axis (each lane owns VEC float4
-// column groups), G lanes cover the chunk, and the 256/G "row slots" stride over the C coefficient
-// rows.  The norm of Eq. (1) is a reduction down the coefficient axis: lane-private accumulation
-// over the rows of a slot, then one butterfly across the slots of a wave and one LDS exchange
-// across the 4 waves - the paper's hybrid reduction (Sec. 4.2: k lane-private steps + one shuffle
-// tree), turned by 90 degrees because here the reduced axis is the strided one, and widened to
-// 64-lane wavefronts.  Sums along the neuron axis (softmax row sums, LayerNorm means) are butterflies
-// over the G lanes of a slot.  As in the paper's sharing-oriented scheduling (Sec. 4.3) the
-// concretized bounds never go to memory: the same workgroup that reduces a neuron's coefficients
+// Layout.  A state has G groups (sentences, or sentence x head), C = P*E + 1 coefficient rows (bias
+// row last), T rows per group (tokens) and n contiguous neurons.  For one coefficient row r the
+// [T][n] slab of a group is contiguous, so kernels that treat neurons independently (concretize,
+// activation) see one flat axis of T*n columns.
+//
+// Geometry.  A workgroup (256 threads) owns a chunk of columns of one group (or one token row for
+// the kernels that also reduce along n).  Lanes lie along the contiguous neuron axis (each lane owns
+// VEC float4 column groups), G lanes cover the chunk, and the 256/G "row slots" stride over the C
+// coefficient rows.  The norm of Eq. (1) is a reduction down the coefficient axis: lane-private
+// accumulation over the rows of a slot, then one butterfly across the slots of a wave and one LDS
+// exchange across the 4 waves - the paper's hybrid reduction (Sec. 4.2: k lane-private steps + one
+// shuffle tree), turned by 90 degrees because here the reduced axis is the strided one, and widened
+// to 64-lane wavefronts.  Sums along the neuron axis (softmax row sums, LayerNorm means) are
+// butterflies over the G lanes of a slot.  As in the paper's sharing-oriented scheduling (Sec. 4.3)
+// the concretized bounds never go to memory: the workgroup that reduces a neuron's coefficients
 // rescales them.
+//
+// Precision.  Coefficient rows stream through fp32 arithmetic on the centre (S) and radius (R)
+// planes.  Per-neuron scalars (ranges, relaxation lines) and the whole bias row are computed in
+// double: the radius of a bias is a second-order quantity (a gap between two lines, a slack between a
+// value and its bound) that is far below the fp32 resolution of the O(1) values it is made from.
 #include <float.h>
 #include "common.h"
 #include "relax.h"
@@ -31,12 +41,17 @@ struct Geo {
   __device__ Geo(int G_, int n4_) : G(G_), NS(kThreads / G_), slot(threadIdx.x / G_), g(threadIdx.x % G_), n4(n4_) {}
 };
 
+// position of a block of rows inside a state: group, rows per group, row, row length, first column
+struct Loc {
+  long grp; int C, T, t, n, c0;
+  __device__ __forceinline__ long off(int r) const { return (((grp * C + r) * (long)T + t) * (long)n) + c0; }
+};
+
 __device__ __forceinline__ float norm_acc(float a, float x, int pn) {
   return pn == TV_NORM_INF ? a + fabsf(x) : (pn == 2 ? fmaf(x, x, a) : fmaxf(a, fabsf(x)));
 }
-__device__ __forceinline__ float norm_comb(float a, float b, int pn) { return pn == 1 ? fmaxf(a, b) : a + b; }
 __device__ __forceinline__ float norm_fin(float a, int pn) { return pn == 2 ? sqrtf(a) : a; }
-__device__ __forceinline__ bool finite_f(float x) { return fabsf(x) <= FLT_MAX; }
+__device__ __forceinline__ bool finite_d(double x) { return fabs(x) <= 3.4028234663852886e38; }
 
 // Combine CNT per-lane partials across the row slots; afterwards every thread holds the totals of its
 // own columns.  red: LDS [4][64][CNT].  `mx`: combine with max instead of +.
@@ -68,8 +83,9 @@ __device__ __forceinline__ void slot_reduce(float (&x)[CNT], const Geo &ge, bool
   }
 }
 
-// Sum (or max) of one value over the G lanes of a row slot (lanes of a slot are consecutive).
-__device__ __forceinline__ float row_sum(float x, int G) {
+// Sum / max of one value over the G lanes of a row slot (lanes of a slot are consecutive).
+template <typename T>
+__device__ __forceinline__ T row_sum(T x, int G) {
   for (int off = 1; off < G; off <<= 1) x += __shfl_xor(x, off);
   return x;
 }
@@ -77,25 +93,38 @@ __device__ __forceinline__ float row_max(float x, int G) {
   for (int off = 1; off < G; off <<= 1) x = fmaxf(x, __shfl_xor(x, off));
   return x;
 }
-// Sum over the whole workgroup of one value held per row slot (same value on the G lanes of a slot).
-__device__ __forceinline__ float block_sum_slots(float x, const Geo &ge, bool mx, float *red) {
-  float v[1] = {x};
-  slot_reduce<1>(v, ge, mx, red);
-  return v[0];
-}
-// Max over all columns of the chunk of a per-column value that every slot holds identically.
-__device__ __forceinline__ float cols_max(float x, int G) { return row_max(x, G); }
-
-// n here is the row stride in floats (the row length when densely packed)
-__device__ __forceinline__ const float4 *row_ptr(const float *base, long row, int C, int r, int n, int c0) {
-  return reinterpret_cast<const float4 *>(base + ((row * C + r) * (long)n + c0));
-}
-__device__ __forceinline__ float4 *row_ptr(float *base, long row, int C, int r, int n, int c0) {
-  return reinterpret_cast<float4 *>(base + ((row * C + r) * (long)n + c0));
-}
 
 #define F4(v, c) (reinterpret_cast<float *>(&(v))[c])
 #define CF4(v, c) (reinterpret_cast<const float *>(&(v))[c])
+
+template <int VEC>
+__device__ __forceinline__ void load_row(const float *S, const float *R, const Loc &lc, int r, const Geo &ge,
+                                         float (&xs)[4 * VEC], float (&xr)[4 * VEC]) {
+  const long o = lc.off(r);
+  const float4 *ps = reinterpret_cast<const float4 *>(S + o), *pr = reinterpret_cast<const float4 *>(R + o);
+#pragma unroll
+  for (int v = 0; v < VEC; ++v) {
+    const int f = ge.g + ge.G * v;
+    float4 s = make_float4(0, 0, 0, 0), rr = s;
+    if (f < ge.n4) { s = ps[f]; rr = pr[f]; }
+#pragma unroll
+    for (int c = 0; c < 4; ++c) { xs[4 * v + c] = CF4(s, c); xr[4 * v + c] = CF4(rr, c); }
+  }
+}
+template <int VEC>
+__device__ __forceinline__ void store_row(float *S, float *R, const Loc &lc, int r, const Geo &ge,
+                                          const float (&ys)[4 * VEC], const float (&yr)[4 * VEC]) {
+  const long o = lc.off(r);
+  float4 *qs = reinterpret_cast<float4 *>(S + o), *qr = reinterpret_cast<float4 *>(R + o);
+#pragma unroll
+  for (int v = 0; v < VEC; ++v) {
+    const int f = ge.g + ge.G * v;
+    if (f < ge.n4) {
+      qs[f] = make_float4(ys[4 * v], ys[4 * v + 1], ys[4 * v + 2], ys[4 * v + 3]);
+      qr[f] = make_float4(yr[4 * v], yr[4 * v + 1], yr[4 * v + 2], yr[4 * v + 3]);
+    }
+  }
+}
 
 // ------------------------------------------------------------------------------------------------
 // Norms of a lower and an upper line of the state down the coefficient axis, for this thread's columns:
@@ -104,11 +133,10 @@ __device__ __forceinline__ float4 *row_ptr(float *base, long row, int C, int r, 
 struct LineCoef { float aS, aR, bS, bR; };
 
 template <int VEC>
-__device__ __forceinline__ void column_norms(const float *S, const float *R, long row, int P, int E, int n, int c0,
+__device__ __forceinline__ void column_norms(const float *S, const float *R, const Loc &lc, int P, int E,
                                              const Geo &ge, int pn, const LineCoef *lines, float *red,
                                              float (&NL)[4 * VEC], float (&NU)[4 * VEC], float (&bS)[4 * VEC],
                                              float (&bR)[4 * VEC]) {
-  const int C = P * E + 1;
 #pragma unroll
   for (int i = 0; i < 4 * VEC; ++i) NL[i] = NU[i] = 0.f;
   for (int pb = 0; pb < P; ++pb) {
@@ -118,124 +146,110 @@ __device__ __forceinline__ void column_norms(const float *S, const float *R, lon
     const int r1 = (pb + 1) * E;
 #pragma unroll 4
     for (int r = pb * E + ge.slot; r < r1; r += ge.NS) {
-      const float4 *ps = row_ptr(S, row, C, r, n, c0), *pr = row_ptr(R, row, C, r, n, c0);
+      float xs[4 * VEC], xr[4 * VEC];
+      load_row<VEC>(S, R, lc, r, ge, xs, xr);
 #pragma unroll
-      for (int v = 0; v < VEC; ++v) {
-        const int f = ge.g + ge.G * v;
-        if (f < ge.n4) {
-          const float4 s = ps[f], rr = pr[f];
-#pragma unroll
-          for (int c = 0; c < 4; ++c) {
-            float a = CF4(s, c) - CF4(rr, c), b = CF4(s, c) + CF4(rr, c);
-            if (lines) {
-              const LineCoef &lc = lines[4 * v + c];
-              a = lc.aS * CF4(s, c) + lc.aR * CF4(rr, c);
-              b = lc.bS * CF4(s, c) + lc.bR * CF4(rr, c);
-            }
-            acc[8 * v + c] = norm_acc(acc[8 * v + c], a, pn);
-            acc[8 * v + 4 + c] = norm_acc(acc[8 * v + 4 + c], b, pn);
-          }
+      for (int i = 0; i < 4 * VEC; ++i) {
+        float a = xs[i] - xr[i], b = xs[i] + xr[i];
+        if (lines) {
+          a = lines[i].aS * xs[i] + lines[i].aR * xr[i];
+          b = lines[i].bS * xs[i] + lines[i].bR * xr[i];
         }
+        acc[2 * i] = norm_acc(acc[2 * i], a, pn);
+        acc[2 * i + 1] = norm_acc(acc[2 * i + 1], b, pn);
       }
     }
     slot_reduce<8 * VEC>(acc, ge, pn == 1, red);
 #pragma unroll
-    for (int v = 0; v < VEC; ++v)
-#pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        NL[4 * v + c] += norm_fin(acc[8 * v + c], pn);
-        NU[4 * v + c] += norm_fin(acc[8 * v + 4 + c], pn);
-      }
+    for (int i = 0; i < 4 * VEC; ++i) {
+      NL[i] += norm_fin(acc[2 * i], pn);
+      NU[i] += norm_fin(acc[2 * i + 1], pn);
+    }
   }
-  const float4 *ps = row_ptr(S, row, C, C - 1, n, c0), *pr = row_ptr(R, row, C, C - 1, n, c0);
-#pragma unroll
-  for (int v = 0; v < VEC; ++v) {
-    const int f = ge.g + ge.G * v;
-    float4 s = make_float4(0, 0, 0, 0), rr = s;
-    if (f < ge.n4) { s = ps[f]; rr = pr[f]; }
-#pragma unroll
-    for (int c = 0; c < 4; ++c) { bS[4 * v + c] = CF4(s, c); bR[4 * v + c] = CF4(rr, c); }
-  }
+  load_row<VEC>(S, R, lc, lc.C - 1, ge, bS, bR);
 }
 
-// Concretized range as (mid, half) in double from centre / radius biases and the two norms:
+// Concretized range in double from centre / radius biases and the two norms:
 //   l = (bS - bR) - e NL,  u = (bS + bR) + e NU   =>   mid = bS + e (NU - NL)/2,  half = bR + e (NU + NL)/2.
 // Both are sums of quantities that fp32 holds accurately, so narrow intervals keep their width.
 __device__ __forceinline__ void range_of(double bS, double bR, double e, double NL, double NU, double &l, double &u) {
   const double mid = bS + 0.5 * e * (NU - NL), half = bR + 0.5 * e * (NU + NL);
   l = mid - half; u = mid + half;
 }
-__device__ __forceinline__ bool finite_d(double x) { return fabs(x) <= 3.4028234663852886e38; }
 
-// Write y = map(x) for every row of the block (bias constants on the last row).
+// Write y = map(x) for every row of the block; the bias row (constants, double arithmetic) included.
 template <int VEC>
-__device__ __forceinline__ void apply_maps(const float *S, const float *R, float *So, float *Ro, long row, int C,
-                                           int n, int c0, const Geo &ge, const Map2 *maps) {
+__device__ __forceinline__ void apply_maps(const float *S, const float *R, float *So, float *Ro, const Loc &lc,
+                                           const Geo &ge, const Map2 *maps) {
+  const int C = lc.C;
 #pragma unroll 4
   for (int r = ge.slot; r < C; r += ge.NS) {
-    const float4 *ps = row_ptr(S, row, C, r, n, c0), *pr = row_ptr(R, row, C, r, n, c0);
-    float4 *qs = row_ptr(So, row, C, r, n, c0), *qr = row_ptr(Ro, row, C, r, n, c0);
-    const bool last = r == C - 1;
+    float xs[4 * VEC], xr[4 * VEC], ys[4 * VEC], yr[4 * VEC];
+    load_row<VEC>(S, R, lc, r, ge, xs, xr);
+    if (r != C - 1) {
 #pragma unroll
-    for (int v = 0; v < VEC; ++v) {
-      const int f = ge.g + ge.G * v;
-      if (f < ge.n4) {
-        const float4 s = ps[f], rr = pr[f];
-        float4 os, orr;
+      for (int i = 0; i < 4 * VEC; ++i) {
+        ys[i] = maps[i].sS * xs[i] + maps[i].sR * xr[i];
+        yr[i] = maps[i].rS * xs[i] + maps[i].rR * xr[i];
+      }
+    } else {
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-          const Map2 &m = maps[4 * v + c];
-          float a = m.sS * CF4(s, c) + m.sR * CF4(rr, c);
-          float b = m.rS * CF4(s, c) + m.rR * CF4(rr, c);
-          if (last) { a += m.sC; b += m.rC; }
-          F4(os, c) = a; F4(orr, c) = b;
-        }
-        qs[f] = os; qr[f] = orr;
+      for (int i = 0; i < 4 * VEC; ++i) {
+        const double s = xs[i], rr = xr[i];
+        ys[i] = (float)(maps[i].sSd * s + maps[i].sRd * rr + maps[i].sCd);
+        yr[i] = (float)(maps[i].rSd * s + maps[i].rRd * rr + maps[i].rCd);
       }
     }
+    store_row<VEC>(So, Ro, lc, r, ge, ys, yr);
   }
 }
 
 // ------------------------------------------------------------------------------------------------
-// Eq. (1).  grid = (rows, column chunks).  mode 0 writes (l, u); mode 1 writes (mid, half).
+// Eq. (1) on the flat [T*n] axis of a group.  grid = (groups, column chunks).
+// mode 0 writes (l, u); mode 1 writes (mid, half) and, if o2 != nullptr, the slack S_b - l = R_b + e NL.
 template <int VEC>
-__global__ __launch_bounds__(kThreads) void concretize_kernel(const float *S, const float *R, int P, int E, int n,
-                                                              int ld, int G, int rps, int pn, const float *eps,
-                                                              float *o0, float *o1, int mode) {
+__global__ __launch_bounds__(kThreads) void concretize_kernel(const float *S, const float *R, int P, int E, int X,
+                                                              int G, int gps, int pn, const float *eps,
+                                                              float *o0, float *o1, float *o2, int mode) {
   __shared__ float red[4 * kWave * 8 * VEC];
-  const long row = blockIdx.x;
   const int chunk = 4 * G * VEC, c0 = blockIdx.y * chunk;
-  const Geo ge(G, min(chunk, n - c0) / 4);
+  const Geo ge(G, min(chunk, X - c0) / 4);
+  const Loc lc{(long)blockIdx.x, P * E + 1, 1, 0, X, c0};
   float NL[4 * VEC], NU[4 * VEC], bS[4 * VEC], bR[4 * VEC];
-  column_norms<VEC>(S, R, row, P, E, ld, c0, ge, pn, nullptr, red, NL, NU, bS, bR);
+  column_norms<VEC>(S, R, lc, P, E, ge, pn, nullptr, red, NL, NU, bS, bR);
   if (ge.slot == 0) {
-    const float e = eps[row / rps];
+    const float e = eps[blockIdx.x / gps];
+    const long o = (long)blockIdx.x * X + c0;
 #pragma unroll
     for (int v = 0; v < VEC; ++v) {
       const int f = ge.g + ge.G * v;
       if (f < ge.n4) {
-        float4 a, b;
+        float4 a, b, c3;
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
           const int i = 4 * v + c;
           if (mode == 0) {
             F4(a, c) = (bS[i] - bR[i]) - e * NL[i];
             F4(b, c) = (bS[i] + bR[i]) + e * NU[i];
+            F4(c3, c) = 0.f;
           } else {
             F4(a, c) = bS[i] + 0.5f * e * (NU[i] - NL[i]);
             F4(b, c) = bR[i] + 0.5f * e * (NU[i] + NL[i]);
+            F4(c3, c) = bR[i] + e * NL[i];
           }
         }
-        reinterpret_cast<float4 *>(o0 + row * n + c0)[f] = a;
-        reinterpret_cast<float4 *>(o1 + row * n + c0)[f] = b;
+        reinterpret_cast<float4 *>(o0 + o)[f] = a;
+        reinterpret_cast<float4 *>(o1 + o)[f] = b;
+        if (mode != 0 && o2) reinterpret_cast<float4 *>(o2 + o)[f] = c3;
       }
     }
   }
 }
 
 // ------------------------------------------------------------------------------------------------
-// Activation: concretize, relax, substitute - one workgroup reads its coefficients for the norm and
-// again (from cache) for the rescale.  GELU adds one mapped-norm pass for the inner product.
+// Activation on the flat [T*n] axis: concretize, relax, substitute - one workgroup reads its
+// coefficients for the norm and again (from cache) for the rescale.  GELU adds one mapped-norm pass
+// for the inner product.
 __device__ __forceinline__ Form gelu_inner(double lx, double ux, double &lb, double &ub) {
   // a = x^2 ; b = k (1 + c3 a) ; returns the form of b and its range
   const double k = 0.7978845608028654, c3 = 0.044715;
@@ -248,17 +262,16 @@ __device__ __forceinline__ Form gelu_inner(double lx, double ux, double &lb, dou
 }
 
 template <int VEC, int ACT>
-__global__ __launch_bounds__(kThreads) void activation_kernel(const float *S, const float *R, int P, int E, int n,
-                                                              int G, int rps, int pn, const float *eps,
+__global__ __launch_bounds__(kThreads) void activation_kernel(const float *S, const float *R, int P, int E, int X,
+                                                              int G, int gps, int pn, const float *eps,
                                                               float *So, float *Ro, int32_t *status) {
   __shared__ float red[4 * kWave * 8 * VEC];
-  const long row = blockIdx.x;
-  const int C = P * E + 1;
   const int chunk = 4 * G * VEC, c0 = blockIdx.y * chunk;
-  const Geo ge(G, min(chunk, n - c0) / 4);
-  const double e = eps[row / rps];
+  const Geo ge(G, min(chunk, X - c0) / 4);
+  const Loc lc{(long)blockIdx.x, P * E + 1, 1, 0, X, c0};
+  const double e = eps[blockIdx.x / gps];
   float NL[4 * VEC], NU[4 * VEC], bS[4 * VEC], bR[4 * VEC];
-  column_norms<VEC>(S, R, row, P, E, n, c0, ge, pn, nullptr, red, NL, NU, bS, bR);
+  column_norms<VEC>(S, R, lc, P, E, ge, pn, nullptr, red, NL, NU, bS, bR);
   Map2 maps[4 * VEC];
   bool bad = false;
   if (ACT != TV_ACT_GELU) {
@@ -272,7 +285,7 @@ __global__ __launch_bounds__(kThreads) void activation_kernel(const float *S, co
     }
   } else {
     Form fg[4 * VEC];
-    LineCoef lc[4 * VEC];
+    LineCoef lcf[4 * VEC];
     double lx[4 * VEC], ux[4 * VEC];
     float xS[4 * VEC], xR[4 * VEC];
 #pragma unroll
@@ -282,11 +295,11 @@ __global__ __launch_bounds__(kThreads) void activation_kernel(const float *S, co
       double lb, ub;
       const Form b = gelu_inner(lx[i], ux[i], lb, ub);
       fg[i] = form_mul(form_identity(), b, lx[i], lb, ub);     // g = x * b
-      lc[i] = LineCoef{(float)(fg[i].pL + fg[i].qL), (float)(fg[i].qL - fg[i].pL), (float)(fg[i].pU + fg[i].qU),
-                       (float)(fg[i].pU - fg[i].qU)};
+      lcf[i] = LineCoef{(float)(fg[i].pL + fg[i].qL), (float)(fg[i].qL - fg[i].pL), (float)(fg[i].pU + fg[i].qU),
+                        (float)(fg[i].pU - fg[i].qU)};
       xS[i] = bS[i]; xR[i] = bR[i];
     }
-    column_norms<VEC>(S, R, row, P, E, n, c0, ge, pn, lc, red, NL, NU, bS, bR);
+    column_norms<VEC>(S, R, lc, P, E, ge, pn, lcf, red, NL, NU, bS, bR);
 #pragma unroll
     for (int i = 0; i < 4 * VEC; ++i) {
       // bias values of g's two lines, as centre / radius in double
@@ -303,57 +316,42 @@ __global__ __launch_bounds__(kThreads) void activation_kernel(const float *S, co
       maps[i] = form_map(form_mul(form_identity(), h, lx[i], 0.5 * lt + 0.5, 0.5 * ut + 0.5));
     }
   }
-  if (bad) status[row / rps] = 1;
-  apply_maps<VEC>(S, R, So, Ro, row, C, n, c0, ge, maps);
+  if (bad) status[blockIdx.x / gps] = 1;
+  apply_maps<VEC>(S, R, So, Ro, lc, ge, maps);
 }
 
 // ------------------------------------------------------------------------------------------------
-// LayerNorm bound.  One workgroup per token; lanes cover all n columns (VEC float4 per lane).
+// LayerNorm bound.  One workgroup per token (g, t); lanes cover all n columns (VEC float4 per lane).
 //   c = x - mean(x)                 one affine map (I - 11^T/n): S_c = S - mean S, R_c = (1-2/n) R + mean R
 //   q = c^2 (relaxed) ; v = mean q + ln_eps ; s = sqrt v ; rho = 1/s ; y = c * rho ; out = gamma y + beta
-// Three sweeps over the block: norms of c; norm of v; output.  All streaming arithmetic is on centre
-// and radius planes (never on lower / upper values, whose difference fp32 cannot hold).
-template <int VEC>
-struct LnRow {
-  float sc[4 * VEC], rc[4 * VEC];   // centred centre / radius planes of one coefficient row
-};
-
-template <int VEC>
-__device__ __forceinline__ void ln_load_row(const float *S, const float *R, long row, int C, int r, int n,
-                                            const Geo &ge, LnRow<VEC> &o) {
-  const float4 *ps = row_ptr(S, row, C, r, n, 0), *pr = row_ptr(R, row, C, r, n, 0);
-  float ss = 0.f, sr = 0.f;
+// Three sweeps over the block: norms of c; norm of v; output.
+template <int VEC, typename T>
+__device__ __forceinline__ void ln_centre(const float (&xs)[4 * VEC], const float (&xr)[4 * VEC], int n, const Geo &ge,
+                                          T (&sc)[4 * VEC], T (&rc)[4 * VEC]) {
+  T ss = 0, sr = 0;
 #pragma unroll
-  for (int v = 0; v < VEC; ++v) {
-    const int f = ge.g + ge.G * v;
-    float4 s = make_float4(0, 0, 0, 0), rr = s;
-    if (f < ge.n4) { s = ps[f]; rr = pr[f]; }
-#pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      o.sc[4 * v + c] = CF4(s, c); o.rc[4 * v + c] = CF4(rr, c);
-      ss += CF4(s, c); sr += CF4(rr, c);
-    }
-  }
-  const float inv = 1.f / (float)n;
-  const float ms = row_sum(ss, ge.G) * inv, mr = row_sum(sr, ge.G) * inv;
-  const float w = 1.f - 2.f * inv;
+  for (int i = 0; i < 4 * VEC; ++i) { ss += (T)xs[i]; sr += (T)xr[i]; }
+  const T inv = (T)1 / (T)n;
+  const T ms = row_sum<T>(ss, ge.G) * inv, mr = row_sum<T>(sr, ge.G) * inv;
+  const T w = (T)1 - (T)2 * inv;
 #pragma unroll
   for (int i = 0; i < 4 * VEC; ++i) {
-    o.sc[i] = o.sc[i] - ms;
-    o.rc[i] = w * o.rc[i] + mr;
+    sc[i] = (T)xs[i] - ms;
+    rc[i] = w * (T)xr[i] + mr;
   }
 }
 
 template <int VEC>
-__global__ __launch_bounds__(kThreads) void layernorm_kernel(const float *S, const float *R, int P, int E, int n,
-                                                             int G, int rps, int pn, const float *eps,
+__global__ __launch_bounds__(kThreads) void layernorm_kernel(const float *S, const float *R, int P, int E, int T_, int n,
+                                                             int G, int gps, int pn, const float *eps,
                                                              const float *gamma, const float *beta, float ln_eps_f,
                                                              float *So, float *Ro, int32_t *status) {
   __shared__ float red[4 * kWave * 8 * VEC];
-  const long row = blockIdx.x;
   const int C = P * E + 1;
   const Geo ge(G, n / 4);
-  const double e = eps[row / rps];
+  const Loc lc{(long)(blockIdx.x / T_), C, T_, (int)(blockIdx.x % T_), n, 0};
+  const int sent = (int)(lc.grp / gps);
+  const double e = eps[sent];
   const double ln_eps = ln_eps_f;
   const float inv = 1.f / (float)n;
   bool colon[VEC];
@@ -361,72 +359,82 @@ __global__ __launch_bounds__(kThreads) void layernorm_kernel(const float *S, con
   for (int v = 0; v < VEC; ++v) colon[v] = ge.g + ge.G * v < ge.n4;
   bool bad = false;
 
-  // ---- sweep 1: concretize c
-  float lc[4 * VEC];         // lower end of c's range (the McCormick multiplier on rho)
-  Map2 mq[4 * VEC];          // centre / radius map of the square relaxation, relative to c
+  // ---- sweep 1: concretize c; square relaxation per column.  With k = l + u the relaxed square is
+  //      S_q = k S_c - (m^2 + l u)/2 [bias],  R_q = |k| R_c + (u - l)^2 / 8 [bias]
+  double cl[4 * VEC], cu[4 * VEC];      // range of c (0, 0 on masked columns)
+  float NLc[4 * VEC];                   // norm of c's lower line: slack S_c_b - l = R_c_b + e NLc
+  float kq[4 * VEC];                    // slope of the square relaxation
   {
-    float NL[4 * VEC], NU[4 * VEC];
+    float NU[4 * VEC];
 #pragma unroll
-    for (int i = 0; i < 4 * VEC; ++i) NL[i] = NU[i] = 0.f;
+    for (int i = 0; i < 4 * VEC; ++i) NLc[i] = NU[i] = 0.f;
     for (int pb = 0; pb < P; ++pb) {
       float acc[8 * VEC];
 #pragma unroll
       for (int i = 0; i < 8 * VEC; ++i) acc[i] = 0.f;
       for (int r = pb * E + ge.slot; r < (pb + 1) * E; r += ge.NS) {
-        LnRow<VEC> x;
-        ln_load_row<VEC>(S, R, row, C, r, n, ge, x);
+        float xs[4 * VEC], xr[4 * VEC], sc[4 * VEC], rc[4 * VEC];
+        load_row<VEC>(S, R, lc, r, ge, xs, xr);
+        ln_centre<VEC, float>(xs, xr, n, ge, sc, rc);
 #pragma unroll
         for (int i = 0; i < 4 * VEC; ++i) {
-          acc[2 * i] = norm_acc(acc[2 * i], x.sc[i] - x.rc[i], pn);
-          acc[2 * i + 1] = norm_acc(acc[2 * i + 1], x.sc[i] + x.rc[i], pn);
+          acc[2 * i] = norm_acc(acc[2 * i], sc[i] - rc[i], pn);
+          acc[2 * i + 1] = norm_acc(acc[2 * i + 1], sc[i] + rc[i], pn);
         }
       }
       slot_reduce<8 * VEC>(acc, ge, pn == 1, red);
 #pragma unroll
       for (int i = 0; i < 4 * VEC; ++i) {
-        NL[i] += norm_fin(acc[2 * i], pn);
+        NLc[i] += norm_fin(acc[2 * i], pn);
         NU[i] += norm_fin(acc[2 * i + 1], pn);
       }
     }
-    LnRow<VEC> x;
-    ln_load_row<VEC>(S, R, row, C, C - 1, n, ge, x);
+    float xs[4 * VEC], xr[4 * VEC];
+    double sc[4 * VEC], rc[4 * VEC];
+    load_row<VEC>(S, R, lc, C - 1, ge, xs, xr);
+    ln_centre<VEC, double>(xs, xr, n, ge, sc, rc);
 #pragma unroll
     for (int i = 0; i < 4 * VEC; ++i) {
-      double l, u;
-      range_of(x.sc[i], x.rc[i], e, NL[i], NU[i], l, u);
-      if (colon[i / 4]) bad |= !(finite_d(l) && finite_d(u));
-      lc[i] = (float)l;
-      mq[i] = form_map(form_sub(form_identity(), relax_square(l, u)));
-      if (!colon[i / 4]) mq[i] = Map2{0, 0, 0, 0, 0, 0};
+      range_of(sc[i], rc[i], e, NLc[i], NU[i], cl[i], cu[i]);
+      if (colon[i / 4]) bad |= !(finite_d(cl[i]) && finite_d(cu[i]));
+      else { cl[i] = 0.0; cu[i] = 0.0; }
+      kq[i] = (float)(cl[i] + cu[i]);
     }
   }
-  // v = mean_d q + ln_eps, as centre / radius per coefficient row
-  auto v_row = [&](const LnRow<VEC> &x, float &vS, float &vR) {
+  // v = mean_d q (+ ln_eps on the bias row) as centre / radius of one coefficient row
+  auto v_row = [&](const float (&sc)[4 * VEC], const float (&rc)[4 * VEC], float &vS, float &vR) {
     float a = 0.f, b = 0.f;
 #pragma unroll
-    for (int i = 0; i < 4 * VEC; ++i) {
-      a += mq[i].sS * x.sc[i] + mq[i].sR * x.rc[i];
-      b += mq[i].rS * x.sc[i] + mq[i].rR * x.rc[i];
-    }
-    vS = row_sum(a, ge.G) * inv;
-    vR = row_sum(b, ge.G) * inv;
+    for (int i = 0; i < 4 * VEC; ++i) { a += kq[i] * sc[i]; b += fabsf(kq[i]) * rc[i]; }
+    vS = row_sum<float>(a, ge.G) * inv;
+    vR = row_sum<float>(b, ge.G) * inv;
   };
-  float cvS = 0.f, cvR = 0.f;   // constants of v on the bias row
+  // the bias row of v in double (constants of the square relaxation included)
+  auto v_bias = [&](const double (&sc)[4 * VEC], const double (&rc)[4 * VEC], double &vS, double &vR) {
+    double a = 0.0, b = 0.0;
 #pragma unroll
-  for (int i = 0; i < 4 * VEC; ++i) { cvS += mq[i].sC; cvR += mq[i].rC; }
-  cvS = row_sum(cvS, ge.G) * inv + ln_eps_f; cvR = row_sum(cvR, ge.G) * inv;
+    for (int i = 0; i < 4 * VEC; ++i) {
+      const double k = cl[i] + cu[i], m = 0.5 * k, w = cu[i] - cl[i];
+      a += k * sc[i] - 0.5 * (m * m + cl[i] * cu[i]);
+      b += fabs(k) * rc[i] + 0.125 * w * w;
+    }
+    vS = row_sum<double>(a, ge.G) / (double)n + ln_eps;
+    vR = row_sum<double>(b, ge.G) / (double)n;
+  };
 
   // ---- sweep 2: concretize v (one neuron per token: each slot accumulates whole rows)
-  double lv, uv;
+  double lv, uv, vSb, vRb;
+  double csb[4 * VEC], crb[4 * VEC];     // centred bias row of the input, kept for sweep 3
   {
     float NLv = 0.f, NUv = 0.f;
     for (int pb = 0; pb < P; ++pb) {
       float acc[2] = {0.f, 0.f};
       for (int r = pb * E + ge.slot; r < (pb + 1) * E; r += ge.NS) {
-        LnRow<VEC> x;
-        ln_load_row<VEC>(S, R, row, C, r, n, ge, x);
+        float xs[4 * VEC], xr[4 * VEC], sc[4 * VEC], rc[4 * VEC];
+        load_row<VEC>(S, R, lc, r, ge, xs, xr);
+        ln_centre<VEC, float>(xs, xr, n, ge, sc, rc);
         float vS, vR;
-        v_row(x, vS, vR);
+        v_row(sc, rc, vS, vR);
         acc[0] = norm_acc(acc[0], vS - vR, pn);
         acc[1] = norm_acc(acc[1], vS + vR, pn);
       }
@@ -434,225 +442,218 @@ __global__ __launch_bounds__(kThreads) void layernorm_kernel(const float *S, con
       NLv += norm_fin(acc[0], pn);
       NUv += norm_fin(acc[1], pn);
     }
-    LnRow<VEC> x;
-    ln_load_row<VEC>(S, R, row, C, C - 1, n, ge, x);
-    float vS, vR;
-    v_row(x, vS, vR);
-    range_of((double)vS + cvS, (double)vR + cvR, e, NLv, NUv, lv, uv);
+    float xs[4 * VEC], xr[4 * VEC];
+    load_row<VEC>(S, R, lc, C - 1, ge, xs, xr);
+    ln_centre<VEC, double>(xs, xr, n, ge, csb, crb);
+    if (!colon[VEC - 1]) {
+#pragma unroll
+      for (int i = 0; i < 4 * VEC; ++i)
+        if (!colon[i / 4]) { csb[i] = 0.0; crb[i] = 0.0; }
+    }
+    v_bias(csb, crb, vSb, vRb);
+    range_of(vSb, vRb, e, NLv, NUv, lv, uv);
     bad |= !(finite_d(lv) && finite_d(uv));
   }
-  // sqrt and reciprocal on the scalar v (double): ranges from the states, clamped where the true value allows
+  // sqrt and reciprocal on the scalar v: ranges from the states, clamped where the true value allows
   const double lvc = fmax(lv, ln_eps), uvc = fmax(uv, lvc);
   const Line2 sq = relax_sqrt(lvc, uvc);
   double ls0, us0;
   line_range(sq, lv, uv, ls0, us0);                 // range of the sqrt state (from the unclamped v state)
   const double ls = fmax(ls0, sqrt(ln_eps)), us = fmax(us0, ls);
-  const Line2 rc = relax_recip(ls, us);
+  const Line2 rcp = relax_recip(ls, us);
   double lr, ur;
-  line_range(rc, ls0, us0, lr, ur);                 // range of rho's state
-  const Map2 mr = form_map(form_sub(form_sub(form_identity(), sq), rc));   // rho relative to v
+  line_range(rcp, ls0, us0, lr, ur);                // range of rho's state
+  const Map2 mr = form_map(form_sub(form_sub(form_identity(), sq), rcp));   // rho relative to v
   const Mul2 mc = mul_coeffs(lr, ur);
-  if (bad) status[row / rps] = 1;
+  if (bad) status[sent] = 1;
 
-  // ---- sweep 3: y = c * rho (x = c_d with multiplier range of rho; y = rho with multiplier lc_d), gamma / beta
-  float gm[4 * VEC], bt[4 * VEC];
+  // ---- sweep 3: y = c * rho (x = c_d with multiplier range of rho; y = rho with multiplier l_c), gamma / beta
+  float gm[4 * VEC], bt[4 * VEC], lcf[4 * VEC];
 #pragma unroll
   for (int v = 0; v < VEC; ++v) {
     const int f = ge.g + ge.G * v;
     float4 a = make_float4(0, 0, 0, 0), b = a;
     if (f < ge.n4) { a = reinterpret_cast<const float4 *>(gamma)[f]; b = reinterpret_cast<const float4 *>(beta)[f]; }
 #pragma unroll
-    for (int c = 0; c < 4; ++c) { gm[4 * v + c] = CF4(a, c); bt[4 * v + c] = CF4(b, c); }
+    for (int c = 0; c < 4; ++c) { gm[4 * v + c] = CF4(a, c); bt[4 * v + c] = CF4(b, c); lcf[4 * v + c] = (float)cl[4 * v + c]; }
   }
-  for (int r = ge.slot; r < C; r += ge.NS) {
-    LnRow<VEC> x;
-    ln_load_row<VEC>(S, R, row, C, r, n, ge, x);
+  for (int r = ge.slot; r < C - 1; r += ge.NS) {
+    float xs[4 * VEC], xr[4 * VEC], sc[4 * VEC], rc[4 * VEC], ys[4 * VEC], yr[4 * VEC];
+    load_row<VEC>(S, R, lc, r, ge, xs, xr);
+    ln_centre<VEC, float>(xs, xr, n, ge, sc, rc);
     float vS, vR;
-    v_row(x, vS, vR);
-    const bool last = r == C - 1;
-    if (last) { vS += cvS; vR += cvR; }
-    float rhoS = mr.sS * vS + mr.sR * vR, rhoR = mr.rS * vS + mr.rR * vR;
-    if (last) { rhoS += mr.sC; rhoR += mr.rC; }
-    float4 *qs = row_ptr(So, row, C, r, n, 0), *qr = row_ptr(Ro, row, C, r, n, 0);
+    v_row(sc, rc, vS, vR);
+    const float rhoS = mr.sS * vS + mr.sR * vR, rhoR = mr.rS * vS + mr.rR * vR;
 #pragma unroll
-    for (int v = 0; v < VEC; ++v) {
-      const int f = ge.g + ge.G * v;
-      float4 os, orr;
-#pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        const int i = 4 * v + c;
-        float yS = mc.a1 * x.sc[i] + mc.a2 * x.rc[i] + lc[i] * rhoS;
-        float yR = mc.a3 * x.sc[i] + mc.a4 * x.rc[i] + fabsf(lc[i]) * rhoR;
-        if (last) { yS -= lc[i] * mc.a1; yR -= lc[i] * mc.a3; }
-        float oS = gm[i] * yS, oR = fabsf(gm[i]) * yR;
-        if (last) oS += bt[i];
-        F4(os, c) = oS;
-        F4(orr, c) = oR;
-      }
-      if (f < ge.n4) { qs[f] = os; qr[f] = orr; }
+    for (int i = 0; i < 4 * VEC; ++i) {
+      const float yS = mc.a1 * sc[i] + mc.a2 * rc[i] + lcf[i] * rhoS;
+      const float yR = mc.a3 * sc[i] + mc.a4 * rc[i] + fabsf(lcf[i]) * rhoR;
+      ys[i] = gm[i] * yS; yr[i] = fabsf(gm[i]) * yR;
     }
+    store_row<VEC>(So, Ro, lc, r, ge, ys, yr);
+  }
+  if (ge.slot == 0) {   // bias row, in double
+    const double rhoS = mr.sSd * vSb + mr.sRd * vRb + mr.sCd, rhoR = mr.rSd * vSb + mr.rRd * vRb + mr.rCd;
+    float ys[4 * VEC], yr[4 * VEC];
+#pragma unroll
+    for (int i = 0; i < 4 * VEC; ++i) {
+      const double slack = crb[i] + e * (double)NLc[i];        // S_c_b - l_c without cancellation
+      const double yS = mc.a1d * csb[i] + mc.a2d * crb[i] + cl[i] * rhoS - cl[i] * mc.a1d;
+      const double yR = mc.a3d * slack + mc.a4d * crb[i] + fabs(cl[i]) * rhoR;
+      ys[i] = (float)((double)gm[i] * yS + (double)bt[i]);
+      yr[i] = (float)(fabs((double)gm[i]) * yR);
+    }
+    store_row<VEC>(So, Ro, lc, C - 1, ge, ys, yr);
   }
 }
 
 // ------------------------------------------------------------------------------------------------
-// Softmax bound over the last axis of the score state, in place.  One workgroup per attention row.
-//   shift by max_j u_j ; e = exp (relaxed) ; sigma = sum_j e ; rho = 1 / sigma ; p = e * rho.
-// Sweeps: norms of s; norm of sigma; output p (and the norm of p's lower line for its concretized bound).
+// Softmax bound over the last axis of the score state, in place.  One workgroup per attention row
+// (g, i).   shift by max_j u_j ; e = exp (relaxed) ; sigma = sum_j e ; rho = 1 / sigma ; p = e * rho.
+// Sweeps: norms of s; norm of sigma; output p (and the norm of p's lower line for its concretized
+// lower bound).  Writes lp (clamped to [0, 1]) and the slack S_p_b - lp.
 template <int VEC>
-__global__ __launch_bounds__(kThreads) void softmax_kernel(float *S, float *R, int P, int E, int n, int G, int rps,
-                                                           int pn, const float *eps, float *lp_out,
-                                                           int32_t *status) {
+__global__ __launch_bounds__(kThreads) void softmax_kernel(float *S, float *R, int P, int E, int T_, int n, int G,
+                                                           int gps, int pn, const float *eps, float *lp_out,
+                                                           float *slack_out, int32_t *status) {
   __shared__ float red[4 * kWave * 8 * VEC];
-  const long row = blockIdx.x;
   const int C = P * E + 1;
   const Geo ge(G, n / 4);
-  const double e = eps[row / rps];
+  const Loc lc{(long)(blockIdx.x / T_), C, T_, (int)(blockIdx.x % T_), n, 0};
+  const int sent = (int)(lc.grp / gps);
+  const double e = eps[sent];
   bool colon[VEC];
 #pragma unroll
   for (int v = 0; v < VEC; ++v) colon[v] = ge.g + ge.G * v < ge.n4;
   bool bad = false;
 
-  float NL[4 * VEC], NU[4 * VEC], bS[4 * VEC], bR[4 * VEC];
-  column_norms<VEC>(S, R, row, P, E, n, 0, ge, pn, nullptr, red, NL, NU, bS, bR);
+  float NLs[4 * VEC], NU[4 * VEC], bS[4 * VEC], bR[4 * VEC];
+  column_norms<VEC>(S, R, lc, P, E, ge, pn, nullptr, red, NLs, NU, bS, bR);
   double ls[4 * VEC], us[4 * VEC];
   float mx = -FLT_MAX;
 #pragma unroll
   for (int i = 0; i < 4 * VEC; ++i) {
-    range_of(bS[i], bR[i], e, NL[i], NU[i], ls[i], us[i]);
+    range_of(bS[i], bR[i], e, NLs[i], NU[i], ls[i], us[i]);
     if (colon[i / 4]) { bad |= !(finite_d(ls[i]) && finite_d(us[i])); mx = fmaxf(mx, (float)us[i]); }
   }
-  const double shift = cols_max(mx, ge.G);
-  // exp relaxation per column on the shifted range (slopes positive); the shift moves s's bias, which
-  // is folded into the constants of the map
-  Map2 me[4 * VEC];
-  float le[4 * VEC];
+  const double shift = row_max(mx, ge.G);
+  // exp relaxation per column on the shifted range (both slopes positive).  With the shift folded into
+  // the intercepts:  S_e = hk S + dk R + hc [bias],  R_e = dk S + hk R + dc [bias]
+  //   hk = (kL+kU)/2, dk = (kU-kL)/2, hc = (cL+cU)/2, dc = (cU-cL)/2
+  double kLe[4 * VEC], hk[4 * VEC], dk[4 * VEC], hc[4 * VEC], dc[4 * VEC], le[4 * VEC];
+  float hkf[4 * VEC], dkf[4 * VEC];
 #pragma unroll
   for (int i = 0; i < 4 * VEC; ++i) {
-    const Line2 ex = relax_exp(ls[i] - shift, us[i] - shift);
-    Line2 sh = ex;
-    sh.cL = ex.cL - ex.kL * shift; sh.cU = ex.cU - ex.kU * shift;
-    me[i] = form_map(form_sub(form_identity(), sh));
-    le[i] = (float)(ex.kL * (ls[i] - shift) + ex.cL);
-    if (!colon[i / 4]) { me[i] = Map2{0, 0, 0, 0, 0, 0}; le[i] = 0.f; }
+    const bool on = colon[i / 4];
+    const Line2 ex = relax_exp(on ? ls[i] - shift : 0.0, on ? us[i] - shift : 0.0);
+    const double cL = ex.cL - ex.kL * shift, cU = ex.cU - ex.kU * shift;
+    kLe[i] = on ? ex.kL : 0.0;
+    hk[i] = on ? 0.5 * (ex.kL + ex.kU) : 0.0; dk[i] = on ? 0.5 * (ex.kU - ex.kL) : 0.0;
+    hc[i] = on ? 0.5 * (cL + cU) : 0.0; dc[i] = on ? 0.5 * (cU - cL) : 0.0;
+    le[i] = on ? ex.kL * (ls[i] - shift) + ex.cL : 0.0;
+    hkf[i] = (float)hk[i]; dkf[i] = (float)dk[i];
   }
-  float csS = 0.f, csR = 0.f;   // constants of sigma on the bias row
-#pragma unroll
-  for (int i = 0; i < 4 * VEC; ++i) { csS += me[i].sC; csR += me[i].rC; }
-  csS = row_sum(csS, ge.G); csR = row_sum(csR, ge.G);
-
-  auto load_row = [&](int r, float (&xs)[4 * VEC], float (&xr)[4 * VEC]) {
-    const float4 *ps = row_ptr((const float *)S, row, C, r, n, 0), *pr = row_ptr((const float *)R, row, C, r, n, 0);
-#pragma unroll
-    for (int v = 0; v < VEC; ++v) {
-      const int f = ge.g + ge.G * v;
-      float4 s = make_float4(0, 0, 0, 0), rr = s;
-      if (f < ge.n4) { s = ps[f]; rr = pr[f]; }
-#pragma unroll
-      for (int c = 0; c < 4; ++c) { xs[4 * v + c] = CF4(s, c); xr[4 * v + c] = CF4(rr, c); }
-    }
-  };
-  // e's planes for one coefficient row (without bias constants) and sigma's planes
+  // e's planes for one coefficient row and sigma's planes
   auto e_row = [&](const float (&xs)[4 * VEC], const float (&xr)[4 * VEC], float (&eS)[4 * VEC], float (&eR)[4 * VEC],
                    float &sgS, float &sgR) {
     float a = 0.f, b = 0.f;
 #pragma unroll
     for (int i = 0; i < 4 * VEC; ++i) {
-      eS[i] = me[i].sS * xs[i] + me[i].sR * xr[i];
-      eR[i] = me[i].rS * xs[i] + me[i].rR * xr[i];
+      eS[i] = hkf[i] * xs[i] + dkf[i] * xr[i];
+      eR[i] = dkf[i] * xs[i] + hkf[i] * xr[i];
       a += eS[i]; b += eR[i];
     }
-    sgS = row_sum(a, ge.G); sgR = row_sum(b, ge.G);
+    sgS = row_sum<float>(a, ge.G); sgR = row_sum<float>(b, ge.G);
   };
+  // the bias row in double
+  double eSb[4 * VEC], eRb[4 * VEC], sgSb, sgRb;
+  {
+    double a = 0.0, b = 0.0;
+#pragma unroll
+    for (int i = 0; i < 4 * VEC; ++i) {
+      eSb[i] = hk[i] * bS[i] + dk[i] * bR[i] + hc[i];
+      eRb[i] = dk[i] * bS[i] + hk[i] * bR[i] + dc[i];
+      a += eSb[i]; b += eRb[i];
+    }
+    sgSb = row_sum<double>(a, ge.G); sgRb = row_sum<double>(b, ge.G);
+  }
 
   // ---- sweep 2: concretize sigma
   double lsg, usg;
   {
-    float NLs = 0.f, NUs = 0.f;
-    float xs[4 * VEC], xr[4 * VEC], eS[4 * VEC], eR[4 * VEC];
+    float NLg = 0.f, NUg = 0.f;
     for (int pb = 0; pb < P; ++pb) {
       float acc[2] = {0.f, 0.f};
       for (int r = pb * E + ge.slot; r < (pb + 1) * E; r += ge.NS) {
-        load_row(r, xs, xr);
+        float xs[4 * VEC], xr[4 * VEC], eS[4 * VEC], eR[4 * VEC];
+        load_row<VEC>(S, R, lc, r, ge, xs, xr);
         float sgS, sgR;
         e_row(xs, xr, eS, eR, sgS, sgR);
         acc[0] = norm_acc(acc[0], sgS - sgR, pn);
         acc[1] = norm_acc(acc[1], sgS + sgR, pn);
       }
       slot_reduce<2>(acc, ge, pn == 1, red);
-      NLs += norm_fin(acc[0], pn); NUs += norm_fin(acc[1], pn);
+      NLg += norm_fin(acc[0], pn); NUg += norm_fin(acc[1], pn);
     }
-    load_row(C - 1, xs, xr);
-    float sgS, sgR;
-    e_row(xs, xr, eS, eR, sgS, sgR);
-    range_of((double)sgS + csS, (double)sgR + csR, e, NLs, NUs, lsg, usg);
+    range_of(sgSb, sgRb, e, NLg, NUg, lsg, usg);
   }
   bad |= !(finite_d(lsg) && finite_d(usg)) || !(lsg >= kRecipMin);
-  const Line2 rc = relax_recip(lsg, usg);
+  const Line2 rcp = relax_recip(lsg, usg);
   double lr, ur;
-  line_range(rc, lsg, usg, lr, ur);
-  const Map2 mr = form_map(form_sub(form_identity(), rc));      // rho relative to sigma
+  line_range(rcp, lsg, usg, lr, ur);
+  const Map2 mr = form_map(form_sub(form_identity(), rcp));      // rho relative to sigma
   const Mul2 mc = mul_coeffs(lr, ur);
-  if (bad) status[row / rps] = 1;
+  if (bad) status[sent] = 1;
 
   // ---- sweep 3: p = e * rho (x = e_j with multiplier range of rho; y = rho with multiplier le_j)
-  float NLp[4 * VEC], pbl[4 * VEC];
+  float lef[4 * VEC], NLp[4 * VEC];
 #pragma unroll
-  for (int i = 0; i < 4 * VEC; ++i) NLp[i] = pbl[i] = 0.f;
-  for (int pb = 0; pb <= P; ++pb) {          // block P is the bias row
+  for (int i = 0; i < 4 * VEC; ++i) { lef[i] = (float)le[i]; NLp[i] = 0.f; }
+  for (int pb = 0; pb < P; ++pb) {
     float acc[4 * VEC];
 #pragma unroll
     for (int i = 0; i < 4 * VEC; ++i) acc[i] = 0.f;
-    const int rbeg = pb < P ? pb * E : C - 1, rend = pb < P ? (pb + 1) * E : C;
-    for (int r = rbeg + ge.slot; r < rend; r += ge.NS) {
-      float xs[4 * VEC], xr[4 * VEC], eS[4 * VEC], eR[4 * VEC];
-      load_row(r, xs, xr);
+    for (int r = pb * E + ge.slot; r < (pb + 1) * E; r += ge.NS) {
+      float xs[4 * VEC], xr[4 * VEC], eS[4 * VEC], eR[4 * VEC], ps[4 * VEC], pr[4 * VEC];
+      load_row<VEC>(S, R, lc, r, ge, xs, xr);
       float sgS, sgR;
       e_row(xs, xr, eS, eR, sgS, sgR);
-      const bool last = r == C - 1;
-      if (last) { sgS += csS; sgR += csR; }
-      float rhoS = mr.sS * sgS + mr.sR * sgR, rhoR = mr.rS * sgS + mr.rR * sgR;
-      if (last) { rhoS += mr.sC; rhoR += mr.rC; }
-      float4 *qs = row_ptr(S, row, C, r, n, 0), *qr = row_ptr(R, row, C, r, n, 0);
+      const float rhoS = mr.sS * sgS + mr.sR * sgR, rhoR = mr.rS * sgS + mr.rR * sgR;
 #pragma unroll
-      for (int v = 0; v < VEC; ++v) {
-        const int f = ge.g + ge.G * v;
-        float4 os, orr;
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-          const int i = 4 * v + c;
-          float es = eS[i], er = eR[i];
-          if (last) { es += me[i].sC; er += me[i].rC; }
-          float pS = mc.a1 * es + mc.a2 * er + le[i] * rhoS;
-          float pR = mc.a3 * es + mc.a4 * er + fabsf(le[i]) * rhoR;
-          if (last) { pS -= le[i] * mc.a1; pR -= le[i] * mc.a3; pbl[i] = pS - pR; }
-          else acc[i] = norm_acc(acc[i], pS - pR, pn);
-          F4(os, c) = pS;
-          F4(orr, c) = pR;
-        }
-        if (f < ge.n4) { qs[f] = os; qr[f] = orr; }
+      for (int i = 0; i < 4 * VEC; ++i) {
+        ps[i] = mc.a1 * eS[i] + mc.a2 * eR[i] + lef[i] * rhoS;
+        pr[i] = mc.a3 * eS[i] + mc.a4 * eR[i] + fabsf(lef[i]) * rhoR;
+        acc[i] = norm_acc(acc[i], ps[i] - pr[i], pn);
       }
+      store_row<VEC>(S, R, lc, r, ge, ps, pr);
     }
-    if (pb < P) {
-      slot_reduce<4 * VEC>(acc, ge, pn == 1, red);
+    slot_reduce<4 * VEC>(acc, ge, pn == 1, red);
 #pragma unroll
-      for (int i = 0; i < 4 * VEC; ++i) NLp[i] += norm_fin(acc[i], pn);
-    }
+    for (int i = 0; i < 4 * VEC; ++i) NLp[i] += norm_fin(acc[i], pn);
   }
-  // concretized lower bound of p, clamped to [0, 1]; the bias row was handled by slot 0
-  {
-    slot_reduce<4 * VEC>(pbl, ge, false, red);      // only one slot holds non-zero values
-    if (ge.slot == 0) {
+  if (ge.slot == 0) {   // bias row, in double; concretized lower bound of p and its slack
+    const double rhoS = mr.sSd * sgSb + mr.sRd * sgRb + mr.sCd, rhoR = mr.rSd * sgSb + mr.rRd * sgRb + mr.rCd;
+    float ps[4 * VEC], pr[4 * VEC], lpv[4 * VEC], slv[4 * VEC];
 #pragma unroll
-      for (int v = 0; v < VEC; ++v) {
-        const int f = ge.g + ge.G * v;
-        float4 o;
+    for (int i = 0; i < 4 * VEC; ++i) {
+      const double slack_e = eRb[i] + e * kLe[i] * (double)NLs[i];     // e_S_b - le without cancellation
+      const double pS = mc.a1d * eSb[i] + mc.a2d * eRb[i] + le[i] * rhoS - le[i] * mc.a1d;
+      const double pR = mc.a3d * slack_e + mc.a4d * eRb[i] + fabs(le[i]) * rhoR;
+      const double half = pR + e * (double)NLp[i];                     // S_p_b - (lower bound of p)
+      const double lraw = pS - half;
+      const double lcl = fmin(fmax(lraw, 0.0), 1.0);
+      ps[i] = (float)pS; pr[i] = (float)pR;
+      lpv[i] = (float)lcl;
+      slv[i] = (float)(lraw == lcl ? half : pS - lcl);
+    }
+    store_row<VEC>(S, R, lc, C - 1, ge, ps, pr);
+    const long o = (lc.grp * T_ + lc.t) * (long)n;
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-          const int i = 4 * v + c;
-          const float l = pbl[i] - (float)e * NLp[i];
-          F4(o, c) = fminf(fmaxf(l, 0.f), 1.f);
-        }
-        if (f < ge.n4) reinterpret_cast<float4 *>(lp_out + row * n)[f] = o;
+    for (int v = 0; v < VEC; ++v) {
+      const int f = ge.g + ge.G * v;
+      if (f < ge.n4) {
+        reinterpret_cast<float4 *>(lp_out + o)[f] = make_float4(lpv[4 * v], lpv[4 * v + 1], lpv[4 * v + 2], lpv[4 * v + 3]);
+        reinterpret_cast<float4 *>(slack_out + o)[f] = make_float4(slv[4 * v], slv[4 * v + 1], slv[4 * v + 2], slv[4 * v + 3]);
       }
     }
   }
@@ -669,14 +670,14 @@ __global__ void zero_kernel(float4 *p, size_t count4) {
   for (; i < count4; i += stride) p[i] = make_float4(0.f, 0.f, 0.f, 0.f);
 }
 
-int pow2_le(int x) { int p = 1; while (p * 2 <= x) p *= 2; return p; }
 int pow2_ge(int x) { int p = 1; while (p < x) p *= 2; return p; }
 int gcd(int a, int b) { while (b) { int t = a % b; a = b; b = t; } return a; }
 
-// chunked geometry for per-column kernels: G = gcd(n/4, 64) lanes, one float4 per lane
-void chunk_geo(int n, int &G, int &nchunks) {
-  G = gcd(n / 4, 64);
-  nchunks = (n + 4 * G - 1) / (4 * G);
+// chunked geometry for per-column kernels: G = gcd(X/4, 64) lanes, one float4 per lane
+void chunk_geo(long X, int &G, int &nchunks) {
+  const int m = (int)((X / 4) % 64);
+  G = m == 0 ? 64 : gcd(m, 64);
+  nchunks = (int)((X + 4 * G - 1) / (4 * G));
 }
 // whole-row geometry: G lanes (power of two), VEC float4 per lane
 int row_geo(int n, int &G, int &VEC) {
@@ -685,66 +686,69 @@ int row_geo(int n, int &G, int &VEC) {
   return VEC <= kMaxVec;
 }
 
-int check_common(const void *S, const void *R, int rows, int P, int E, int n, int rps, int pn, const float *eps) {
+int check_common(const void *S, const void *R, int groups, int P, int E, int T, int n, int gps, int pn,
+                 const float *eps) {
   TV_REQUIRE(S && R && eps, TV_E_NULL, "null state or eps pointer");
-  TV_REQUIRE(rows > 0 && P >= 0 && P <= kMaxP && E > 0 && n > 0 && n % 4 == 0 && rps > 0 && rows % rps == 0,
-             TV_E_SHAPE, "bad shape rows=%d P=%d E=%d n=%d rows_per_sentence=%d", rows, P, E, n, rps);
+  TV_REQUIRE(groups > 0 && P >= 0 && P <= kMaxP && E > 0 && T > 0 && n > 0 && n % 4 == 0 && gps > 0 &&
+                 groups % gps == 0 && (long)T * n < (1L << 31),
+             TV_E_SHAPE, "bad shape groups=%d P=%d E=%d T=%d n=%d groups_per_sentence=%d", groups, P, E, T, n, gps);
   TV_REQUIRE(norm_ok(pn), TV_E_NORM, "p_norm must be 1, 2 or TV_NORM_INF, got %d", pn);
   return TV_OK;
 }
 
 }  // namespace
 
-int concretize(CState x, int rows, int P, int E, int n, int ld, int rps, int pn, const float *eps, float *l,
-               float *u, int mode, hipStream_t st) {
-  if (int rc = check_common(x.S, x.R, rows, P, E, n, rps, pn, eps)) return rc;
-  TV_REQUIRE(l && u, TV_E_NULL, "null output");
-  TV_REQUIRE(ld >= n && ld % 4 == 0, TV_E_SHAPE, "concretize: row stride %d must be a multiple of 4 and >= %d", ld, n);
+int concretize(CState x, int groups, int P, int E, int T, int n, int gps, int pn, const float *eps, float *o0,
+               float *o1, float *o2, int mode, hipStream_t st) {
+  if (int rc = check_common(x.S, x.R, groups, P, E, T, n, gps, pn, eps)) return rc;
+  TV_REQUIRE(o0 && o1, TV_E_NULL, "null output");
+  const long X = (long)T * n;
   int G, nch;
-  chunk_geo(n, G, nch);
+  chunk_geo(X, G, nch);
   const double C = (double)P * E + 1;
-  ProfScope prof(K_CONCRETIZE, st, 4.0 * rows * C * n, 8.0 * rows * C * n + 8.0 * rows * n);
-  hipLaunchKernelGGL((concretize_kernel<1>), dim3(rows, nch), dim3(kThreads), 0, st, x.S, x.R, P, E, n, ld, G, rps,
-                     pn, eps, l, u, mode);
+  ProfScope prof(K_CONCRETIZE, st, 4.0 * groups * C * X, 8.0 * groups * C * X + 8.0 * groups * X);
+  hipLaunchKernelGGL((concretize_kernel<1>), dim3(groups, nch), dim3(kThreads), 0, st, x.S, x.R, P, E, (int)X, G, gps,
+                     pn, eps, o0, o1, o2, mode);
   TV_HIP(hipGetLastError());
   return TV_OK;
 }
 
-int activation(int act, CState x, int rows, int P, int E, int n, int rps, int pn, const float *eps, State y,
+int activation(int act, CState x, int groups, int P, int E, int T, int n, int gps, int pn, const float *eps, State y,
                int32_t *status, hipStream_t st) {
-  if (int rc = check_common(x.S, x.R, rows, P, E, n, rps, pn, eps)) return rc;
+  if (int rc = check_common(x.S, x.R, groups, P, E, T, n, gps, pn, eps)) return rc;
   TV_REQUIRE(y.S && y.R && status, TV_E_NULL, "null output");
   TV_REQUIRE(act == TV_ACT_RELU || act == TV_ACT_TANH || act == TV_ACT_GELU, TV_E_ARG, "unknown activation %d", act);
+  const long X = (long)T * n;
   int G, nch;
-  chunk_geo(n, G, nch);
+  chunk_geo(X, G, nch);
   const double C = (double)P * E + 1;
-  ProfScope prof(K_ACTIVATION, st, 12.0 * rows * C * n, 16.0 * rows * C * n);
-  dim3 grid(rows, nch), block(kThreads);
+  ProfScope prof(K_ACTIVATION, st, 12.0 * groups * C * X, 16.0 * groups * C * X);
+  dim3 grid(groups, nch), block(kThreads);
   if (act == TV_ACT_RELU)
-    hipLaunchKernelGGL((activation_kernel<1, TV_ACT_RELU>), grid, block, 0, st, x.S, x.R, P, E, n, G, rps, pn, eps,
+    hipLaunchKernelGGL((activation_kernel<1, TV_ACT_RELU>), grid, block, 0, st, x.S, x.R, P, E, (int)X, G, gps, pn, eps,
                        y.S, y.R, status);
   else if (act == TV_ACT_TANH)
-    hipLaunchKernelGGL((activation_kernel<1, TV_ACT_TANH>), grid, block, 0, st, x.S, x.R, P, E, n, G, rps, pn, eps,
+    hipLaunchKernelGGL((activation_kernel<1, TV_ACT_TANH>), grid, block, 0, st, x.S, x.R, P, E, (int)X, G, gps, pn, eps,
                        y.S, y.R, status);
   else
-    hipLaunchKernelGGL((activation_kernel<1, TV_ACT_GELU>), grid, block, 0, st, x.S, x.R, P, E, n, G, rps, pn, eps,
+    hipLaunchKernelGGL((activation_kernel<1, TV_ACT_GELU>), grid, block, 0, st, x.S, x.R, P, E, (int)X, G, gps, pn, eps,
                        y.S, y.R, status);
   TV_HIP(hipGetLastError());
   return TV_OK;
 }
 
-int layernorm(CState x, int rows, int P, int E, int n, int rps, int pn, const float *eps, const float *gamma,
+int layernorm(CState x, int groups, int P, int E, int T, int n, int gps, int pn, const float *eps, const float *gamma,
               const float *beta, float ln_eps, State y, int32_t *status, hipStream_t st) {
-  if (int rc = check_common(x.S, x.R, rows, P, E, n, rps, pn, eps)) return rc;
+  if (int rc = check_common(x.S, x.R, groups, P, E, T, n, gps, pn, eps)) return rc;
   TV_REQUIRE(y.S && y.R && status && gamma && beta, TV_E_NULL, "null pointer");
   TV_REQUIRE(ln_eps > 0.f, TV_E_ARG, "ln_eps must be positive");
   int G, VEC;
   TV_REQUIRE(row_geo(n, G, VEC), TV_E_SHAPE, "layernorm width %d exceeds %d", n, 4 * 64 * kMaxVec);
-  const double C = (double)P * E + 1;
+  const double C = (double)P * E + 1, rows = (double)groups * T;
   ProfScope prof(K_LAYERNORM, st, 40.0 * rows * C * n, 16.0 * rows * C * n);
-  dim3 grid(rows), block(kThreads);
-#define LN_LAUNCH(V)                                                                                            \
-  hipLaunchKernelGGL((layernorm_kernel<V>), grid, block, 0, st, x.S, x.R, P, E, n, G, rps, pn, eps, gamma, beta, \
+  dim3 grid((unsigned)(groups * T)), block(kThreads);
+#define LN_LAUNCH(V)                                                                                               \
+  hipLaunchKernelGGL((layernorm_kernel<V>), grid, block, 0, st, x.S, x.R, P, E, T, n, G, gps, pn, eps, gamma, beta, \
                      ln_eps, y.S, y.R, status)
   switch (VEC) {
     case 1: LN_LAUNCH(1); break;
@@ -757,17 +761,18 @@ int layernorm(CState x, int rows, int P, int E, int n, int rps, int pn, const fl
   return TV_OK;
 }
 
-int softmax(State s, int rows, int P, int E, int L, int rps, int pn, const float *eps, float *lp, int32_t *status,
-            hipStream_t st) {
-  if (int rc = check_common(s.S, s.R, rows, P, E, L, rps, pn, eps)) return rc;
-  TV_REQUIRE(lp && status, TV_E_NULL, "null pointer");
+int softmax(State s, int groups, int P, int E, int T, int n, int gps, int pn, const float *eps, float *lp,
+            float *slack, int32_t *status, hipStream_t st) {
+  if (int rc = check_common(s.S, s.R, groups, P, E, T, n, gps, pn, eps)) return rc;
+  TV_REQUIRE(lp && slack && status, TV_E_NULL, "null pointer");
   int G, VEC;
-  TV_REQUIRE(row_geo(L, G, VEC), TV_E_SHAPE, "softmax width %d exceeds %d", L, 4 * 64 * kMaxVec);
-  const double C = (double)P * E + 1;
-  ProfScope prof(K_SOFTMAX, st, 40.0 * rows * C * L, 16.0 * rows * C * L);
-  dim3 grid(rows), block(kThreads);
-#define SM_LAUNCH(V) \
-  hipLaunchKernelGGL((softmax_kernel<V>), grid, block, 0, st, s.S, s.R, P, E, L, G, rps, pn, eps, lp, status)
+  TV_REQUIRE(row_geo(n, G, VEC), TV_E_SHAPE, "softmax width %d exceeds %d", n, 4 * 64 * kMaxVec);
+  const double C = (double)P * E + 1, rows = (double)groups * T;
+  ProfScope prof(K_SOFTMAX, st, 40.0 * rows * C * n, 16.0 * rows * C * n);
+  dim3 grid((unsigned)(groups * T)), block(kThreads);
+#define SM_LAUNCH(V)                                                                                          \
+  hipLaunchKernelGGL((softmax_kernel<V>), grid, block, 0, st, s.S, s.R, P, E, T, n, G, gps, pn, eps, lp, slack, \
+                     status)
   switch (VEC) {
     case 1: SM_LAUNCH(1); break;
     case 2: SM_LAUNCH(2); break;

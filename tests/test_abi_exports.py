@@ -49,7 +49,7 @@ def test_argument_errors_without_gpu(lib):
     assert b"null" in lib.tv_last_error()
     assert lib.tv_workspace_query(None, 1, 8, 1, None, None) == -1
     assert lib.tv_verify(*([None] * 17)) == -1
-    assert lib.tv_op_concretize(None, None, 1, 1, 4, 4, 1, 2, None, None, None, None) == -1
+    assert lib.tv_op_concretize(None, None, 1, 1, 4, 1, 4, 1, 2, None, None, None, None) == -1
     one = ctypes.c_void_p(16)   # non-null dummy: shape checks come before any launch
-    assert lib.tv_op_concretize(one, one, 1, 1, 4, 6, 1, 2, one, one, one, None) == -2     # n % 4 != 0
-    assert lib.tv_op_concretize(one, one, 1, 1, 4, 8, 1, 7, one, one, one, None) == -3     # bad norm
+    assert lib.tv_op_concretize(one, one, 1, 1, 4, 1, 6, 1, 2, one, one, one, None) == -2     # n % 4 != 0
+    assert lib.tv_op_concretize(one, one, 1, 1, 4, 1, 8, 1, 7, one, one, one, None) == -3     # bad norm

@@ -1,8 +1,9 @@
 """GPU parity of the single-operator entry points against the float64 oracle.
 
-Both sides start from the same fp32-rounded random states.  Sizes span several tiles and ragged
-tails of every kernel.  Tolerance (written here, derived in the design document):
-    |gpu - oracle| <= 1e-4 * |oracle| + 2e-6 * max|oracle tensor|
+Both sides start from the same fp32-rounded random states (layout [G, C, T, n]).  Sizes span several
+tiles and ragged tails of every kernel.  States are compared as the library stores them, on the
+centre and radius planes (tv_testutil.assert_state_close):
+    |gpu - oracle| <= rtol * |oracle| + atol_scale * max|plane part|,   rtol 1e-4 .. 3e-4
 """
 import numpy as np
 import pytest
@@ -12,7 +13,6 @@ pytestmark = pytest.mark.gpu
 torch = pytest.importorskip("torch")
 
 from oracle import bounds as B  # noqa: E402
-from oracle import relaxations as rx  # noqa: E402
 from oracle import verifier as V  # noqa: E402
 from oracle.verifier import _Ctx  # noqa: E402
 from tv_testutil import assert_close, assert_state_close, quantize, random_state, to_planes  # noqa: E402
@@ -31,8 +31,8 @@ def dev(a, dtype=torch.float32):
     return torch.as_tensor(np.ascontiguousarray(a), dtype=dtype, device="cuda:0")
 
 
-def planes_dev(X):
-    S, R = to_planes(X)
+def planes_dev(X, G):
+    S, R = to_planes(X, G)
     return dev(S), dev(R)
 
 
@@ -44,47 +44,49 @@ NORMS = [0, 2, 1]
 
 
 @pytest.mark.parametrize("p", NORMS)
-@pytest.mark.parametrize("rows,P,E,n,rps", [(6, 1, 64, 64, 3), (4, 2, 40, 8, 2), (3, 1, 36, 768, 1), (2, 3, 8, 200, 1),
-                                            (5, 1, 129, 32, 5)])
-def test_concretize(tv, p, rows, P, E, n, rps):
-    rng = np.random.default_rng(rows * 100 + n + p)
-    eps_b = rng.uniform(0.01, 0.5, rows // rps)
-    X = quantize(random_state(rng, (rows, n), P, E, 0.3, p))
-    S, R = planes_dev(X)
-    l, u = tv.op_concretize(S, R, P, E, rps, p, dev(eps_b))
-    e = np.repeat(eps_b.astype(np.float32).astype(np.float64), rps)[:, None]
+@pytest.mark.parametrize("G,T,P,E,n,gps", [(2, 3, 1, 64, 64, 1), (4, 1, 2, 40, 8, 2), (1, 3, 1, 36, 768, 1),
+                                           (2, 1, 3, 8, 200, 1), (5, 2, 1, 129, 32, 5), (1, 32, 1, 24, 384, 1)])
+def test_concretize(tv, p, G, T, P, E, n, gps):
+    rng = np.random.default_rng(G * 100 + n + p)
+    eps_b = rng.uniform(0.01, 0.5, G // gps)
+    X = quantize(random_state(rng, (G * T, n), P, E, 0.3, p), G)
+    S, R = planes_dev(X, G)
+    l, u = tv.op_concretize(S, R, P, E, gps, p, dev(eps_b))
+    e = np.repeat(eps_b.astype(np.float32).astype(np.float64), gps * T)[:, None]
     lo = X.lb - e * B.block_dual_norm(X.lw, P, p)
     up = X.ub + e * B.block_dual_norm(X.uw, P, p)
-    assert_close(l.cpu().numpy(), lo, "l"); assert_close(u.cpu().numpy(), up, "u")
+    assert_close(l.cpu().numpy().reshape(G * T, n), lo, "l"); assert_close(u.cpu().numpy().reshape(G * T, n), up, "u")
 
 
 def test_concretize_no_perturbation_rows(tv):
     """P = 0 (bias row only): bounds are the bias values."""
     rng = np.random.default_rng(1)
-    S = rng.standard_normal((3, 1, 16)).astype(np.float32); R = np.abs(rng.standard_normal((3, 1, 16))).astype(np.float32)
+    S = rng.standard_normal((3, 1, 2, 16)).astype(np.float32)
+    R = np.abs(rng.standard_normal((3, 1, 2, 16))).astype(np.float32)
     l, u = tv.op_concretize(dev(S), dev(R), 0, 16, 1, 2, dev(np.ones(3)))
     np.testing.assert_allclose(l.cpu().numpy(), (S - R)[:, 0]); np.testing.assert_allclose(u.cpu().numpy(), (S + R)[:, 0])
 
 
-@pytest.mark.parametrize("rows,P,E,K,N,bias,add", [
-    (3, 1, 40, 40, 72, True, False),       # ragged M, N tails
-    (2, 2, 64, 64, 192, True, True),       # two N tiles, residual
-    (1, 1, 96, 256, 64, False, False),     # several K stages, N = 64 tile
-    (5, 1, 33, 36, 20, True, True),        # K tail (36 = 32 + 4), tiny N
-    (2, 1, 300, 128, 128, True, False),    # > 2 M tiles
+@pytest.mark.parametrize("G,T,P,E,K,N,bias,add", [
+    (1, 3, 1, 40, 40, 72, True, False),       # ragged M, N tails
+    (2, 2, 2, 64, 64, 192, True, True),       # two N tiles, residual, bias rows of two groups
+    (1, 1, 1, 96, 256, 64, False, False),     # several K stages, N = 64 tile
+    (5, 1, 1, 33, 36, 20, True, True),        # K tail (36 = 32 + 4), tiny N
+    (1, 2, 1, 300, 128, 128, True, False),    # > 2 M tiles
+    (2, 5, 1, 64, 64, 384, True, False),      # T not a power of two, three N tiles
 ])
-def test_affine(tv, rows, P, E, K, N, bias, add):
-    rng = np.random.default_rng(rows + K + N)
-    X = quantize(random_state(rng, (rows, K), P, E, 0.3, 2))
+def test_affine(tv, G, T, P, E, K, N, bias, add):
+    rng = np.random.default_rng(G + T + K + N)
+    X = quantize(random_state(rng, (G * T, K), P, E, 0.3, 2), G)
     W = rng.standard_normal((N, K)).astype(np.float32)
     c = rng.standard_normal(N).astype(np.float32) if bias else None
     Y = B.affine(X, W.astype(np.float64), None if c is None else c.astype(np.float64))
     addp = None
     if add:
-        A = quantize(random_state(rng, (rows, N), P, E, 0.3, 2))
+        A = quantize(random_state(rng, (G * T, N), P, E, 0.3, 2), G)
         Y = B.add(Y, A)
-        addp = planes_dev(A)
-    S, R = planes_dev(X)
+        addp = planes_dev(A, G)
+    S, R = planes_dev(X, G)
     out = tv.op_affine(S, R, P, E, dev(W), None if c is None else dev(c), addp)
     assert_state_close(host(out), Y, "affine")
 
@@ -93,33 +95,49 @@ def test_affine(tv, rows, P, E, K, N, bias, add):
 @pytest.mark.parametrize("act,name", [(0, "relu"), (1, "tanh"), (2, "gelu")])
 def test_activation(tv, act, name, p):
     rng = np.random.default_rng(7 + act + 10 * p)
-    rows, P, E, n, rps = 6, 2, 24, 192, 2
+    G, T, P, E, n, gps = 2, 3, 2, 24, 192, 1
     eps = 0.2
-    X = quantize(random_state(rng, (rows, n), P, E, eps, p, wscale=0.5))
-    # include one-sided and nearly degenerate neurons
+    X = quantize(random_state(rng, (G * T, n), P, E, eps, p, wscale=0.5), G)
+    # include one-sided neurons
     X.lb[:, :8] += 6.0; X.ub[:, :8] += 6.0
     X.lb[:, 8:16] -= 6.0; X.ub[:, 8:16] -= 6.0
-    X = quantize(X)
+    X = quantize(X, G)
     ctx = _Ctx(eps, P, p)
     ref = V.activation_bound(X, act, ctx)
-    S, R = planes_dev(X)
-    Sy, Ry, status = tv.op_activation(act, S, R, P, E, rps, p, dev(np.full(rows // rps, eps)))
+    S, R = planes_dev(X, G)
+    Sy, Ry, status = tv.op_activation(act, S, R, P, E, gps, p, dev(np.full(G // gps, eps)))
     assert int(status.sum()) == 0
     assert_state_close(host((Sy, Ry)), ref, name, rtol=2e-4, atol_scale=5e-6)
     # in place gives the same result
-    S2, R2, _ = tv.op_activation(act, S, R, P, E, rps, p, dev(np.full(rows // rps, eps)), inplace=True)
+    S2, R2, _ = tv.op_activation(act, S, R, P, E, gps, p, dev(np.full(G // gps, eps)), inplace=True)
     assert torch.equal(S2, Sy) and torch.equal(R2, Ry)
+
+
+@pytest.mark.parametrize("act,name", [(0, "relu"), (1, "tanh"), (2, "gelu")])
+def test_activation_narrow_intervals(tv, act, name):
+    """Intervals far narrower than fp32 resolves on their end points (width 1e-6 of the value): the
+    radius plane of the output must still match (per-neuron scalars are computed in double)."""
+    rng = np.random.default_rng(31 + act)
+    G, T, P, E, n = 1, 2, 1, 16, 64
+    eps = 1e-6
+    X = quantize(random_state(rng, (G * T, n), P, E, eps, 2, wscale=0.3, slack=1e-7, spread=1e-3), G)
+    ref = V.activation_bound(X, act, _Ctx(eps, P, 2))
+    Sy, Ry, _ = tv.op_activation(act, *planes_dev(X, G), P, E, 1, 2, dev(np.full(G, eps)))
+    assert_state_close(host((Sy, Ry)), ref, name + "/narrow", rtol=2e-4, atol_scale=1e-6)
+    # the radius plane alone, relative to its own scale
+    _, r_ref = to_planes(ref, G)
+    r_gpu = Ry.cpu().numpy()
+    assert np.abs(r_gpu[:, -1] - r_ref[:, -1]).max() <= 2e-4 * np.abs(r_ref[:, -1]).max() + 1e-12
 
 
 def test_activation_eps0_is_exact(tv):
     """Degenerate ranges (eps = 0, lower == upper): tangent rule, output = f(x) with the Jacobian slope."""
     rng = np.random.default_rng(3)
-    rows, P, E, n = 2, 1, 16, 64
-    X = random_state(rng, (rows, n), P, E, 0.0, 2, slack=0.0, spread=0.0)
-    X = quantize(X)
+    G, T, P, E, n = 1, 2, 1, 16, 64
+    X = quantize(random_state(rng, (G * T, n), P, E, 0.0, 2, slack=0.0, spread=0.0), G)
     for act in (1, 2):
         ref = V.activation_bound(X, act, _Ctx(0.0, P, 2))
-        Sy, Ry, _ = tv.op_activation(act, *planes_dev(X), P, E, rows, 2, dev(np.zeros(1)))
+        Sy, Ry, _ = tv.op_activation(act, *planes_dev(X, G), P, E, 1, 2, dev(np.zeros(1)))
         assert_state_close(host((Sy, Ry)), ref, f"act{act}@0", rtol=2e-4, atol_scale=5e-6)
 
 
@@ -127,30 +145,35 @@ def test_activation_eps0_is_exact(tv):
 @pytest.mark.parametrize("n", [64, 128, 320, 768])
 def test_layernorm(tv, n, p):
     rng = np.random.default_rng(n + p)
-    rows, P, E, rps = 4, 1, 20, 2
+    G, T, P, E, gps = 2, 2, 1, 20, 1
     eps = 0.05
-    X = quantize(random_state(rng, (rows, n), P, E, eps, p, wscale=0.3, slack=0.05))
+    X = quantize(random_state(rng, (G * T, n), P, E, eps, p, wscale=0.3, slack=0.05), G)
     gamma = (rng.standard_normal(n) * 0.5 + 0.8).astype(np.float32)
     beta = (rng.standard_normal(n) * 0.1).astype(np.float32)
     ref = V.layernorm_bound(X, gamma.astype(np.float64), beta.astype(np.float64), 1e-5, _Ctx(eps, P, p))
-    Sy, Ry, status = tv.op_layernorm(*planes_dev(X), P, E, rps, p, dev(np.full(rows // rps, eps)), dev(gamma),
+    Sy, Ry, status = tv.op_layernorm(*planes_dev(X, G), P, E, gps, p, dev(np.full(G // gps, eps)), dev(gamma),
                                      dev(beta), 1e-5)
     assert int(status.sum()) == 0
     assert_state_close(host((Sy, Ry)), ref, "layernorm", rtol=2e-4, atol_scale=1e-5)
 
 
-@pytest.mark.parametrize("p", NORMS)
-@pytest.mark.parametrize("B_,L,H,D,P", [(2, 8, 4, 64, 1), (1, 32, 4, 128, 1), (2, 12, 2, 40, 2), (1, 64, 2, 128, 1)])
-def test_attention_stages(tv, B_, L, H, D, P, p):
-    rng = np.random.default_rng(B_ + L + D + p)
-    eps = {0: 0.008, 2: 0.05, 1: 0.08}[p]     # comparable range widths for the three balls
+def test_layernorm_narrow_intervals(tv):
+    rng = np.random.default_rng(77)
+    G, T, P, E, n = 1, 3, 1, 16, 128
+    eps = 1e-6
+    X = quantize(random_state(rng, (G * T, n), P, E, eps, 2, wscale=0.3, slack=1e-7, spread=1e-3), G)
+    gamma = (rng.standard_normal(n) * 0.5 + 0.8).astype(np.float32)
+    beta = (rng.standard_normal(n) * 0.1).astype(np.float32)
+    ref = V.layernorm_bound(X, gamma.astype(np.float64), beta.astype(np.float64), 1e-5, _Ctx(eps, P, 2))
+    Sy, Ry, _ = tv.op_layernorm(*planes_dev(X, G), P, E, 1, 2, dev(np.full(G, eps)), dev(gamma), dev(beta), 1e-5)
+    assert_state_close(host((Sy, Ry)), ref, "layernorm/narrow", rtol=2e-4, atol_scale=1e-6)
+    _, r_ref = to_planes(ref, G)
+    r_gpu = Ry.cpu().numpy()
+    assert np.abs(r_gpu[:, -1] - r_ref[:, -1]).max() <= 5e-4 * np.abs(r_ref[:, -1]).max() + 1e-12
+
+
+def attention_reference(Q, K, Vv, B_, L, H, D, ctx):
     dh = D // H
-    mk = lambda: quantize(random_state(rng, (B_ * L, D), P, D, eps, p, wscale=0.15, slack=0.05, bscale=0.7))
-    Q, K, Vv = mk(), mk(), mk()
-    eps_d = dev(np.full(B_, eps))
-    qd, kd, vd = planes_dev(Q), planes_dev(K), planes_dev(Vv)
-    ctx = _Ctx(eps, P, p)
-    # oracle, sentence by sentence, head by head
     S_ref, P_ref, O_ref = [], [], []
     for b in range(B_):
         sl_b = slice(b * L, (b + 1) * L)
@@ -166,18 +189,50 @@ def test_attention_stages(tv, B_, L, H, D, P, p):
             outs.append(B.dot_pv(Pb, v[sl], lp, lv[sl], uv[sl]))
         O_ref.append(B.Bounds(*[np.concatenate([getattr(o, a) for o in outs], 1) for a in ("lw", "lb", "uw", "ub")]))
     cat = lambda lst: B.Bounds(*[np.concatenate([getattr(o, a) for o in lst], 0) for a in ("lw", "lb", "uw", "ub")])
-    _, s1, _ = tv.op_attention(qd, kd, vd, B_, L, H, P, p, eps_d, stop_after=1)
-    assert_state_close(host(s1), cat(S_ref), "scores", rtol=2e-4, atol_scale=5e-6)
-    _, s2, st = tv.op_attention(qd, kd, vd, B_, L, H, P, p, eps_d, stop_after=2)
+    return cat(S_ref), cat(P_ref), cat(O_ref)
+
+
+@pytest.mark.parametrize("p", NORMS)
+@pytest.mark.parametrize("B_,L,H,D,P", [(2, 8, 4, 64, 1), (1, 32, 4, 128, 1), (2, 12, 2, 40, 2), (1, 64, 2, 128, 1)])
+def test_attention_stages(tv, B_, L, H, D, P, p):
+    rng = np.random.default_rng(B_ + L + D + p)
+    eps = {0: 0.008, 2: 0.05, 1: 0.08}[p]     # comparable range widths for the three balls
+    mk = lambda: quantize(random_state(rng, (B_ * L, D), P, D, eps, p, wscale=0.15, slack=0.05, bscale=0.7), B_)
+    Q, K, Vv = mk(), mk(), mk()
+    eps_d = dev(np.full(B_, eps))
+    qd, kd, vd = planes_dev(Q, B_), planes_dev(K, B_), planes_dev(Vv, B_)
+    S_ref, P_ref, O_ref = attention_reference(Q, K, Vv, B_, L, H, D, _Ctx(eps, P, p))
+    _, s1, _ = tv.op_attention(qd, kd, vd, H, P, p, eps_d, stop_after=1)
+    assert_state_close(host(s1), S_ref, "scores", rtol=2e-4, atol_scale=5e-6)
+    _, s2, st = tv.op_attention(qd, kd, vd, H, P, p, eps_d, stop_after=2)
     assert int(st.sum()) == 0
-    assert_state_close(host(s2), cat(P_ref), "softmax", rtol=3e-4, atol_scale=1e-5)
-    o, _, st = tv.op_attention(qd, kd, vd, B_, L, H, P, p, eps_d, stop_after=0)
-    assert_state_close(host(o), cat(O_ref), "attention out", rtol=3e-4, atol_scale=1e-5)
+    assert_state_close(host(s2), P_ref, "softmax", rtol=3e-4, atol_scale=1e-5)
+    o, _, st = tv.op_attention(qd, kd, vd, H, P, p, eps_d, stop_after=0)
+    assert_state_close(host(o), O_ref, "attention out", rtol=3e-4, atol_scale=1e-5)
+
+
+def test_attention_narrow_intervals(tv):
+    """Second-order bias radii (slack x half-width) at widths far below fp32 resolution of the values."""
+    rng = np.random.default_rng(99)
+    B_, L, H, D, P, p = 1, 8, 2, 32, 1, 2
+    eps = 1e-6
+    mk = lambda: quantize(random_state(rng, (B_ * L, D), P, D, eps, p, wscale=0.3, slack=1e-7, spread=1e-3, bscale=0.7), B_)
+    Q, K, Vv = mk(), mk(), mk()
+    eps_d = dev(np.full(B_, eps))
+    qd, kd, vd = planes_dev(Q, B_), planes_dev(K, B_), planes_dev(Vv, B_)
+    S_ref, P_ref, O_ref = attention_reference(Q, K, Vv, B_, L, H, D, _Ctx(eps, P, p))
+    for stop, ref, nm in ((1, S_ref, "scores"), (2, P_ref, "softmax"), (0, O_ref, "out")):
+        o, s, _ = tv.op_attention(qd, kd, vd, H, P, p, eps_d, stop_after=stop)
+        got = host(o if stop == 0 else s)
+        _, r_ref = to_planes(ref, got[0].shape[0])
+        rb = got[1][:, -1]
+        assert np.abs(rb - r_ref[:, -1]).max() <= 1e-3 * np.abs(r_ref[:, -1]).max() + 1e-13, nm
 
 
 def test_error_codes_on_device(tv):
-    S = torch.zeros(2, 5, 8, device="cuda:0"); R = torch.zeros_like(S)
+    S = torch.zeros(2, 5, 1, 8, device="cuda:0"); R = torch.zeros_like(S)
     with pytest.raises(tv.TvError, match="p_norm"):
         tv.op_concretize(S, R, 1, 4, 1, 7, dev(np.ones(2)))
+    S3 = torch.zeros(3, 5, 1, 8, device="cuda:0")
     with pytest.raises(tv.TvError, match="shape"):
-        tv.op_concretize(S, R, 1, 4, 3, 2, dev(np.ones(2)))     # rows % rows_per_sentence != 0
+        tv.op_concretize(S3, torch.zeros_like(S3), 1, 4, 2, 2, dev(np.ones(2)))     # groups % groups_per_sentence != 0

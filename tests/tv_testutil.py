@@ -16,29 +16,33 @@ def random_state(rng, shape, P, E, eps, p, wscale=1.0, slack=0.2, offset=0.0, bs
     return B.Bounds(lw, b - s - 0.5 * gap, uw, b + s + 0.5 * gap)
 
 
-def to_planes(X):
-    """Oracle state (neuron shape [rows..., n]) -> fp32 centre/radius planes [rows, C, n] (bias row last)."""
+def to_planes(X, G):
+    """Oracle state with neuron shape [G*T, n] -> fp32 centre/radius planes [G, C, T, n] (bias row last)."""
     lw, uw, lb, ub = X.lw, X.uw, X.lb, X.ub
     n = lb.shape[-1]
     rows = int(np.prod(lb.shape[:-1]))
+    T = rows // G
     PE = lw.shape[-1]
-    lw = lw.reshape(rows, n, PE).transpose(0, 2, 1)
-    uw = uw.reshape(rows, n, PE).transpose(0, 2, 1)
-    L = np.concatenate([lw, lb.reshape(rows, 1, n)], 1)
-    U = np.concatenate([uw, ub.reshape(rows, 1, n)], 1)
+    lw = lw.reshape(G, T, n, PE).transpose(0, 3, 1, 2)
+    uw = uw.reshape(G, T, n, PE).transpose(0, 3, 1, 2)
+    L = np.concatenate([lw, lb.reshape(G, 1, T, n)], 1)
+    U = np.concatenate([uw, ub.reshape(G, 1, T, n)], 1)
     return (0.5 * (U + L)).astype(np.float32), (0.5 * (U - L)).astype(np.float32)
 
 
 def from_planes(S, R):
-    """fp32 planes [rows, C, n] -> oracle-style (lw [rows,n,PE], lb [rows,n], uw, ub) in float64."""
+    """fp32 planes [G, C, T, n] -> oracle-style (lw [G*T,n,PE], lb [G*T,n], uw, ub) in float64."""
     S = S.astype(np.float64); R = R.astype(np.float64)
+    G, C, T, n = S.shape
     L, U = S - R, S + R
-    return (L[:, :-1].transpose(0, 2, 1), L[:, -1], U[:, :-1].transpose(0, 2, 1), U[:, -1])
+    w = lambda a: a[:, :-1].transpose(0, 2, 3, 1).reshape(G * T, n, C - 1)
+    b = lambda a: a[:, -1].reshape(G * T, n)
+    return w(L), b(L), w(U), b(U)
 
 
-def quantize(X):
+def quantize(X, G=1):
     """Round an oracle state to what the fp32 planes hold, so that both sides start from identical inputs."""
-    S, R = to_planes(X)
+    S, R = to_planes(X, G)
     lw, lb, uw, ub = from_planes(S, R)
     shp = X.lb.shape
     return B.Bounds(lw.reshape(shp + (-1,)), lb.reshape(shp), uw.reshape(shp + (-1,)), ub.reshape(shp))
@@ -59,19 +63,17 @@ def assert_close(got, ref, what, rtol=1e-4, atol_scale=1e-6):
 
 
 def assert_state_close(planes, X, what, rtol=1e-4, atol_scale=2e-6):
-    """Compare GPU planes with an oracle state in the representation the library stores: centre and
-    radius planes, coefficient rows and bias row separately (they live on different scales).  The
-    absolute allowance is atol_scale times the largest |centre| or |radius| entry of that part, i.e.
-    fp32 rounding of the terms a lower / upper line is the sum or difference of."""
+    """Compare GPU planes [G, C, T, n] with an oracle state (neuron shape [G*T, n]) in the representation
+    the library stores: centre and radius planes, coefficient rows and bias row separately (they live on
+    different scales).  The absolute allowance is atol_scale times the largest |centre| or |radius|
+    entry of that part, i.e. fp32 rounding of the terms a lower / upper line is the sum or difference of."""
     Sg, Rg = (np.asarray(a, np.float64) for a in planes)
-    shp = X.lb.shape
-    rows = int(np.prod(shp[:-1])); n = shp[-1]
-    lw = X.lw.reshape(rows, n, -1).transpose(0, 2, 1); uw = X.uw.reshape(rows, n, -1).transpose(0, 2, 1)
-    lb = X.lb.reshape(rows, 1, n); ub = X.ub.reshape(rows, 1, n)
-    for nm, g_s, g_r, lo, up in (("weights", Sg[:, :-1], Rg[:, :-1], lw, uw), ("bias", Sg[:, -1:], Rg[:, -1:], lb, ub)):
-        s_ref, r_ref = 0.5 * (up + lo), 0.5 * (up - lo)
+    G = Sg.shape[0]
+    s32, r32 = to_planes_f64(X, G)
+    for nm, sl in (("weights", np.s_[:, :-1]), ("bias", np.s_[:, -1:])):
+        s_ref, r_ref = s32[sl], r32[sl]
         scale = max(np.abs(s_ref).max(initial=0.0), np.abs(r_ref).max(initial=0.0))
-        for pn, g, o in (("centre", g_s, s_ref), ("radius", g_r, r_ref)):
+        for pn, g, o in (("centre", Sg[sl], s_ref), ("radius", Rg[sl], r_ref)):
             err = np.abs(g - o)
             tol = rtol * np.abs(o) + atol_scale * scale
             bad = err > tol
@@ -79,3 +81,16 @@ def assert_state_close(planes, X, what, rtol=1e-4, atol_scale=2e-6):
                 k = np.unravel_index(np.argmax(err - tol), err.shape)
                 raise AssertionError(f"{what} {nm} {pn}: {bad.sum()} of {bad.size} off; worst at {k}: got {g[k]!r} "
                                      f"ref {o[k]!r} (scale {scale:.3e})")
+
+
+def to_planes_f64(X, G):
+    lw, uw, lb, ub = X.lw, X.uw, X.lb, X.ub
+    n = lb.shape[-1]
+    rows = int(np.prod(lb.shape[:-1]))
+    T = rows // G
+    PE = lw.shape[-1]
+    lw = lw.reshape(G, T, n, PE).transpose(0, 3, 1, 2)
+    uw = uw.reshape(G, T, n, PE).transpose(0, 3, 1, 2)
+    L = np.concatenate([lw, lb.reshape(G, 1, T, n)], 1)
+    U = np.concatenate([uw, ub.reshape(G, 1, T, n)], 1)
+    return 0.5 * (U + L), 0.5 * (U - L)
