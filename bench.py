@@ -19,6 +19,11 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0       # MI355X HBM3E
 MFMA_FP32_PEAK_TF = 157.3   # MI355X dense fp32 matrix
+# HBM bytes per launch of a kernel class from `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE` on `bench.py --probe`,
+# scaled by the counters' readings for the 2^30-byte copy of the same run (2048 and 1024 bytes per unit) and
+# averaged over the launches of one certify call; counters cannot be read inside this process, so the figure is
+# a constant of the workload and is reported only for the workload it was collected on
+PMC_TRAFFIC = {"c2": {"affine_gemm": 434.0e6, "layernorm": 271.3e6, "activation": 408.0e6, "softmax": 176.9e6}}
 MFMA_KINDS = ("affine_gemm", "qk_gemm_x", "qk_gemm_y", "pv_gemm_x", "pv_gemm_y", "head_gemm")
 
 
@@ -113,6 +118,7 @@ def main():
             ach = d["bytes"] / (d["ms"] * 1e-3) / 1e9
             roofline = {"kernel": dom, "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS,
                         "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None}
+        roofline["traffic"] = PMC_TRAFFIC.get(args.workload, {}).get(dom)
         roofline["avg_launch_us"] = round(d["ms"] * 1e3 / d["launches"], 2)
         roofline["algorithmic_bytes_per_launch"] = d["bytes"] / d["launches"]
         roofline["algorithmic_flops_per_launch"] = d["flops"] / d["launches"]

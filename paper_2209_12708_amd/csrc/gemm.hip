@@ -282,14 +282,8 @@ int gemm(const GemmArgs &g, hipStream_t st) {
   if (a.M <= 64) return launch<64, 128, 2, 2>(a, st);
   if (a.N <= 32) return launch<128, 32, 4, 1>(a, st);
   if (a.N <= 64) return launch<128, 64, 2, 2>(a, st);
-  static const int exp_nobias = getenv("TV_GEMM_NOBIAS") ? 1 : 0;   // experiment hook (timing only)
-  if (exp_nobias) a.bias = nullptr;
-  static const int exp_tile = getenv("TV_GEMM_TILE") ? atoi(getenv("TV_GEMM_TILE")) : 0;   // experiment hook
-  if (exp_tile == 1 || (exp_tile == 0 && a.K <= 256 && a.N % 128 == 0)) return launch<64, 128, 2, 2>(a, st);
-  if (exp_tile == 2) return launch<128, 64, 2, 2>(a, st);
-  if (exp_tile == 3) return launch<64, 64, 2, 2>(a, st);
-  if (exp_tile == 4) return launch<128, 128, 2, 2, 64>(a, st);
-  if (exp_tile == 5) return launch<64, 128, 2, 2, 64>(a, st);
+  // short K: the smaller tile doubles the workgroups in flight, which hides the epilogue better (measured)
+  if (a.K <= 256 && a.N % 128 == 0) return launch<64, 128, 2, 2>(a, st);
   return launch<128, 128, 2, 2>(a, st);
 }
 
