@@ -89,7 +89,9 @@ void tv_model_destroy(tv_model *m);
 /* Workspace bytes for a call on B sentences of L tokens with P perturbed positions when all B
  * sentences are resident at once (*bytes_full) and the minimum, one sentence at a time
  * (*bytes_min).  Any size in between is accepted by tv_verify / tv_certify, which process the
- * batch in chunks of as many sentences as fit.  Either output pointer may be NULL. */
+ * batch in chunks of as many sentences as fit.  *bytes_full includes the region in which
+ * tv_certify keeps the first layer's q/k/v (independent of eps) across its probes; with less,
+ * tv_certify recomputes it in every probe.  Either output pointer may be NULL. */
 int tv_workspace_query(const tv_model *m, int B, int L, int P, size_t *bytes_full, size_t *bytes_min);
 
 /* Bounds on the logits over the perturbation set (forward bound propagation: Eq. (2) for affine

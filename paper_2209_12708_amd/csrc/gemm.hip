@@ -225,23 +225,27 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs g, int mtiles,
         for (int v = 0; v < 16; ++v) acc[i][j][v] += add[v];
       }
     }
+    if (tile_has_bias) {   // uniform branch: the plain store loop below never waits on a load
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int m = mb + 8 * (v >> 2) + (v & 3);
+        // rows are ordered (group, coefficient row, t); the last coefficient row is the bias row
+        const int blk = m / g.bias_T;
+        if (m < M && blk % g.bias_C == g.bias_C - 1) {
+          const float *brow = bias + ((long)(blk / g.bias_C) * g.bias_T + m % g.bias_T) * g.bias_ld;
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+            if (con[j]) acc[i][j][v] += brow[col[j]];
+        }
+      }
+    }
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
       const int m = mb + 8 * (v >> 2) + (v & 3);
       if (m >= M) continue;
-      const float *brow = nullptr;
-      if (tile_has_bias) {   // rows are ordered (group, coefficient row, t); the last coefficient row is the bias row
-        const int blk = m / g.bias_T;
-        if (blk % g.bias_C == g.bias_C - 1)
-          brow = bias + ((long)(blk / g.bias_C) * g.bias_T + m % g.bias_T) * g.bias_ld;
-      }
 #pragma unroll
-      for (int j = 0; j < TN; ++j) {
-        if (!con[j]) continue;
-        float val = acc[i][j][v];
-        if (brow) val += brow[col[j]];
-        C[(long)m * g.ldc + col[j]] = val;
-      }
+      for (int j = 0; j < TN; ++j)
+        if (con[j]) C[(long)m * g.ldc + col[j]] = acc[i][j][v];
     }
   }
 }

@@ -192,11 +192,13 @@ struct tv_model {
 namespace {
 
 struct Plan {      // workspace offsets in floats for a chunk of Bc sentences
-  size_t x, qkv, t1, big, attn, attn_floats, wh, bh, hy, hl, hu, eps, margin, lohi, labels, status, cnt, total;
+  size_t x, qkv, t1, big, attn, attn_floats, wh, bh, hy, hl, hu, eps, margin, lohi, labels, status, cnt, qkv0, total;
   int NP;
 };
 
-Plan make_plan(const tv_config &c, int Bc, int L, int P) {
+// cache0: reserve a second q/k/v region that keeps the first layer's projection of the input state, which does
+// not depend on eps, across the probes of a bisection (placed last, so every other offset is unchanged)
+Plan make_plan(const tv_config &c, int Bc, int L, int P, bool cache0 = false) {
   const size_t D = c.hidden, F = c.ffn, H = c.n_heads;
   const size_t C = (size_t)P * D + 1;
   const size_t rows = (size_t)Bc * L;
@@ -222,17 +224,18 @@ Plan make_plan(const tv_config &c, int Bc, int L, int P) {
   p.labels = take(Bc);
   p.status = take(Bc);
   p.cnt = take(Bc);
+  p.qkv0 = cache0 ? take(2 * rows * C * 3 * D) : 0;
   p.total = o;
   return p;
 }
 
-int chunk_size(const tv_config &c, int B, int L, int P, size_t ws_bytes) {
+int chunk_size(const tv_config &c, int B, int L, int P, size_t ws_bytes, bool cache0 = false) {
   // largest Bc <= B whose plan fits (plan size is monotone in Bc)
-  if (make_plan(c, 1, L, P).total * sizeof(float) > ws_bytes) return 0;
+  if (make_plan(c, 1, L, P, cache0).total * sizeof(float) > ws_bytes) return 0;
   int lo = 1, hi = B;
   while (lo < hi) {
     const int mid = (lo + hi + 1) / 2;
-    if (make_plan(c, mid, L, P).total * sizeof(float) <= ws_bytes) lo = mid; else hi = mid - 1;
+    if (make_plan(c, mid, L, P, cache0).total * sizeof(float) <= ws_bytes) lo = mid; else hi = mid - 1;
   }
   return lo;
 }
@@ -254,8 +257,32 @@ int affine(const float *xS, long xplane, long M, int C, int T, int K, int N, con
   return gemm(g, st);
 }
 
+// input state (Sec. 2.1): bias row = clean embedding, identity rows at the perturbed positions, zero radius
+int init_input(const tv_model *m, const Plan &pl, float *w, const int32_t *tokens, const int32_t *positions, int Bc,
+               int L, int P, hipStream_t st) {
+  const int D = m->cfg.hidden;
+  const long rows = (long)Bc * L, pD = rows * (P * D + 1) * D;
+  float *X = w + pl.x;
+  if (int rc = fill_zero(X, (size_t)2 * pD, st)) return rc;
+  hipLaunchKernelGGL(init_state_kernel, dim3(nblk(rows * D)), dim3(256), 0, st, tokens, positions, m->tok_emb,
+                     m->pos_emb, Bc, L, D, P, X);
+  TV_HIP(hipGetLastError());
+  return TV_OK;
+}
+
+// q, k, v of the first layer from the input state: the same for every eps, so a bisection computes it once
+int project_input(const tv_model *m, const Plan &pl, float *w, const int32_t *tokens, const int32_t *positions,
+                  int Bc, int L, int P, hipStream_t st) {
+  const int D = m->cfg.hidden, C = P * D + 1;
+  const long M = (long)Bc * L * C;
+  if (int rc = init_input(m, pl, w, tokens, positions, Bc, L, P, st)) return rc;
+  return affine(w + pl.x, M * D, M, C, L, D, 3 * D, m->layers[0].Wqkv, m->layers[0].bqkv, nullptr, 0, w + pl.qkv0,
+                M * 3 * D, st);
+}
+
+// one pass of the encoder.  qkv0: the cached first-layer projection (project_input), or nullptr to compute it.
 int sweep(const tv_model *m, const Plan &pl, float *w, const int32_t *tokens, const int32_t *positions, int Bc, int L,
-          int P, int pn, const float *eps, int32_t *status, hipStream_t st) {
+          int P, int pn, const float *eps, int32_t *status, const float *qkv0, hipStream_t st) {
   const tv_config &c = m->cfg;
   const int D = c.hidden, F = c.ffn, H = c.n_heads;
   const int C = P * D + 1;
@@ -266,16 +293,15 @@ int sweep(const tv_model *m, const Plan &pl, float *w, const int32_t *tokens, co
   void *attn_ws = w + pl.attn;
   const size_t attn_bytes = pl.attn_floats * sizeof(float);
 
-  if (int rc = fill_zero(X, (size_t)2 * pD, st)) return rc;
-  hipLaunchKernelGGL(init_state_kernel, dim3(nblk(rows * D)), dim3(256), 0, st, tokens, positions, m->tok_emb,
-                     m->pos_emb, Bc, L, D, P, X);
-  TV_HIP(hipGetLastError());
+  if (int rc = init_input(m, pl, w, tokens, positions, Bc, L, P, st)) return rc;
 
   for (int l = 0; l < c.n_layers; ++l) {
     const tv_layer_dev &lw = m->layers[l];
     // q, k, v in one product: columns [0,D) q, [D,2D) k, [2D,3D) v
-    if (int rc = affine(X, pD, M, C, L, D, 3 * D, lw.Wqkv, lw.bqkv, nullptr, 0, QKV, p3D, st)) return rc;
-    CState q{QKV, QKV + p3D}, k{QKV + D, QKV + p3D + D}, v{QKV + 2 * D, QKV + p3D + 2 * D};
+    const float *Q = QKV;
+    if (l == 0 && qkv0) Q = qkv0;
+    else if (int rc = affine(X, pD, M, C, L, D, 3 * D, lw.Wqkv, lw.bqkv, nullptr, 0, QKV, p3D, st)) return rc;
+    CState q{Q, Q + p3D}, k{Q + D, Q + p3D + D}, v{Q + 2 * D, Q + p3D + 2 * D};
     State o{T1, T1 + pD}, s{BIG, BIG + pS};
     if (int rc = attention(q, k, v, 3 * D, Bc, L, H, D, P, pn, eps, o, s, 0, status, attn_ws, attn_bytes, st))
       return rc;
@@ -348,7 +374,8 @@ int chunk_labels(const tv_model *m, float *w, const Plan &pl, const int32_t *tok
   hipLaunchKernelGGL(fill_i32_kernel, dim3(nblk(Bc)), dim3(256), 0, st, reinterpret_cast<int32_t *>(w + p0.status),
                      Bc, 0);
   TV_HIP(hipGetLastError());
-  if (int rc = sweep(m, p0, w, tokens, positions, Bc, L, 0, pn, eps0, reinterpret_cast<int32_t *>(w + p0.status), st))
+  if (int rc = sweep(m, p0, w, tokens, positions, Bc, L, 0, pn, eps0, reinterpret_cast<int32_t *>(w + p0.status), nullptr,
+                     st))
     return rc;
   if (int rc = head(m, p0, w, Bc, L, 0, pn, eps0, reinterpret_cast<int32_t *>(w + p0.labels), st)) return rc;
   // p0's small arrays sit below pl's (its big regions are smaller), so writing pl.labels last is safe
@@ -453,7 +480,7 @@ void tv_model_destroy(tv_model *m) {
 int tv_workspace_query(const tv_model *m, int B, int L, int P, size_t *bytes_full, size_t *bytes_min) {
   TV_REQUIRE(m, TV_E_NULL, "tv_workspace_query: null model");
   TV_REQUIRE(B > 0 && L > 0 && L % 4 == 0 && P >= 1 && P <= kMaxP, TV_E_SHAPE, "tv_workspace_query: bad sizes");
-  if (bytes_full) *bytes_full = make_plan(m->cfg, B, L, P).total * sizeof(float);
+  if (bytes_full) *bytes_full = make_plan(m->cfg, B, L, P, true).total * sizeof(float);
   if (bytes_min) *bytes_min = make_plan(m->cfg, 1, L, P).total * sizeof(float);
   return TV_OK;
 }
@@ -477,7 +504,7 @@ int tv_verify(const tv_model *m, const int32_t *tokens, int B, int L, const int3
     if (int rc = chunk_labels(m, w, pl, tok, pos, Bc, L, pn, labels ? labels + b0 : nullptr, st)) return rc;
     hipLaunchKernelGGL(fill_i32_kernel, dim3(nblk(Bc)), dim3(256), 0, st, stat, Bc, 0);
     TV_HIP(hipGetLastError());
-    if (int rc = sweep(m, pl, w, tok, pos, Bc, L, P, pn, eps + b0, stat, st)) return rc;
+    if (int rc = sweep(m, pl, w, tok, pos, Bc, L, P, pn, eps + b0, stat, nullptr, st)) return rc;
     if (int rc = head(m, pl, w, Bc, L, P, pn, eps + b0, lab, st)) return rc;
     hipLaunchKernelGGL(head_out_kernel, dim3(nblk(Bc)), dim3(256), 0, st, w + pl.hl, w + pl.hu, stat, lab, Bc, nc,
                        pl.NP, out_lower + (size_t)b0 * nc, out_upper + (size_t)b0 * nc,
@@ -496,15 +523,18 @@ int tv_certify(const tv_model *m, const int32_t *tokens, int B, int L, const int
   TV_REQUIRE(steps >= 1 && steps <= 64, TV_E_ARG, "tv_certify: steps must be in [1, 64], got %d", steps);
   TV_REQUIRE(eps_lo >= 0.f && eps_hi > eps_lo && eps_hi <= 3.0e38f, TV_E_ARG,
              "tv_certify: need 0 <= eps_lo < eps_hi (finite)");
-  const int Bmax = chunk_size(m->cfg, B, L, P, workspace_bytes);
-  TV_REQUIRE(Bmax >= 1, TV_E_WORKSPACE, "tv_certify: workspace of %zu bytes cannot hold one sentence (%zu needed)",
+  // keep the first layer's q/k/v across the probes when the workspace has room for it at the same chunk size
+  const int Bplain = chunk_size(m->cfg, B, L, P, workspace_bytes);
+  TV_REQUIRE(Bplain >= 1, TV_E_WORKSPACE, "tv_certify: workspace of %zu bytes cannot hold one sentence (%zu needed)",
              workspace_bytes, make_plan(m->cfg, 1, L, P).total * sizeof(float));
+  const bool cache0 = steps >= 2 && chunk_size(m->cfg, B, L, P, workspace_bytes, true) == Bplain;
+  const int Bmax = Bplain;
   hipStream_t st = static_cast<hipStream_t>(stream);
   float *w = static_cast<float *>(workspace);
   const int nc = m->cfg.n_classes;
   for (int b0 = 0; b0 < B; b0 += Bmax) {
     const int Bc = B - b0 < Bmax ? B - b0 : Bmax;
-    const Plan pl = make_plan(m->cfg, Bc, L, P);
+    const Plan pl = make_plan(m->cfg, Bc, L, P, cache0);
     int32_t *lab = reinterpret_cast<int32_t *>(w + pl.labels), *stat = reinterpret_cast<int32_t *>(w + pl.status);
     int32_t *cnt = reinterpret_cast<int32_t *>(w + pl.cnt);
     float *eps = w + pl.eps, *lohi = w + pl.lohi, *margin = w + pl.margin;
@@ -512,11 +542,13 @@ int tv_certify(const tv_model *m, const int32_t *tokens, int B, int L, const int
     if (int rc = chunk_labels(m, w, pl, tok, pos, Bc, L, pn, labels ? labels + b0 : nullptr, st)) return rc;
     hipLaunchKernelGGL(search_init_kernel, dim3(nblk(Bc)), dim3(256), 0, st, lohi, Bc, eps_lo, eps_hi, cnt);
     TV_HIP(hipGetLastError());
+    if (cache0)
+      if (int rc = project_input(m, pl, w, tok, pos, Bc, L, P, st)) return rc;
     for (int it = 0; it < steps; ++it) {
       hipLaunchKernelGGL(search_mid_kernel, dim3(nblk(Bc)), dim3(256), 0, st, lohi, Bc, eps);
       hipLaunchKernelGGL(fill_i32_kernel, dim3(nblk(Bc)), dim3(256), 0, st, stat, Bc, 0);
       TV_HIP(hipGetLastError());
-      if (int rc = sweep(m, pl, w, tok, pos, Bc, L, P, pn, eps, stat, st)) return rc;
+      if (int rc = sweep(m, pl, w, tok, pos, Bc, L, P, pn, eps, stat, cache0 ? w + pl.qkv0 : nullptr, st)) return rc;
       if (int rc = head(m, pl, w, Bc, L, P, pn, eps, lab, st)) return rc;
       hipLaunchKernelGGL(head_out_kernel, dim3(nblk(Bc)), dim3(256), 0, st, w + pl.hl, w + pl.hu, stat, lab, Bc, nc,
                          pl.NP, (float *)nullptr, (float *)nullptr, (float *)nullptr, (int32_t *)nullptr, stat, margin);

@@ -12,6 +12,12 @@
 #pragma once
 #include <hip/hip_runtime.h>
 
+// The scalar algebra below relies on identical inputs giving bit-identical outputs for the lower and
+// the upper line (a point interval must produce exactly coinciding lines, hence an exactly zero radius).
+// Fused multiply-add contraction breaks that: after inlining, one of two equal products may be fused
+// into a following sum and the other not.  Every function here therefore switches contraction off.
+#define TV_NO_CONTRACT _Pragma("clang fp contract(off)")
+
 namespace tv {
 
 struct Line2 { double kL, cL, kU, cU; };
@@ -21,11 +27,13 @@ constexpr double kExpCap = 0.99;       // exp lower tangent at min(mid, l + 0.99
 constexpr double kRecipMin = 1e-12;    // domain guard of the reciprocal
 
 __device__ __forceinline__ bool is_point(double l, double u) {
+  TV_NO_CONTRACT
   return (u - l) <= kTau * fmax(1.0, fmax(fabs(l), fabs(u)));
 }
 
 // slope f'(m) for both lines, intercepts min / max of f(x) - k x over {l, m, u}
 __device__ __forceinline__ Line2 point_rule(double k, double fl, double fm, double fu, double l, double m, double u) {
+  TV_NO_CONTRACT
   const double a = fl - k * l, b = fm - k * m, c = fu - k * u;
   Line2 r;
   r.kL = r.kU = k;
@@ -35,6 +43,7 @@ __device__ __forceinline__ Line2 point_rule(double k, double fl, double fm, doub
 }
 
 __device__ __forceinline__ Line2 relax_relu(double l, double u) {
+  TV_NO_CONTRACT
   Line2 r;
   if (l >= 0.0) { r.kL = r.kU = 1.0; r.cL = r.cU = 0.0; }
   else if (u <= 0.0) { r.kL = r.kU = 0.0; r.cL = r.cU = 0.0; }
@@ -49,6 +58,7 @@ __device__ __forceinline__ Line2 relax_relu(double l, double u) {
 // tangent point d in [lo, hi] whose tangent passes through (end, tanh end); returns the bracket end on
 // the sound side (lower end for the lower line, upper end for the upper line)
 __device__ __forceinline__ double tanh_tangent_through(double end, double lo, double hi, bool sound_lo) {
+  TV_NO_CONTRACT
   const double te = tanh(end);
   auto g = [&](double d) { const double t = tanh(d); return t + (1.0 - t * t) * (end - d) - te; };
   const bool neg_lo = g(lo) < 0.0;
@@ -60,6 +70,7 @@ __device__ __forceinline__ double tanh_tangent_through(double end, double lo, do
 }
 
 __device__ __forceinline__ Line2 relax_tanh(double l, double u) {
+  TV_NO_CONTRACT
   const double m = 0.5 * (l + u);
   const double tl = tanh(l), tu = tanh(u), tm = tanh(m);
   if (is_point(l, u)) return point_rule(1.0 - tm * tm, tl, tm, tu, l, m, u);
@@ -88,6 +99,7 @@ __device__ __forceinline__ Line2 relax_tanh(double l, double u) {
 }
 
 __device__ __forceinline__ Line2 relax_exp(double l, double u) {
+  TV_NO_CONTRACT
   const double m = 0.5 * (l + u);
   const double el = exp(l), eu = exp(u);
   if (is_point(l, u)) { const double em = exp(m); return point_rule(em, el, em, eu, l, m, u); }
@@ -99,6 +111,7 @@ __device__ __forceinline__ Line2 relax_exp(double l, double u) {
 }
 
 __device__ __forceinline__ Line2 relax_recip(double l, double u) {   // requires l > 0
+  TV_NO_CONTRACT
   const double m = 0.5 * (l + u);
   if (is_point(l, u)) return point_rule(-1.0 / (m * m), 1.0 / l, 1.0 / m, 1.0 / u, l, m, u);
   Line2 r;
@@ -108,6 +121,7 @@ __device__ __forceinline__ Line2 relax_recip(double l, double u) {   // requires
 }
 
 __device__ __forceinline__ Line2 relax_sqrt(double l, double u) {    // requires l > 0
+  TV_NO_CONTRACT
   const double m = 0.5 * (l + u);
   const double sl = sqrt(l), su = sqrt(u), sm = sqrt(m);
   if (is_point(l, u)) return point_rule(0.5 / sm, sl, sm, su, l, m, u);
@@ -118,6 +132,7 @@ __device__ __forceinline__ Line2 relax_sqrt(double l, double u) {    // requires
 }
 
 __device__ __forceinline__ Line2 relax_square(double l, double u) {
+  TV_NO_CONTRACT
   const double m = 0.5 * (l + u);
   if (is_point(l, u)) return point_rule(2.0 * m, l * l, m * m, u * u, l, m, u);
   Line2 r;
@@ -135,6 +150,7 @@ __device__ __forceinline__ Form form_identity() { return Form{1.0, 0.0, 0.0, 1.0
 // z with k_L y + c_L <= z <= k_U y + c_U: each line takes y's own side for a non-negative slope, the
 // other side for a negative one (sign rule of Eq. (2) applied to a per-neuron scalar)
 __device__ __forceinline__ Form form_sub(const Form &y, double kL, double cL, double kU, double cU) {
+  TV_NO_CONTRACT
   Form z;
   if (kL >= 0.0) { z.pL = kL * y.pL; z.qL = kL * y.qL; z.cL = kL * y.cL + cL; }
   else           { z.pL = kL * y.qU; z.qL = kL * y.pU; z.cL = kL * y.cU + cL; }
@@ -145,12 +161,14 @@ __device__ __forceinline__ Form form_sub(const Form &y, double kL, double cL, do
 __device__ __forceinline__ Form form_sub(const Form &y, const Line2 &ln) { return form_sub(y, ln.kL, ln.cL, ln.kU, ln.cU); }
 
 __device__ __forceinline__ Form form_add(const Form &a, const Form &b) {
+  TV_NO_CONTRACT
   return Form{a.pL + b.pL, a.qL + b.qL, a.cL + b.cL, a.pU + b.pU, a.qU + b.qU, a.cU + b.cU};
 }
 
 // z = x * y (both relative to the same base), McCormick planes
 //   z >= ly x + lx y - lx ly ,   z <= uy x + lx y - lx uy
 __device__ __forceinline__ Form form_mul(const Form &x, const Form &y, double lx, double ly, double uy) {
+  TV_NO_CONTRACT
   const Form ax = form_sub(x, ly, 0.0, uy, 0.0);
   const Form by = form_sub(y, lx, 0.0, lx, 0.0);
   Form z = form_add(ax, by);
@@ -162,6 +180,7 @@ __device__ __forceinline__ Form form_mul(const Form &x, const Form &y, double lx
 // concretized bounds of z = relaxation of y on [ly, uy] (single-input chain: the norm of z's
 // coefficients is |k| times the norm of one side of y)
 __device__ __forceinline__ void line_range(const Line2 &ln, double ly, double uy, double &lz, double &uz) {
+  TV_NO_CONTRACT
   lz = (ln.kL >= 0.0 ? ln.kL * ly : ln.kL * uy) + ln.cL;
   uz = (ln.kU >= 0.0 ? ln.kU * uy : ln.kU * ly) + ln.cU;
 }
@@ -174,6 +193,7 @@ struct Map2 {
   double sSd, sRd, sCd, rSd, rRd, rCd;
 };
 __device__ __forceinline__ Map2 form_map(const Form &f) {
+  TV_NO_CONTRACT
   Map2 m;
   m.sSd = 0.5 * (f.pL + f.qL + f.pU + f.qU);
   m.sRd = 0.5 * (-f.pL + f.qL + f.pU - f.qU);
@@ -194,6 +214,7 @@ struct Mul2 {
   double a1d, a2d, a3d, a4d;
 };
 __device__ __forceinline__ Mul2 mul_coeffs(double ly, double uy) {
+  TV_NO_CONTRACT
   Mul2 m;
   m.a1d = 0.5 * (ly + uy);
   m.a2d = 0.5 * (fabs(uy) - fabs(ly));

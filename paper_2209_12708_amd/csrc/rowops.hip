@@ -84,9 +84,27 @@ __device__ __forceinline__ void slot_reduce(float (&x)[CNT], const Geo &ge, bool
 }
 
 // Sum / max of one value over the G lanes of a row slot (lanes of a slot are consecutive).
+// The first four butterfly steps stay inside a 16-lane row and run as data-parallel-primitive moves on
+// the vector ALU (quad permutes for lane distance 1 and 2; mirrors within 8 and 16 lanes pair the same
+// partial sums as distances 4 and 8 would); distance 16 is a swizzle, only distance 32 goes through a
+// permute with an address register.
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float x) {
+  return x + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xF, 0xF, true));
+}
 template <typename T>
 __device__ __forceinline__ T row_sum(T x, int G) {
   for (int off = 1; off < G; off <<= 1) x += __shfl_xor(x, off);
+  return x;
+}
+template <>
+__device__ __forceinline__ float row_sum<float>(float x, int G) {
+  if (G > 1) x = dpp_add<0xB1>(x);     // quad_perm [1,0,3,2]
+  if (G > 2) x = dpp_add<0x4E>(x);     // quad_perm [2,3,0,1]
+  if (G > 4) x = dpp_add<0x141>(x);    // row_half_mirror
+  if (G > 8) x = dpp_add<0x140>(x);    // row_mirror
+  if (G > 16) x += __int_as_float(__builtin_amdgcn_ds_swizzle(__float_as_int(x), 0x401F));   // lane ^ 16
+  if (G > 32) x += __shfl_xor(x, 32);
   return x;
 }
 __device__ __forceinline__ float row_max(float x, int G) {
@@ -197,7 +215,8 @@ __device__ __forceinline__ void apply_maps(const float *S, const float *R, float
       for (int i = 0; i < 4 * VEC; ++i) {
         const double s = xs[i], rr = xr[i];
         ys[i] = (float)(maps[i].sSd * s + maps[i].sRd * rr + maps[i].sCd);
-        yr[i] = (float)(maps[i].rSd * s + maps[i].rRd * rr + maps[i].rCd);
+        // the gap between the two lines at the centre point is >= 0 by construction; rounding must not flip it
+        yr[i] = (float)fmax(maps[i].rSd * s + maps[i].rRd * rr + maps[i].rCd, 0.0);
       }
     }
     store_row<VEC>(So, Ro, lc, r, ge, ys, yr);
@@ -341,6 +360,24 @@ __device__ __forceinline__ void ln_centre(const float (&xs)[4 * VEC], const floa
   }
 }
 
+// sqrt and reciprocal on the scalar v of one token: ranges from the states, clamped where the true value
+// allows; returns rho's lines relative to v and the product coefficients for c * rho
+struct LnScalars { Map2 mr; Mul2 mc; };
+__device__ __forceinline__ LnScalars ln_scalars(double lv, double uv, double ln_eps) {
+  const double lvc = fmax(lv, ln_eps), uvc = fmax(uv, lvc);
+  const Line2 sq = relax_sqrt(lvc, uvc);
+  double ls0, us0;
+  line_range(sq, lv, uv, ls0, us0);                 // range of the sqrt state (from the unclamped v state)
+  const double ls = fmax(ls0, sqrt(ln_eps)), us = fmax(us0, ls);
+  const Line2 rcp = relax_recip(ls, us);
+  double lr, ur;
+  line_range(rcp, ls0, us0, lr, ur);                // range of rho's state
+  LnScalars o;
+  o.mr = form_map(form_sub(form_sub(form_identity(), sq), rcp));   // rho relative to v
+  o.mc = mul_coeffs(lr, ur);
+  return o;
+}
+
 template <int VEC>
 __global__ __launch_bounds__(kThreads) void layernorm_kernel(const float *S, const float *R, int P, int E, int T_, int n,
                                                              int G, int gps, int pn, const float *eps,
@@ -454,17 +491,9 @@ __global__ __launch_bounds__(kThreads) void layernorm_kernel(const float *S, con
     range_of(vSb, vRb, e, NLv, NUv, lv, uv);
     bad |= !(finite_d(lv) && finite_d(uv));
   }
-  // sqrt and reciprocal on the scalar v: ranges from the states, clamped where the true value allows
-  const double lvc = fmax(lv, ln_eps), uvc = fmax(uv, lvc);
-  const Line2 sq = relax_sqrt(lvc, uvc);
-  double ls0, us0;
-  line_range(sq, lv, uv, ls0, us0);                 // range of the sqrt state (from the unclamped v state)
-  const double ls = fmax(ls0, sqrt(ln_eps)), us = fmax(us0, ls);
-  const Line2 rcp = relax_recip(ls, us);
-  double lr, ur;
-  line_range(rcp, ls0, us0, lr, ur);                // range of rho's state
-  const Map2 mr = form_map(form_sub(form_sub(form_identity(), sq), rcp));   // rho relative to v
-  const Mul2 mc = mul_coeffs(lr, ur);
+  const LnScalars sc_ = ln_scalars(lv, uv, ln_eps);
+  const Map2 &mr = sc_.mr;
+  const Mul2 &mc = sc_.mc;
   if (bad) status[sent] = 1;
 
   // ---- sweep 3: y = c * rho (x = c_d with multiplier range of rho; y = rho with multiplier l_c), gamma / beta
@@ -501,9 +530,150 @@ __global__ __launch_bounds__(kThreads) void layernorm_kernel(const float *S, con
       const double yS = mc.a1d * csb[i] + mc.a2d * crb[i] + cl[i] * rhoS - cl[i] * mc.a1d;
       const double yR = mc.a3d * slack + mc.a4d * crb[i] + fabs(cl[i]) * rhoR;
       ys[i] = (float)((double)gm[i] * yS + (double)bt[i]);
-      yr[i] = (float)(fabs((double)gm[i]) * yR);
+      yr[i] = (float)fmax(fabs((double)gm[i]) * yR, 0.0);
     }
     store_row<VEC>(So, Ro, lc, C - 1, ge, ys, yr);
+  }
+}
+
+// LayerNorm for small blocks (one perturbed position, at most ROWS coefficient rows per row slot, one
+// float4 per lane): the token's block is read once, all loads in flight together, and kept centred in
+// registers for the three sweeps.
+template <int ROWS>
+__global__ __launch_bounds__(kThreads, 2) void layernorm_cached_kernel(const float *S, const float *R, int nrows, int T_,
+                                                                    int n, int G, int gps, int pn, const float *eps,
+                                                                    const float *gamma, const float *beta,
+                                                                    float ln_eps_f, float *So, float *Ro,
+                                                                    int32_t *status) {
+  __shared__ float red[4 * kWave * 8];
+  const int C = nrows + 1;
+  const Geo ge(G, n / 4);
+  const Loc lc{(long)(blockIdx.x / T_), C, T_, (int)(blockIdx.x % T_), n, 0};
+  const int sent = (int)(lc.grp / gps);
+  const double e = eps[sent];
+  const double ln_eps = ln_eps_f;
+  const float inv = 1.f / (float)n;
+  const bool colon = ge.g < ge.n4;
+  bool bad = false;
+
+  // all loads of the block are issued before the first use; each row is then centred in place
+  float cs[ROWS][4], cr[ROWS][4];
+#pragma unroll
+  for (int it = 0; it < ROWS; ++it) {
+    const int r = ge.slot + it * ge.NS;
+    float4 a = make_float4(0.f, 0.f, 0.f, 0.f), b = a;
+    if (r < nrows && colon) {
+      const long o = lc.off(r);
+      a = reinterpret_cast<const float4 *>(S + o)[ge.g];
+      b = reinterpret_cast<const float4 *>(R + o)[ge.g];
+    }
+    cs[it][0] = a.x; cs[it][1] = a.y; cs[it][2] = a.z; cs[it][3] = a.w;
+    cr[it][0] = b.x; cr[it][1] = b.y; cr[it][2] = b.z; cr[it][3] = b.w;
+  }
+#pragma unroll
+  for (int it = 0; it < ROWS; ++it)
+    if (ge.slot + it * ge.NS < nrows) ln_centre<1, float>(cs[it], cr[it], n, ge, cs[it], cr[it]);
+  // ---- sweep 1: range of c, slope of the square relaxation
+  double cl[4], cu[4], csb[4], crb[4];
+  float NLc[4], kq[4];
+  {
+    float acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] = 0.f;
+#pragma unroll
+    for (int it = 0; it < ROWS; ++it) {
+      if (ge.slot + it * ge.NS < nrows) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          acc[2 * i] = norm_acc(acc[2 * i], cs[it][i] - cr[it][i], pn);
+          acc[2 * i + 1] = norm_acc(acc[2 * i + 1], cs[it][i] + cr[it][i], pn);
+        }
+      }
+    }
+    slot_reduce<8>(acc, ge, pn == 1, red);
+    float xs[4], xr[4];
+    load_row<1>(S, R, lc, C - 1, ge, xs, xr);
+    ln_centre<1, double>(xs, xr, n, ge, csb, crb);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      NLc[i] = norm_fin(acc[2 * i], pn);
+      range_of(csb[i], crb[i], e, NLc[i], norm_fin(acc[2 * i + 1], pn), cl[i], cu[i]);
+      if (colon) bad |= !(finite_d(cl[i]) && finite_d(cu[i]));
+      else { cl[i] = cu[i] = 0.0; csb[i] = crb[i] = 0.0; }
+      kq[i] = (float)(cl[i] + cu[i]);
+    }
+  }
+  // ---- sweep 2: v = mean_d q + ln_eps, one value per coefficient row
+  float vS[ROWS], vR[ROWS];
+  double lv, uv, vSb, vRb;
+  {
+    float acc[2] = {0.f, 0.f};
+#pragma unroll
+    for (int it = 0; it < ROWS; ++it) {
+      if (ge.slot + it * ge.NS < nrows) {
+        float a = 0.f, b = 0.f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { a += kq[i] * cs[it][i]; b += fabsf(kq[i]) * cr[it][i]; }
+        vS[it] = row_sum<float>(a, ge.G) * inv;
+        vR[it] = row_sum<float>(b, ge.G) * inv;
+        acc[0] = norm_acc(acc[0], vS[it] - vR[it], pn);
+        acc[1] = norm_acc(acc[1], vS[it] + vR[it], pn);
+      }
+    }
+    slot_reduce<2>(acc, ge, pn == 1, red);
+    double a = 0.0, b = 0.0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const double k = cl[i] + cu[i], m = 0.5 * k, w = cu[i] - cl[i];
+      a += k * csb[i] - 0.5 * (m * m + cl[i] * cu[i]);
+      b += fabs(k) * crb[i] + 0.125 * w * w;
+    }
+    vSb = row_sum<double>(a, ge.G) / (double)n + ln_eps;
+    vRb = row_sum<double>(b, ge.G) / (double)n;
+    range_of(vSb, vRb, e, norm_fin(acc[0], pn), norm_fin(acc[1], pn), lv, uv);
+    bad |= !(finite_d(lv) && finite_d(uv));
+  }
+  const LnScalars sc_ = ln_scalars(lv, uv, ln_eps);
+  const Map2 &mr = sc_.mr;
+  const Mul2 &mc = sc_.mc;
+  if (bad) status[sent] = 1;
+
+  // ---- sweep 3: y = c * rho, gamma / beta
+  float gm[4] = {0.f, 0.f, 0.f, 0.f}, bt[4] = {0.f, 0.f, 0.f, 0.f}, lcf[4];
+  if (colon) {
+    const float4 a = reinterpret_cast<const float4 *>(gamma)[ge.g], b = reinterpret_cast<const float4 *>(beta)[ge.g];
+    gm[0] = a.x; gm[1] = a.y; gm[2] = a.z; gm[3] = a.w;
+    bt[0] = b.x; bt[1] = b.y; bt[2] = b.z; bt[3] = b.w;
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) lcf[i] = (float)cl[i];
+#pragma unroll
+  for (int it = 0; it < ROWS; ++it) {
+    const int r = ge.slot + it * ge.NS;
+    if (r < nrows) {
+      const float rhoS = mr.sS * vS[it] + mr.sR * vR[it], rhoR = mr.rS * vS[it] + mr.rR * vR[it];
+      float ys[4], yr[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float yS = mc.a1 * cs[it][i] + mc.a2 * cr[it][i] + lcf[i] * rhoS;
+        const float yR = mc.a3 * cs[it][i] + mc.a4 * cr[it][i] + fabsf(lcf[i]) * rhoR;
+        ys[i] = gm[i] * yS; yr[i] = fabsf(gm[i]) * yR;
+      }
+      store_row<1>(So, Ro, lc, r, ge, ys, yr);
+    }
+  }
+  if (ge.slot == 0) {   // bias row, in double
+    const double rhoS = mr.sSd * vSb + mr.sRd * vRb + mr.sCd, rhoR = mr.rSd * vSb + mr.rRd * vRb + mr.rCd;
+    float ys[4], yr[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const double slack = crb[i] + e * (double)NLc[i];        // S_c_b - l_c without cancellation
+      const double yS = mc.a1d * csb[i] + mc.a2d * crb[i] + cl[i] * rhoS - cl[i] * mc.a1d;
+      const double yR = mc.a3d * slack + mc.a4d * crb[i] + fabs(cl[i]) * rhoR;
+      ys[i] = (float)((double)gm[i] * yS + (double)bt[i]);
+      yr[i] = (float)fmax(fabs((double)gm[i]) * yR, 0.0);
+    }
+    store_row<1>(So, Ro, lc, C - 1, ge, ys, yr);
   }
 }
 
@@ -642,7 +812,7 @@ __global__ __launch_bounds__(kThreads) void softmax_kernel(float *S, float *R, i
       const double half = pR + e * (double)NLp[i];                     // S_p_b - (lower bound of p)
       const double lraw = pS - half;
       const double lcl = fmin(fmax(lraw, 0.0), 1.0);
-      ps[i] = (float)pS; pr[i] = (float)pR;
+      ps[i] = (float)pS; pr[i] = (float)fmax(pR, 0.0);
       lpv[i] = (float)lcl;
       slv[i] = (float)(lraw == lcl ? half : pS - lcl);
     }
@@ -747,6 +917,18 @@ int layernorm(CState x, int groups, int P, int E, int T, int n, int gps, int pn,
   const double C = (double)P * E + 1, rows = (double)groups * T;
   ProfScope prof(K_LAYERNORM, st, 40.0 * rows * C * n, 16.0 * rows * C * n);
   dim3 grid((unsigned)(groups * T)), block(kThreads);
+  const int per_slot = (P * E + kThreads / G - 1) / (kThreads / G);
+  if (P <= 1 && VEC == 1 && per_slot <= 16) {   // the token's block fits the register file: read it once
+#define LNC_LAUNCH(ROWS)                                                                                         \
+  hipLaunchKernelGGL((layernorm_cached_kernel<ROWS>), grid, block, 0, st, x.S, x.R, P * E, T, n, G, gps, pn, eps, \
+                     gamma, beta, ln_eps, y.S, y.R, status)
+    if (per_slot <= 4) LNC_LAUNCH(4);
+    else if (per_slot <= 8) LNC_LAUNCH(8);
+    else LNC_LAUNCH(16);
+#undef LNC_LAUNCH
+    TV_HIP(hipGetLastError());
+    return TV_OK;
+  }
 #define LN_LAUNCH(V)                                                                                               \
   hipLaunchKernelGGL((layernorm_kernel<V>), grid, block, 0, st, x.S, x.R, P, E, T, n, G, gps, pn, eps, gamma, beta, \
                      ln_eps, y.S, y.R, status)

@@ -138,6 +138,20 @@ def test_chunked_batch_equals_resident_batch(tv):
     model.close()
 
 
+def test_certify_with_and_without_cached_first_projection(tv):
+    """tv_certify keeps the first layer's q/k/v across probes when the workspace has room; a workspace a few
+    KB short of that recomputes it in every probe and must return the same radii."""
+    w = CONFIGS["c1"]
+    model = tv.Model(make_model(w))
+    tok, pos = dev(make_tokens(w, 4)), dev(make_positions(w, 4))
+    full, _ = model.workspace_query(4, w.seq_len, 1)
+    a = model.certify(tok, pos, 2, 0.0, 0.5, 8, workspace=torch.empty(full, dtype=torch.uint8, device="cuda:0"))
+    b = model.certify(tok, pos, 2, 0.0, 0.5, 8, workspace=torch.empty(full - 4096, dtype=torch.uint8, device="cuda:0"))
+    assert torch.equal(a["eps"], b["eps"]) and torch.equal(a["status"], b["status"])
+    assert float(a["eps"].max()) > 0.0
+    model.close()
+
+
 def test_soundness_at_full_c2_shape(tv):
     """Property that holds at any size: sampled perturbed forward passes stay inside the GPU bounds."""
     import plain_forward as pf
