@@ -42,7 +42,7 @@ class _Weights(C.Structure):
 _lib = None
 
 EXPORTS = ("tv_version", "tv_last_error", "tv_model_create", "tv_model_destroy", "tv_workspace_query", "tv_verify",
-           "tv_certify", "tv_op_concretize", "tv_op_abs", "tv_op_affine", "tv_op_activation", "tv_op_layernorm",
+           "tv_certify", "tv_op_concretize", "tv_op_abs", "tv_op_affine", "tv_op_split3", "tv_op_affine_split", "tv_op_activation", "tv_op_layernorm",
            "tv_attention_workspace", "tv_op_attention", "tv_profile_enable", "tv_profile_reset",
            "tv_profile_kinds", "tv_profile_get")
 
@@ -69,6 +69,8 @@ def lib():
         L.tv_op_concretize.argtypes = [vp, vp, i, i, i, i, i, i, i, vp, vp, vp, vp]
         L.tv_op_abs.argtypes = [vp, vp, sz, vp]
         L.tv_op_affine.argtypes = [vp, vp, i, i, i, i, i, i, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.tv_op_split3.argtypes = [vp, vp, sz, i, vp]
+        L.tv_op_affine_split.argtypes = [vp, vp, i, i, i, i, i, i, vp, vp, vp, vp, vp, vp, vp, vp]
         L.tv_op_activation.argtypes = [i, vp, vp, i, i, i, i, i, i, i, vp, vp, vp, vp, vp]
         L.tv_op_layernorm.argtypes = [vp, vp, i, i, i, i, i, i, i, vp, vp, vp, f, vp, vp, vp, vp]
         L.tv_op_attention.argtypes = [vp] * 6 + [i] * 6 + [vp] * 5 + [i, vp, vp, sz, vp]
@@ -216,6 +218,26 @@ def op_affine(S, R, P, E, W, bias=None, add=None):
     _check(lib().tv_op_affine(_ptr(S), _ptr(R), G, P, E, T, K, N, _ptr(W), _ptr(Wabs), _ptr(bias),
                               _ptr(add[0]) if add else None, _ptr(add[1]) if add else None, _ptr(Sy), _ptr(Ry),
                               _stream()))
+    return Sy, Ry
+
+
+def op_split3(x, take_abs=False):
+    """bf16 pieces [3, *x.shape] (int16 bit patterns) of x or |x|."""
+    out = torch.empty((3,) + tuple(x.shape), dtype=torch.int16, device=x.device)
+    _check(lib().tv_op_split3(_ptr(x), _ptr(out), x.numel(), 1 if take_abs else 0, _stream()))
+    return out
+
+
+def op_affine_split(S, R, P, E, W, bias=None, add=None):
+    """op_affine through the split-bf16 kernel that tv_verify uses for the model's weight matrices."""
+    G, Cc, T, K = S.shape
+    N = W.shape[0]
+    W3, Wa3 = op_split3(W), op_split3(W, take_abs=True)
+    Sy = torch.empty(G, Cc, T, N, dtype=torch.float32, device=S.device)
+    Ry = torch.empty_like(Sy)
+    _check(lib().tv_op_affine_split(_ptr(S), _ptr(R), G, P, E, T, K, N, _ptr(W3), _ptr(Wa3), _ptr(bias),
+                                    _ptr(add[0]) if add else None, _ptr(add[1]) if add else None, _ptr(Sy),
+                                    _ptr(Ry), _stream()))
     return Sy, Ry
 
 

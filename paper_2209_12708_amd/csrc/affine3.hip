@@ -1,0 +1,296 @@
+// The affine bound of Eq. (2) with a constant weight matrix, y = x W^T, at fp32 accuracy on the bf16
+// matrix cores.
+//
+// An fp32 number is the exact sum of three bf16 numbers (8 + 8 + 8 mantissa bits, same exponent range):
+// x = x1 + x2 + x3.  A product of two bf16 numbers is exact in fp32, so
+//   x w = x1 w1 + (x1 w2 + x2 w1) + (x2 w2 + x1 w3 + x3 w1) + O(2^-24 |x w|)
+// and six bf16 MFMA products with fp32 accumulation reproduce the fp32 product to about one fp32
+// rounding.  On gfx950 one v_mfma_f32_32x32x16_bf16 does 16 k-steps in 32 cycles where the fp32
+// instruction (32x32x2) does 2 in 64: six of the former per 16 k-steps cost 192 cycles against 512,
+// which moves the affine layers of small encoders (K, N of 128..384) from the matrix-core roof to the
+// HBM roof.  The weights are split once when the model is created (split3); the state is split while
+// a tile is staged into LDS.
+//
+// Tiling as in gemm.hip: a workgroup of 4 waves owns a BM x BN tile, K advances in stages of 32 through
+// LDS with a register prefetch of the next stage, XCD-aware tile order.  LDS holds the three pieces of
+// both operands as [row][k] bf16 with rows padded to 80 bytes, so the 16-byte fragment reads of 16
+// consecutive rows fall on distinct 16-byte bank groups.
+#include "common.h"
+
+namespace tv {
+namespace {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+
+struct Affine3Args {
+  const float *A; long sA;              // [M][K] fp32; the two planes are sA floats apart
+  const unsigned short *W3; long sW;    // [3][N][K] bf16 pieces of W; planes (W, |W|) sW elements apart
+  float *C; long sC;                    // [M][N]
+  const float *Cadd; long sAdd;         // residual, same layout as C, or nullptr
+  const float *bias; long sBias;        // [N] added on bias rows, or nullptr
+  int bias_T, bias_C;                   // rows are (group, coefficient row, t): bias rows have r == bias_C - 1
+  int M, N, K;
+};
+
+// x = a + b + c exactly (up to the last piece's rounding, below 2^-24 |x|)
+__device__ __forceinline__ void split3(float x, __bf16 &a, __bf16 &b, __bf16 &c) {
+  a = (__bf16)x;
+  const float r1 = x - (float)a;
+  b = (__bf16)r1;
+  const float r2 = r1 - (float)b;
+  c = (__bf16)r2;
+}
+
+__global__ void split3_kernel(const float *in, unsigned short *out, size_t count, int take_abs) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  __bf16 *o = reinterpret_cast<__bf16 *>(out);
+  for (; i < count; i += stride) {
+    const float x = take_abs ? fabsf(in[i]) : in[i];
+    __bf16 a, b, c;
+    split3(x, a, b, c);
+    o[i] = a; o[count + i] = b; o[2 * count + i] = c;
+  }
+}
+
+template <int BM, int BN, int WM, int WN, int PF, int PB>
+__global__ __launch_bounds__(256) void affine3_kernel(const Affine3Args g, int mtiles, int ntiles) {
+  constexpr int BK = 32;
+  constexpr int RS = 80;                           // LDS row stride in bytes (32 bf16 + 16 bytes of padding)
+  constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
+  constexpr int A_P = BM * RS, B_P = BN * RS;      // bytes per piece
+  constexpr int A_F4 = BM * 8 / 256;               // float4 loads of A per thread and stage
+  constexpr int B_CH = 3 * BN * 4 / 256;           // 16-byte chunks of the weight pieces per thread and stage
+  static_assert(A_F4 >= 1 && B_CH >= 1 && (3 * BN * 4) % 256 == 0 && (BM * 8) % 256 == 0, "tile too small");
+  __shared__ __attribute__((aligned(16))) unsigned char lds[3 * A_P + 3 * B_P];
+  unsigned char *As = lds, *Bs = lds + 3 * A_P;
+
+  // XCD-aware tile order (see gemm.hip)
+  const int wid = blockIdx.x;
+  int mt, nt;
+  if (mtiles >= 8) {
+    const int xcd = wid & 7, slot = wid >> 3;
+    nt = slot % ntiles;
+    mt = (slot / ntiles) * 8 + xcd;
+    if (mt >= mtiles) return;
+  } else {
+    mt = wid % mtiles;
+    nt = wid / mtiles;
+  }
+  const int m0 = mt * BM, n0 = nt * BN;
+  const int z = blockIdx.y;
+  const float *A = g.A + z * g.sA;
+  const __bf16 *W3 = reinterpret_cast<const __bf16 *>(g.W3) + z * g.sW;
+  float *C = g.C + z * g.sC;
+  const float *Cadd = g.Cadd ? g.Cadd + z * g.sAdd : nullptr;
+  const float *bias = g.bias ? g.bias + z * g.sBias : nullptr;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WN, wn = wave % WN;
+  const int l32 = lane & 31, half = lane >> 5;
+  const int M = g.M, N = g.N, K = g.K;
+
+  const float *a_ptr[A_F4]; int a_k[A_F4], a_lds[A_F4];
+#pragma unroll
+  for (int i = 0; i < A_F4; ++i) {
+    const int f = tid + 256 * i, row = f / 8, kq = f % 8;
+    int m = m0 + row; if (m >= M) m = M - 1;
+    a_ptr[i] = A + (long)m * K;
+    a_k[i] = kq * 4;
+    a_lds[i] = row * RS + kq * 8;
+  }
+  const __bf16 *b_ptr[B_CH]; int b_k[B_CH], b_lds[B_CH];
+#pragma unroll
+  for (int i = 0; i < B_CH; ++i) {
+    const int f = tid + 256 * i, piece = f / (BN * 4), rem = f % (BN * 4), row = rem / 4, c = rem % 4;
+    int n = n0 + row; if (n >= N) n = N - 1;
+    b_ptr[i] = W3 + (long)piece * N * K + (long)n * K;
+    b_k[i] = c * 8;
+    b_lds[i] = piece * B_P + row * RS + c * 16;
+  }
+
+  // Register prefetch, PF stages of the state and PB of the weight pieces ahead of the products.  One stage
+  // each measured fastest on the layer shapes of the benchmark (deeper rings cost a workgroup per CU).
+  float4 ra[PF][A_F4]; uint4 rb[PB][B_CH];
+  auto load_a = [&](float4 (&r)[A_F4], int k0) {
+#pragma unroll
+    for (int i = 0; i < A_F4; ++i) {
+      const int k = k0 + a_k[i];
+      r[i] = k < K ? *reinterpret_cast<const float4 *>(a_ptr[i] + k) : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+  };
+  auto load_b = [&](uint4 (&r)[B_CH], int k0) {
+#pragma unroll
+    for (int i = 0; i < B_CH; ++i) {
+      const int k = k0 + b_k[i];
+      r[i] = k < K ? *reinterpret_cast<const uint4 *>(b_ptr[i] + k) : make_uint4(0u, 0u, 0u, 0u);
+    }
+  };
+  auto store_stage = [&](const float4 (&xa)[A_F4], const uint4 (&xb)[B_CH]) {
+#pragma unroll
+    for (int i = 0; i < A_F4; ++i) {
+      bf16x4 p0, p1, p2;
+      const float x[4] = {xa[i].x, xa[i].y, xa[i].z, xa[i].w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        __bf16 a, b, c;
+        split3(x[e], a, b, c);
+        p0[e] = a; p1[e] = b; p2[e] = c;
+      }
+      *reinterpret_cast<bf16x4 *>(As + a_lds[i]) = p0;
+      *reinterpret_cast<bf16x4 *>(As + A_P + a_lds[i]) = p1;
+      *reinterpret_cast<bf16x4 *>(As + 2 * A_P + a_lds[i]) = p2;
+    }
+#pragma unroll
+    for (int i = 0; i < B_CH; ++i) *reinterpret_cast<uint4 *>(Bs + b_lds[i]) = xb[i];
+  };
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  const int KT = (K + BK - 1) / BK;
+#pragma unroll
+  for (int s = 0; s < PF; ++s) load_a(ra[s], s * BK);          // stages beyond K load zeros (never used)
+#pragma unroll
+  for (int s = 0; s < PB; ++s) load_b(rb[s], s * BK);
+  for (int kt0 = 0; kt0 < KT; kt0 += PF) {
+#pragma unroll
+    for (int s = 0; s < PF; ++s) {
+      const int kt = kt0 + s;
+      if (kt < KT) {                                           // uniform
+        store_stage(ra[s], rb[s % PB]);
+        __syncthreads();
+        if (kt + PF < KT) load_a(ra[s], (kt + PF) * BK);
+        if (kt + PB < KT) load_b(rb[s % PB], (kt + PB) * BK);
+        // lane l holds k = 8 (l / 32) .. + 7 of each 16-wide MFMA step, for row / column l % 32
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+          bf16x8 af[TM][3], bf[TN][3];
+#pragma unroll
+          for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int p = 0; p < 3; ++p)
+              af[i][p] = *reinterpret_cast<const bf16x8 *>(As + p * A_P + (wm * (BM / WM) + i * 32 + l32) * RS + ks * 32 + half * 16);
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int p = 0; p < 3; ++p)
+              bf[j][p] = *reinterpret_cast<const bf16x8 *>(Bs + p * B_P + (wn * (BN / WN) + j * 32 + l32) * RS + ks * 32 + half * 16);
+#pragma unroll
+          for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {   // small terms first
+              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i][2], bf[j][0], acc[i][j], 0, 0, 0);
+              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i][0], bf[j][2], acc[i][j], 0, 0, 0);
+              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i][1], bf[j][1], acc[i][j], 0, 0, 0);
+              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i][1], bf[j][0], acc[i][j], 0, 0, 0);
+              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i][0], bf[j][1], acc[i][j], 0, 0, 0);
+              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i][0], bf[j][0], acc[i][j], 0, 0, 0);
+            }
+        }
+        __syncthreads();
+      }
+    }
+  }
+
+  // ---- epilogue.  Accumulator v of lane l holds row 8*(v/4) + 4*(l/32) + v%4, column l%32.
+  bool tile_has_bias = false;
+  if (bias) {   // does this tile contain rows of a bias block at all?
+    const int ba = m0 / g.bias_T, bb = (min(m0 + BM, M) - 1) / g.bias_T;
+    tile_has_bias = (ba % g.bias_C) + (bb - ba) >= g.bias_C - 1;
+  }
+  int col[TN]; bool con[TN];
+#pragma unroll
+  for (int j = 0; j < TN; ++j) {
+    col[j] = n0 + wn * (BN / WN) + j * 32 + l32;
+    con[j] = col[j] < N;
+  }
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+    const int mb = m0 + wm * (BM / WM) + i * 32 + 4 * half;
+    if (Cadd) {
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        float add[16];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int m = mb + 8 * (v >> 2) + (v & 3);
+          add[v] = (m < M && con[j]) ? Cadd[(long)m * N + col[j]] : 0.f;
+        }
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][j][v] += add[v];
+      }
+    }
+    if (tile_has_bias) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int m = mb + 8 * (v >> 2) + (v & 3);
+        if (m < M && (m / g.bias_T) % g.bias_C == g.bias_C - 1) {
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+            if (con[j]) acc[i][j][v] += bias[col[j]];
+        }
+      }
+    }
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int m = mb + 8 * (v >> 2) + (v & 3);
+      if (m >= M) continue;
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        if (con[j]) C[(long)m * N + col[j]] = acc[i][j][v];
+    }
+  }
+}
+
+template <int BM, int BN, int WM, int WN, int PF = 1, int PB = 1>
+int launch3(const Affine3Args &g, int planes, hipStream_t st) {
+  const int mtiles = (g.M + BM - 1) / BM, ntiles = (g.N + BN - 1) / BN;
+  const long groups = mtiles >= 8 ? (long)((mtiles + 7) / 8) * 8 * ntiles : (long)mtiles * ntiles;
+  TV_REQUIRE(groups < (1L << 31), TV_E_SHAPE, "affine: grid too large");
+  hipLaunchKernelGGL((affine3_kernel<BM, BN, WM, WN, PF, PB>), dim3((unsigned)groups, (unsigned)planes, 1), dim3(256), 0, st, g,
+                     mtiles, ntiles);
+  TV_HIP(hipGetLastError());
+  return TV_OK;
+}
+
+}  // namespace
+
+int split_bf16x3(const float *in, unsigned short *out, size_t count, bool take_abs, hipStream_t st) {
+  TV_REQUIRE(in && out, TV_E_NULL, "split_bf16x3: null pointer");
+  if (count == 0) return TV_OK;
+  const unsigned blocks = (unsigned)((count + 255) / 256 > 4096 ? 4096 : (count + 255) / 256);
+  hipLaunchKernelGGL(split3_kernel, dim3(blocks), dim3(256), 0, st, in, out, count, take_abs ? 1 : 0);
+  TV_HIP(hipGetLastError());
+  return TV_OK;
+}
+
+int affine_split(const float *xS, long xplane, long M, int C, int T, int K, int N, const unsigned short *W3pair,
+                 const float *bpair, const float *addS, long addplane, float *yS, long yplane, hipStream_t st, int planes) {
+  TV_REQUIRE(planes == 1 || planes == 2, TV_E_ARG, "affine: planes must be 1 or 2");
+  TV_REQUIRE(xS && W3pair && yS, TV_E_NULL, "affine: null operand");
+  TV_REQUIRE(M > 0 && M < (1L << 31) && N > 0 && K > 0 && K % 8 == 0, TV_E_SHAPE,
+             "affine (split weights): need 0 < M < 2^31, K %% 8 == 0 (M=%ld N=%d K=%d)", M, N, K);
+  TV_REQUIRE(bpair == nullptr || (T > 0 && C > 0), TV_E_ARG, "affine: bias without row structure");
+  Affine3Args g;
+  g.A = xS; g.sA = xplane;
+  g.W3 = W3pair; g.sW = 3L * N * K;
+  g.C = yS; g.sC = yplane;
+  g.Cadd = addS; g.sAdd = addplane;
+  g.bias = bpair; g.sBias = N; g.bias_T = T; g.bias_C = C;
+  g.M = (int)M; g.N = N; g.K = K;
+  const double mn = (double)M * N;
+  ProfScope prof(K_AFFINE, st, planes * 2.0 * mn * K,
+                 planes * 4.0 * ((double)M * K + (double)N * K + mn * (addS ? 2.0 : 1.0)));
+  if (N <= 64) return launch3<128, 64, 2, 2>(g, planes, st);
+  return launch3<64, 128, 2, 2>(g, planes, st);
+}
+
+}  // namespace tv

@@ -66,6 +66,16 @@ struct GemmArgs {
 };
 int gemm(const GemmArgs &g, hipStream_t st);
 
+// ---- affine layers with constant weights on the bf16 matrix cores at fp32 accuracy (affine3.hip) ----
+// out[p][i] = p-th bf16 piece of in[i] (or of |in[i]|), p = 0..2: in = out[0] + out[1] + out[2]
+int split_bf16x3(const float *in, unsigned short *out, size_t count, bool take_abs, hipStream_t st);
+// y = x W^T (+ bias on bias rows of the centre plane) (+ add) for both planes in one launch.  W3pair:
+// [2][3][N][K] bf16 pieces of (W, |W|); bpair: [2][N] = (b, 0) or nullptr; planes of x / add / y are xplane /
+// addplane / yplane floats apart; rows are (group, coefficient row of C, t of T).  K % 8 == 0.
+int affine_split(const float *xS, long xplane, long M, int C, int T, int K, int N, const unsigned short *W3pair,
+                 const float *bpair, const float *addS, long addplane, float *yS, long yplane, hipStream_t st,
+                 int planes = 2);
+
 // ---- elementwise / reduction kernels (rowops.hip) ------------------------------------------
 // States are [groups][C][T][n]; eps is indexed by group / gps (groups per sentence).
 // concretize: mode 0 -> (o0, o1) = (l, u); mode 1 -> (mid, half) = ((u+l)/2, (u-l)/2), each accurate in

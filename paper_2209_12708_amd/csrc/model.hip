@@ -180,6 +180,8 @@ struct tv_layer_dev {
   float *W1, *b1;       // [2][F][D], [2][F]
   float *W2, *b2;       // [2][D][F], [2][D]
   float *ln1_g, *ln1_b, *ln2_g, *ln2_b;
+  // bf16 pieces of the same matrices, [2][3][N][K] (W, then |W|), or nullptr when K is not a multiple of 8
+  unsigned short *Wqkv3 = nullptr, *Wo3 = nullptr, *W13 = nullptr, *W23 = nullptr;
 };
 struct tv_model {
   tv_config cfg;
@@ -242,8 +244,10 @@ int chunk_size(const tv_config &c, int B, int L, int P, size_t ws_bytes, bool ca
 
 // Eq. (2) in centre/radius form: y = x W^T (+ bias on bias rows of the S plane) (+ add).  Wpair =
 // [W ; |W|], bpair = [b ; 0].  x planes are `xplane` floats apart, y planes `yplane`.
-int affine(const float *xS, long xplane, long M, int C, int T, int K, int N, const float *Wpair, const float *bpair,
-           const float *addS, long addplane, float *yS, long yplane, hipStream_t st) {
+int affine(const float *xS, long xplane, long M, int C, int T, int K, int N, const float *Wpair,
+           const unsigned short *W3pair, const float *bpair, const float *addS, long addplane, float *yS, long yplane,
+           hipStream_t st) {
+  if (W3pair) return affine_split(xS, xplane, M, C, T, K, N, W3pair, bpair, addS, addplane, yS, yplane, st);
   GemmArgs g;
   g.A = xS; g.lda = K;
   g.B = Wpair; g.ldb = K; g.b_mode = 0;
@@ -276,8 +280,8 @@ int project_input(const tv_model *m, const Plan &pl, float *w, const int32_t *to
   const int D = m->cfg.hidden, C = P * D + 1;
   const long M = (long)Bc * L * C;
   if (int rc = init_input(m, pl, w, tokens, positions, Bc, L, P, st)) return rc;
-  return affine(w + pl.x, M * D, M, C, L, D, 3 * D, m->layers[0].Wqkv, m->layers[0].bqkv, nullptr, 0, w + pl.qkv0,
-                M * 3 * D, st);
+  return affine(w + pl.x, M * D, M, C, L, D, 3 * D, m->layers[0].Wqkv, m->layers[0].Wqkv3, m->layers[0].bqkv, nullptr, 0,
+                w + pl.qkv0, M * 3 * D, st);
 }
 
 // one pass of the encoder.  qkv0: the cached first-layer projection (project_input), or nullptr to compute it.
@@ -300,21 +304,21 @@ int sweep(const tv_model *m, const Plan &pl, float *w, const int32_t *tokens, co
     // q, k, v in one product: columns [0,D) q, [D,2D) k, [2D,3D) v
     const float *Q = QKV;
     if (l == 0 && qkv0) Q = qkv0;
-    else if (int rc = affine(X, pD, M, C, L, D, 3 * D, lw.Wqkv, lw.bqkv, nullptr, 0, QKV, p3D, st)) return rc;
+    else if (int rc = affine(X, pD, M, C, L, D, 3 * D, lw.Wqkv, lw.Wqkv3, lw.bqkv, nullptr, 0, QKV, p3D, st)) return rc;
     CState q{Q, Q + p3D}, k{Q + D, Q + p3D + D}, v{Q + 2 * D, Q + p3D + 2 * D};
     State o{T1, T1 + pD}, s{BIG, BIG + pS};
     if (int rc = attention(q, k, v, 3 * D, Bc, L, H, D, P, pn, eps, o, s, 0, status, attn_ws, attn_bytes, st))
       return rc;
     // a = o Wo^T + bo + x   (written over the dead q/k/v region), x' = LN(a) (over the dead x)
     float *A = QKV;
-    if (int rc = affine(T1, pD, M, C, L, D, D, lw.Wo, lw.bo, X, pD, A, pD, st)) return rc;
+    if (int rc = affine(T1, pD, M, C, L, D, D, lw.Wo, lw.Wo3, lw.bo, X, pD, A, pD, st)) return rc;
     if (int rc = layernorm(CState{A, A + pD}, Bc, P, D, L, D, 1, pn, eps, lw.ln1_g, lw.ln1_b, c.ln_eps,
                            State{X, X + pD}, status, st)) return rc;
     // feed-forward: h = x' W1^T + b1 ; act ; f = act W2^T + b2 + x' ; x'' = LN(f)
-    if (int rc = affine(X, pD, M, C, L, D, F, lw.W1, lw.b1, nullptr, 0, BIG, pF, st)) return rc;
+    if (int rc = affine(X, pD, M, C, L, D, F, lw.W1, lw.W13, lw.b1, nullptr, 0, BIG, pF, st)) return rc;
     if (int rc = activation(c.activation, CState{BIG, BIG + pF}, Bc, P, D, L, F, 1, pn, eps,
                             State{BIG, BIG + pF}, status, st)) return rc;
-    if (int rc = affine(BIG, pF, M, C, L, F, D, lw.W2, lw.b2, X, pD, T1, pD, st)) return rc;
+    if (int rc = affine(BIG, pF, M, C, L, F, D, lw.W2, lw.W23, lw.b2, X, pD, T1, pD, st)) return rc;
     if (int rc = layernorm(CState{T1, T1 + pD}, Bc, P, D, L, D, 1, pn, eps, lw.ln2_g, lw.ln2_b, c.ln_eps,
                            State{X, X + pD}, status, st)) return rc;
   }
@@ -421,7 +425,7 @@ int tv_model_create(const tv_config *cfg, const tv_weights *w, tv_model **out) {
   auto take = [&](size_t n) { size_t r = o; o += align_up(n); return r; };
   const size_t o_tok = take((size_t)c.vocab * D), o_pos = take((size_t)c.max_len * D);
   const size_t o_wc = take((size_t)c.n_classes * D), o_bc = take(c.n_classes);
-  struct Off { size_t Wqkv, bqkv, Wo, bo, W1, b1, W2, b2, g1, be1, g2, be2; };
+  struct Off { size_t Wqkv, bqkv, Wo, bo, W1, b1, W2, b2, g1, be1, g2, be2, Wqkv3, Wo3, W13, W23; };
   std::vector<Off> off(c.n_layers);
   for (int l = 0; l < c.n_layers; ++l) {
     Off &f = off[l];
@@ -430,6 +434,8 @@ int tv_model_create(const tv_config *cfg, const tv_weights *w, tv_model **out) {
     f.W1 = take(2 * F * D); f.b1 = take(2 * F);
     f.W2 = take(2 * D * F); f.b2 = take(2 * D);
     f.g1 = take(D); f.be1 = take(D); f.g2 = take(D); f.be2 = take(D);
+    // bf16 pieces [2][3][n] of each matrix: 6 n halves = 3 n floats
+    f.Wqkv3 = take(3 * 3 * D * D); f.Wo3 = take(3 * D * D); f.W13 = take(3 * F * D); f.W23 = take(3 * D * F);
   }
   m->blob_floats = o;
   hipError_t e = hipMalloc(&m->blob, o * sizeof(float));
@@ -441,6 +447,12 @@ int tv_model_create(const tv_config *cfg, const tv_weights *w, tv_model **out) {
   };
   auto put_abs = [&](size_t base, size_t n) {   // second copy = |first copy|
     if (e == hipSuccess && tv::vec_abs(m->blob + base, m->blob + base + n, n, nullptr) != TV_OK) e = hipErrorUnknown;
+  };
+  auto put_split = [&](size_t src, size_t dst, size_t n) {   // pieces of the first copy, then of its absolute value
+    unsigned short *o3 = reinterpret_cast<unsigned short *>(m->blob + dst);
+    if (e == hipSuccess && (tv::split_bf16x3(m->blob + src, o3, n, false, nullptr) != TV_OK ||
+                            tv::split_bf16x3(m->blob + src, o3 + 3 * n, n, true, nullptr) != TV_OK))
+      e = hipErrorUnknown;
   };
   put(o_tok, w->tok_emb, (size_t)c.vocab * D); put(o_pos, w->pos_emb, (size_t)c.max_len * D);
   put(o_wc, w->Wc, (size_t)c.n_classes * D); put(o_bc, w->bc, c.n_classes);
@@ -459,6 +471,16 @@ int tv_model_create(const tv_config *cfg, const tv_weights *w, tv_model **out) {
     d.Wqkv = m->blob + f.Wqkv; d.bqkv = m->blob + f.bqkv; d.Wo = m->blob + f.Wo; d.bo = m->blob + f.bo;
     d.W1 = m->blob + f.W1; d.b1 = m->blob + f.b1; d.W2 = m->blob + f.W2; d.b2 = m->blob + f.b2;
     d.ln1_g = m->blob + f.g1; d.ln1_b = m->blob + f.be1; d.ln2_g = m->blob + f.g2; d.ln2_b = m->blob + f.be2;
+    if (D % 8 == 0) {
+      put_split(f.Wqkv, f.Wqkv3, 3 * D * D); put_split(f.Wo, f.Wo3, D * D); put_split(f.W1, f.W13, F * D);
+      d.Wqkv3 = reinterpret_cast<unsigned short *>(m->blob + f.Wqkv3);
+      d.Wo3 = reinterpret_cast<unsigned short *>(m->blob + f.Wo3);
+      d.W13 = reinterpret_cast<unsigned short *>(m->blob + f.W13);
+    }
+    if (F % 8 == 0) {
+      put_split(f.W2, f.W23, D * F);
+      d.W23 = reinterpret_cast<unsigned short *>(m->blob + f.W23);
+    }
   }
   if (e == hipSuccess) e = hipDeviceSynchronize();
   if (e != hipSuccess) {
@@ -625,6 +647,26 @@ int tv_op_affine(const float *Sx, const float *Rx, int groups, int P, int E, int
   if (int rc = gemm(g, st)) return rc;
   g.A = Rx; g.B = Wabs; g.C = Ry; g.Cadd = Radd; g.bias = nullptr;
   return gemm(g, st);
+}
+
+int tv_op_split3(const float *in, uint16_t *out, size_t count, int take_abs, void *stream) {
+  return split_bf16x3(in, out, count, take_abs != 0, static_cast<hipStream_t>(stream));
+}
+
+int tv_op_affine_split(const float *Sx, const float *Rx, int groups, int P, int E, int T, int K, int N,
+                       const uint16_t *W3, const uint16_t *Wabs3, const float *bias, const float *Sadd,
+                       const float *Radd, float *Sy, float *Ry, void *stream) {
+  TV_REQUIRE(Sx && Rx && W3 && Wabs3 && Sy && Ry, TV_E_NULL, "tv_op_affine_split: null pointer");
+  TV_REQUIRE((Sadd == nullptr) == (Radd == nullptr), TV_E_NULL,
+             "tv_op_affine_split: Sadd and Radd must both be given or both NULL");
+  TV_REQUIRE(groups > 0 && P >= 0 && E > 0 && T > 0 && K > 0 && N > 0 && K % 8 == 0 && N % 4 == 0, TV_E_SHAPE,
+             "tv_op_affine_split: bad shape groups=%d P=%d E=%d T=%d K=%d N=%d", groups, P, E, T, K, N);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int C = P * E + 1;
+  const long M = (long)groups * C * T;
+  // the two planes use unrelated buffers here: one launch per plane (plane stride 0, second plane skipped)
+  if (int rc = affine_split(Sx, 0, M, C, T, K, N, W3, bias, Sadd, 0, Sy, 0, st, 1)) return rc;
+  return affine_split(Rx, 0, M, C, T, K, N, Wabs3, nullptr, Radd, 0, Ry, 0, st, 1);
 }
 
 int tv_op_activation(int act, const float *Sx, const float *Rx, int groups, int P, int E, int T, int n, int gps, int pn,

@@ -91,6 +91,44 @@ def test_affine(tv, G, T, P, E, K, N, bias, add):
     assert_state_close(host(out), Y, "affine")
 
 
+@pytest.mark.parametrize("G,T,P,E,K,N,bias,add", [
+    (1, 3, 1, 40, 40, 72, True, False),       # ragged M, N tails, K = 32 + 8
+    (2, 2, 2, 64, 64, 192, True, True),       # two N tiles, residual, bias rows of two groups
+    (1, 1, 1, 96, 256, 64, False, False),     # several K stages, the N <= 64 tile
+    (5, 1, 1, 33, 24, 20, True, True),        # K below one stage, tiny N
+    (1, 2, 1, 300, 128, 128, True, False),    # > 2 M tiles
+    (2, 5, 1, 64, 64, 384, True, False),      # T not a power of two, three N tiles
+])
+def test_affine_split_weights(tv, G, T, P, E, K, N, bias, add):
+    """The kernel the encoder sweep uses for constant weights: three bf16 pieces per fp32 operand, six MFMA
+    products, fp32 accumulation - held to the same tolerance as the fp32 kernel."""
+    rng = np.random.default_rng(G + T + K + N + 1)
+    X = quantize(random_state(rng, (G * T, K), P, E, 0.3, 2), G)
+    W = rng.standard_normal((N, K)).astype(np.float32)
+    c = rng.standard_normal(N).astype(np.float32) if bias else None
+    Y = B.affine(X, W.astype(np.float64), None if c is None else c.astype(np.float64))
+    addp = None
+    if add:
+        A = quantize(random_state(rng, (G * T, N), P, E, 0.3, 2), G)
+        Y = B.add(Y, A)
+        addp = planes_dev(A, G)
+    S, R = planes_dev(X, G)
+    out = tv.op_affine_split(S, R, P, E, dev(W), None if c is None else dev(c), addp)
+    assert_state_close(host(out), Y, "affine (split weights)")
+
+
+def test_split3_pieces_sum_to_the_input(tv):
+    rng = np.random.default_rng(5)
+    x = (rng.standard_normal(4096) * 10.0 ** rng.uniform(-6, 6, 4096)).astype(np.float32)
+    x[:4] = [0.0, -0.0, 1.0, -3.0e-39]
+    for take_abs in (False, True):
+        pieces = tv.op_split3(dev(x), take_abs).cpu().numpy().view(np.uint16).astype(np.uint32) << 16
+        total = pieces.view(np.float32).astype(np.float64).sum(0)
+        ref = np.abs(x) if take_abs else x
+        # denormal inputs may be flushed: allow the smallest normal number as absolute slack
+        assert np.all(np.abs(total - ref) <= 2.0 ** -23 * np.abs(ref) + 1.2e-38)
+
+
 @pytest.mark.parametrize("p", NORMS)
 @pytest.mark.parametrize("act,name", [(0, "relu"), (1, "tanh"), (2, "gelu")])
 def test_activation(tv, act, name, p):
