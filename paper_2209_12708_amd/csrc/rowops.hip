@@ -38,7 +38,8 @@ struct Geo {
   int slot;   // this thread's row slot
   int g;      // this thread's lane within the row
   int n4;     // float4 groups in the chunk
-  __device__ Geo(int G_, int n4_) : G(G_), NS(kThreads / G_), slot(threadIdx.x / G_), g(threadIdx.x % G_), n4(n4_) {}
+  __device__ Geo(int G_, int n4_, int threads = kThreads)
+      : G(G_), NS(threads / G_), slot(threadIdx.x / G_), g(threadIdx.x % G_), n4(n4_) {}
 };
 
 // position of a block of rows inside a state: group, rows per group, row, row length, first column
@@ -54,8 +55,8 @@ __device__ __forceinline__ float norm_fin(float a, int pn) { return pn == 2 ? sq
 __device__ __forceinline__ bool finite_d(double x) { return fabs(x) <= 3.4028234663852886e38; }
 
 // Combine CNT per-lane partials across the row slots; afterwards every thread holds the totals of its
-// own columns.  red: LDS [4][64][CNT].  `mx`: combine with max instead of +.
-template <int CNT>
+// own columns.  red: LDS [NW][64][CNT] (NW waves per workgroup).  `mx`: combine with max instead of +.
+template <int CNT, int NW = 4>
 __device__ __forceinline__ void slot_reduce(float (&x)[CNT], const Geo &ge, bool mx, float *red) {
   for (int off = ge.G; off < kWave; off <<= 1) {
 #pragma unroll
@@ -75,7 +76,7 @@ __device__ __forceinline__ void slot_reduce(float (&x)[CNT], const Geo &ge, bool
   for (int i = 0; i < CNT; ++i) {
     float t = red[(0 * kWave + ge.g) * CNT + i];
 #pragma unroll
-    for (int w = 1; w < 4; ++w) {
+    for (int w = 1; w < NW; ++w) {
       const float o = red[(w * kWave + ge.g) * CNT + i];
       t = mx ? fmaxf(t, o) : t + o;
     }
@@ -226,10 +227,11 @@ __device__ __forceinline__ void apply_maps(const float *S, const float *R, float
 // ------------------------------------------------------------------------------------------------
 // Eq. (1) on the flat [T*n] axis of a group.  grid = (groups, column chunks).
 // mode 0 writes (l, u); mode 1 writes (mid, half) and, if o2 != nullptr, the slack S_b - l = R_b + e NL.
-template <int VEC>
+template <int VEC, int PN>
 __global__ __launch_bounds__(kThreads) void concretize_kernel(const float *S, const float *R, int P, int E, int X,
-                                                              int G, int gps, int pn, const float *eps,
+                                                              int G, int gps, const float *eps,
                                                               float *o0, float *o1, float *o2, int mode) {
+  constexpr int pn = PN;   // the norm is a compile-time constant: no selects in the accumulation loops
   __shared__ float red[4 * kWave * 8 * VEC];
   const int chunk = 4 * G * VEC, c0 = blockIdx.y * chunk;
   const Geo ge(G, min(chunk, X - c0) / 4);
@@ -280,10 +282,11 @@ __device__ __forceinline__ Form gelu_inner(double lx, double ux, double &lb, dou
   return form_sub(a, k * c3, k, k * c3, k);
 }
 
-template <int VEC, int ACT>
+template <int VEC, int ACT, int PN>
 __global__ __launch_bounds__(kThreads) void activation_kernel(const float *S, const float *R, int P, int E, int X,
-                                                              int G, int gps, int pn, const float *eps,
+                                                              int G, int gps, const float *eps,
                                                               float *So, float *Ro, int32_t *status) {
+  constexpr int pn = PN;
   __shared__ float red[4 * kWave * 8 * VEC];
   const int chunk = 4 * G * VEC, c0 = blockIdx.y * chunk;
   const Geo ge(G, min(chunk, X - c0) / 4);
@@ -378,11 +381,12 @@ __device__ __forceinline__ LnScalars ln_scalars(double lv, double uv, double ln_
   return o;
 }
 
-template <int VEC>
+template <int VEC, int PN>
 __global__ __launch_bounds__(kThreads) void layernorm_kernel(const float *S, const float *R, int P, int E, int T_, int n,
-                                                             int G, int gps, int pn, const float *eps,
+                                                             int G, int gps, const float *eps,
                                                              const float *gamma, const float *beta, float ln_eps_f,
                                                              float *So, float *Ro, int32_t *status) {
+  constexpr int pn = PN;
   __shared__ float red[4 * kWave * 8 * VEC];
   const int C = P * E + 1;
   const Geo ge(G, n / 4);
@@ -539,15 +543,17 @@ __global__ __launch_bounds__(kThreads) void layernorm_kernel(const float *S, con
 // LayerNorm for small blocks (one perturbed position, at most ROWS coefficient rows per row slot, one
 // float4 per lane): the token's block is read once, all loads in flight together, and kept centred in
 // registers for the three sweeps.
-template <int ROWS>
-__global__ __launch_bounds__(kThreads, 2) void layernorm_cached_kernel(const float *S, const float *R, int nrows, int T_,
-                                                                    int n, int G, int gps, int pn, const float *eps,
+template <int ROWS, int NT, int PN>
+__global__ __launch_bounds__(NT) void layernorm_cached_kernel(const float *S, const float *R, int nrows, int T_,
+                                                                    int n, int G, int gps, const float *eps,
                                                                     const float *gamma, const float *beta,
                                                                     float ln_eps_f, float *So, float *Ro,
                                                                     int32_t *status) {
-  __shared__ float red[4 * kWave * 8];
+  constexpr int NW = NT / kWave;
+  constexpr int pn = PN;
+  __shared__ float red[NW * kWave * 8];
   const int C = nrows + 1;
-  const Geo ge(G, n / 4);
+  const Geo ge(G, n / 4, NT);
   const Loc lc{(long)(blockIdx.x / T_), C, T_, (int)(blockIdx.x % T_), n, 0};
   const int sent = (int)(lc.grp / gps);
   const double e = eps[sent];
@@ -573,9 +579,13 @@ __global__ __launch_bounds__(kThreads, 2) void layernorm_cached_kernel(const flo
 #pragma unroll
   for (int it = 0; it < ROWS; ++it)
     if (ge.slot + it * ge.NS < nrows) ln_centre<1, float>(cs[it], cr[it], n, ge, cs[it], cr[it]);
+  // Per-column and per-token scalars (double precision) are computed once, by row slot 0, and published through
+  // LDS: the other waves of the workgroup do not issue that code at all.
+  __shared__ float colf[2][4 * kWave];      // slope of the square relaxation, lower bound of c, per column
+  __shared__ float tokf[8];                 // rho's map and the product coefficients, per token
   // ---- sweep 1: range of c, slope of the square relaxation
-  double cl[4], cu[4], csb[4], crb[4];
-  float NLc[4], kq[4];
+  double cl[4], cu[4], csb[4], crb[4];      // slot 0 only
+  float NLc[4];
   {
     float acc[8];
 #pragma unroll
@@ -590,22 +600,31 @@ __global__ __launch_bounds__(kThreads, 2) void layernorm_cached_kernel(const flo
         }
       }
     }
-    slot_reduce<8>(acc, ge, pn == 1, red);
-    float xs[4], xr[4];
-    load_row<1>(S, R, lc, C - 1, ge, xs, xr);
-    ln_centre<1, double>(xs, xr, n, ge, csb, crb);
+    slot_reduce<8, NW>(acc, ge, pn == 1, red);
+    if (ge.slot == 0) {
+      float xs[4], xr[4];
+      load_row<1>(S, R, lc, C - 1, ge, xs, xr);
+      ln_centre<1, double>(xs, xr, n, ge, csb, crb);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      NLc[i] = norm_fin(acc[2 * i], pn);
-      range_of(csb[i], crb[i], e, NLc[i], norm_fin(acc[2 * i + 1], pn), cl[i], cu[i]);
-      if (colon) bad |= !(finite_d(cl[i]) && finite_d(cu[i]));
-      else { cl[i] = cu[i] = 0.0; csb[i] = crb[i] = 0.0; }
-      kq[i] = (float)(cl[i] + cu[i]);
+      for (int i = 0; i < 4; ++i) {
+        NLc[i] = norm_fin(acc[2 * i], pn);
+        range_of(csb[i], crb[i], e, NLc[i], norm_fin(acc[2 * i + 1], pn), cl[i], cu[i]);
+        if (colon) bad |= !(finite_d(cl[i]) && finite_d(cu[i]));
+        else { cl[i] = cu[i] = 0.0; csb[i] = crb[i] = 0.0; }
+        colf[0][4 * ge.g + i] = (float)(cl[i] + cu[i]);
+        colf[1][4 * ge.g + i] = (float)cl[i];
+      }
     }
   }
+  __syncthreads();
+  float kq[4], lcf[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) { kq[i] = colf[0][4 * ge.g + i]; lcf[i] = colf[1][4 * ge.g + i]; }
   // ---- sweep 2: v = mean_d q + ln_eps, one value per coefficient row
   float vS[ROWS], vR[ROWS];
-  double lv, uv, vSb, vRb;
+  double vSb = 0.0, vRb = 0.0;
+  Map2 mr;
+  Mul2 mc;
   {
     float acc[2] = {0.f, 0.f};
 #pragma unroll
@@ -620,43 +639,50 @@ __global__ __launch_bounds__(kThreads, 2) void layernorm_cached_kernel(const flo
         acc[1] = norm_acc(acc[1], vS[it] + vR[it], pn);
       }
     }
-    slot_reduce<2>(acc, ge, pn == 1, red);
-    double a = 0.0, b = 0.0;
+    slot_reduce<2, NW>(acc, ge, pn == 1, red);
+    if (ge.slot == 0) {
+      double a = 0.0, b = 0.0;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const double k = cl[i] + cu[i], m = 0.5 * k, w = cu[i] - cl[i];
-      a += k * csb[i] - 0.5 * (m * m + cl[i] * cu[i]);
-      b += fabs(k) * crb[i] + 0.125 * w * w;
+      for (int i = 0; i < 4; ++i) {
+        const double k = cl[i] + cu[i], m = 0.5 * k, w = cu[i] - cl[i];
+        a += k * csb[i] - 0.5 * (m * m + cl[i] * cu[i]);
+        b += fabs(k) * crb[i] + 0.125 * w * w;
+      }
+      vSb = row_sum<double>(a, ge.G) / (double)n + ln_eps;
+      vRb = row_sum<double>(b, ge.G) / (double)n;
+      double lv, uv;
+      range_of(vSb, vRb, e, norm_fin(acc[0], pn), norm_fin(acc[1], pn), lv, uv);
+      bad |= !(finite_d(lv) && finite_d(uv));
+      const LnScalars sc_ = ln_scalars(lv, uv, ln_eps);
+      mr = sc_.mr; mc = sc_.mc;
+      if (bad) status[sent] = 1;
+      if (ge.g == 0) {
+        tokf[0] = mr.sS; tokf[1] = mr.sR; tokf[2] = mr.rS; tokf[3] = mr.rR;
+        tokf[4] = mc.a1; tokf[5] = mc.a2; tokf[6] = mc.a3; tokf[7] = mc.a4;
+      }
     }
-    vSb = row_sum<double>(a, ge.G) / (double)n + ln_eps;
-    vRb = row_sum<double>(b, ge.G) / (double)n;
-    range_of(vSb, vRb, e, norm_fin(acc[0], pn), norm_fin(acc[1], pn), lv, uv);
-    bad |= !(finite_d(lv) && finite_d(uv));
   }
-  const LnScalars sc_ = ln_scalars(lv, uv, ln_eps);
-  const Map2 &mr = sc_.mr;
-  const Mul2 &mc = sc_.mc;
-  if (bad) status[sent] = 1;
+  __syncthreads();
+  const float m_sS = tokf[0], m_sR = tokf[1], m_rS = tokf[2], m_rR = tokf[3];
+  const float c_a1 = tokf[4], c_a2 = tokf[5], c_a3 = tokf[6], c_a4 = tokf[7];
 
   // ---- sweep 3: y = c * rho, gamma / beta
-  float gm[4] = {0.f, 0.f, 0.f, 0.f}, bt[4] = {0.f, 0.f, 0.f, 0.f}, lcf[4];
+  float gm[4] = {0.f, 0.f, 0.f, 0.f}, bt[4] = {0.f, 0.f, 0.f, 0.f};
   if (colon) {
     const float4 a = reinterpret_cast<const float4 *>(gamma)[ge.g], b = reinterpret_cast<const float4 *>(beta)[ge.g];
     gm[0] = a.x; gm[1] = a.y; gm[2] = a.z; gm[3] = a.w;
     bt[0] = b.x; bt[1] = b.y; bt[2] = b.z; bt[3] = b.w;
   }
 #pragma unroll
-  for (int i = 0; i < 4; ++i) lcf[i] = (float)cl[i];
-#pragma unroll
   for (int it = 0; it < ROWS; ++it) {
     const int r = ge.slot + it * ge.NS;
     if (r < nrows) {
-      const float rhoS = mr.sS * vS[it] + mr.sR * vR[it], rhoR = mr.rS * vS[it] + mr.rR * vR[it];
+      const float rhoS = m_sS * vS[it] + m_sR * vR[it], rhoR = m_rS * vS[it] + m_rR * vR[it];
       float ys[4], yr[4];
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const float yS = mc.a1 * cs[it][i] + mc.a2 * cr[it][i] + lcf[i] * rhoS;
-        const float yR = mc.a3 * cs[it][i] + mc.a4 * cr[it][i] + fabsf(lcf[i]) * rhoR;
+        const float yS = c_a1 * cs[it][i] + c_a2 * cr[it][i] + lcf[i] * rhoS;
+        const float yR = c_a3 * cs[it][i] + c_a4 * cr[it][i] + fabsf(lcf[i]) * rhoR;
         ys[i] = gm[i] * yS; yr[i] = fabsf(gm[i]) * yR;
       }
       store_row<1>(So, Ro, lc, r, ge, ys, yr);
@@ -682,10 +708,11 @@ __global__ __launch_bounds__(kThreads, 2) void layernorm_cached_kernel(const flo
 // (g, i).   shift by max_j u_j ; e = exp (relaxed) ; sigma = sum_j e ; rho = 1 / sigma ; p = e * rho.
 // Sweeps: norms of s; norm of sigma; output p (and the norm of p's lower line for its concretized
 // lower bound).  Writes lp (clamped to [0, 1]) and the slack S_p_b - lp.
-template <int VEC>
+template <int VEC, int PN>
 __global__ __launch_bounds__(kThreads) void softmax_kernel(float *S, float *R, int P, int E, int T_, int n, int G,
-                                                           int gps, int pn, const float *eps, float *lp_out,
+                                                           int gps, const float *eps, float *lp_out,
                                                            float *slack_out, int32_t *status) {
+  constexpr int pn = PN;
   __shared__ float red[4 * kWave * 8 * VEC];
   const int C = P * E + 1;
   const Geo ge(G, n / 4);
@@ -856,6 +883,14 @@ int row_geo(int n, int &G, int &VEC) {
   return VEC <= kMaxVec;
 }
 
+// instantiate a launch for the norm given at run time
+#define NORM_SWITCH(pn, LAUNCH)            \
+  switch (pn) {                            \
+    case 1: LAUNCH(1); break;              \
+    case 2: LAUNCH(2); break;              \
+    default: LAUNCH(TV_NORM_INF); break;   \
+  }
+
 int check_common(const void *S, const void *R, int groups, int P, int E, int T, int n, int gps, int pn,
                  const float *eps) {
   TV_REQUIRE(S && R && eps, TV_E_NULL, "null state or eps pointer");
@@ -877,8 +912,11 @@ int concretize(CState x, int groups, int P, int E, int T, int n, int gps, int pn
   chunk_geo(X, G, nch);
   const double C = (double)P * E + 1;
   ProfScope prof(K_CONCRETIZE, st, 4.0 * groups * C * X, 8.0 * groups * C * X + 8.0 * groups * X);
-  hipLaunchKernelGGL((concretize_kernel<1>), dim3(groups, nch), dim3(kThreads), 0, st, x.S, x.R, P, E, (int)X, G, gps,
-                     pn, eps, o0, o1, o2, mode);
+#define CONC_LAUNCH(PN)                                                                                            \
+  hipLaunchKernelGGL((concretize_kernel<1, PN>), dim3(groups, nch), dim3(kThreads), 0, st, x.S, x.R, P, E, (int)X, G, \
+                     gps, eps, o0, o1, o2, mode)
+  NORM_SWITCH(pn, CONC_LAUNCH);
+#undef CONC_LAUNCH
   TV_HIP(hipGetLastError());
   return TV_OK;
 }
@@ -894,15 +932,20 @@ int activation(int act, CState x, int groups, int P, int E, int T, int n, int gp
   const double C = (double)P * E + 1;
   ProfScope prof(K_ACTIVATION, st, 12.0 * groups * C * X, 16.0 * groups * C * X);
   dim3 grid(groups, nch), block(kThreads);
-  if (act == TV_ACT_RELU)
-    hipLaunchKernelGGL((activation_kernel<1, TV_ACT_RELU>), grid, block, 0, st, x.S, x.R, P, E, (int)X, G, gps, pn, eps,
-                       y.S, y.R, status);
-  else if (act == TV_ACT_TANH)
-    hipLaunchKernelGGL((activation_kernel<1, TV_ACT_TANH>), grid, block, 0, st, x.S, x.R, P, E, (int)X, G, gps, pn, eps,
-                       y.S, y.R, status);
-  else
-    hipLaunchKernelGGL((activation_kernel<1, TV_ACT_GELU>), grid, block, 0, st, x.S, x.R, P, E, (int)X, G, gps, pn, eps,
-                       y.S, y.R, status);
+#define ACT_LAUNCH(PN)                                                                                              \
+  do {                                                                                                              \
+    if (act == TV_ACT_RELU)                                                                                         \
+      hipLaunchKernelGGL((activation_kernel<1, TV_ACT_RELU, PN>), grid, block, 0, st, x.S, x.R, P, E, (int)X, G, gps, \
+                         eps, y.S, y.R, status);                                                                    \
+    else if (act == TV_ACT_TANH)                                                                                    \
+      hipLaunchKernelGGL((activation_kernel<1, TV_ACT_TANH, PN>), grid, block, 0, st, x.S, x.R, P, E, (int)X, G, gps, \
+                         eps, y.S, y.R, status);                                                                    \
+    else                                                                                                            \
+      hipLaunchKernelGGL((activation_kernel<1, TV_ACT_GELU, PN>), grid, block, 0, st, x.S, x.R, P, E, (int)X, G, gps, \
+                         eps, y.S, y.R, status);                                                                    \
+  } while (0)
+  NORM_SWITCH(pn, ACT_LAUNCH);
+#undef ACT_LAUNCH
   TV_HIP(hipGetLastError());
   return TV_OK;
 }
@@ -917,27 +960,40 @@ int layernorm(CState x, int groups, int P, int E, int T, int n, int gps, int pn,
   const double C = (double)P * E + 1, rows = (double)groups * T;
   ProfScope prof(K_LAYERNORM, st, 40.0 * rows * C * n, 16.0 * rows * C * n);
   dim3 grid((unsigned)(groups * T)), block(kThreads);
-  const int per_slot = (P * E + kThreads / G - 1) / (kThreads / G);
-  if (P <= 1 && VEC == 1 && per_slot <= 16) {   // the token's block fits the register file: read it once
-#define LNC_LAUNCH(ROWS)                                                                                         \
-  hipLaunchKernelGGL((layernorm_cached_kernel<ROWS>), grid, block, 0, st, x.S, x.R, P * E, T, n, G, gps, pn, eps, \
-                     gamma, beta, ln_eps, y.S, y.R, status)
-    if (per_slot <= 4) LNC_LAUNCH(4);
-    else if (per_slot <= 8) LNC_LAUNCH(8);
-    else LNC_LAUNCH(16);
+  // small blocks: the token's block fits the register file of one workgroup (at most 8 rows per thread) and is
+  // read once.  512 threads halve the rows per thread where 256 would need more than 8.
+  const int crows = P * E;
+  const int per256 = (crows + kThreads / G - 1) / (kThreads / G), per512 = (crows + 512 / G - 1) / (512 / G);
+  if (P <= 1 && VEC == 1 && per512 <= 8) {
+#define LNC_LAUNCH(PN)                                                                                           \
+  do {                                                                                                           \
+    if (per256 <= 4)                                                                                             \
+      hipLaunchKernelGGL((layernorm_cached_kernel<4, 256, PN>), grid, dim3(256), 0, st, x.S, x.R, crows, T, n, G, gps, \
+                         eps, gamma, beta, ln_eps, y.S, y.R, status);                                            \
+    else if (per256 <= 8)                                                                                        \
+      hipLaunchKernelGGL((layernorm_cached_kernel<8, 256, PN>), grid, dim3(256), 0, st, x.S, x.R, crows, T, n, G, gps, \
+                         eps, gamma, beta, ln_eps, y.S, y.R, status);                                            \
+    else                                                                                                         \
+      hipLaunchKernelGGL((layernorm_cached_kernel<8, 512, PN>), grid, dim3(512), 0, st, x.S, x.R, crows, T, n, G, gps, \
+                         eps, gamma, beta, ln_eps, y.S, y.R, status);                                            \
+  } while (0)
+    NORM_SWITCH(pn, LNC_LAUNCH);
 #undef LNC_LAUNCH
     TV_HIP(hipGetLastError());
     return TV_OK;
   }
-#define LN_LAUNCH(V)                                                                                               \
-  hipLaunchKernelGGL((layernorm_kernel<V>), grid, block, 0, st, x.S, x.R, P, E, T, n, G, gps, pn, eps, gamma, beta, \
+#define LN_LAUNCH2(V, PN)                                                                                        \
+  hipLaunchKernelGGL((layernorm_kernel<V, PN>), grid, block, 0, st, x.S, x.R, P, E, T, n, G, gps, eps, gamma, beta, \
                      ln_eps, y.S, y.R, status)
-  switch (VEC) {
-    case 1: LN_LAUNCH(1); break;
-    case 2: LN_LAUNCH(2); break;
-    case 3: LN_LAUNCH(3); break;
-    default: LN_LAUNCH(4); break;
+#define LN_LAUNCH(PN)                 \
+  switch (VEC) {                      \
+    case 1: LN_LAUNCH2(1, PN); break; \
+    case 2: LN_LAUNCH2(2, PN); break; \
+    case 3: LN_LAUNCH2(3, PN); break; \
+    default: LN_LAUNCH2(4, PN); break; \
   }
+  NORM_SWITCH(pn, LN_LAUNCH);
+#undef LN_LAUNCH2
 #undef LN_LAUNCH
   TV_HIP(hipGetLastError());
   return TV_OK;
@@ -952,15 +1008,18 @@ int softmax(State s, int groups, int P, int E, int T, int n, int gps, int pn, co
   const double C = (double)P * E + 1, rows = (double)groups * T;
   ProfScope prof(K_SOFTMAX, st, 40.0 * rows * C * n, 16.0 * rows * C * n);
   dim3 grid((unsigned)(groups * T)), block(kThreads);
-#define SM_LAUNCH(V)                                                                                          \
-  hipLaunchKernelGGL((softmax_kernel<V>), grid, block, 0, st, s.S, s.R, P, E, T, n, G, gps, pn, eps, lp, slack, \
+#define SM_LAUNCH2(V, PN)                                                                                    \
+  hipLaunchKernelGGL((softmax_kernel<V, PN>), grid, block, 0, st, s.S, s.R, P, E, T, n, G, gps, eps, lp, slack, \
                      status)
-  switch (VEC) {
-    case 1: SM_LAUNCH(1); break;
-    case 2: SM_LAUNCH(2); break;
-    case 3: SM_LAUNCH(3); break;
-    default: SM_LAUNCH(4); break;
+#define SM_LAUNCH(PN)                 \
+  switch (VEC) {                      \
+    case 1: SM_LAUNCH2(1, PN); break; \
+    case 2: SM_LAUNCH2(2, PN); break; \
+    case 3: SM_LAUNCH2(3, PN); break; \
+    default: SM_LAUNCH2(4, PN); break; \
   }
+  NORM_SWITCH(pn, SM_LAUNCH);
+#undef SM_LAUNCH2
 #undef SM_LAUNCH
   TV_HIP(hipGetLastError());
   return TV_OK;
