@@ -19,6 +19,7 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0       # MI355X HBM3E
 MFMA_FP32_PEAK_TF = 157.3   # MI355X dense fp32 matrix
+BF16_SPLIT_PEAK_TF = 2500.0 / 6.0   # dense bf16 peak over the six bf16 products that make one fp32 product
 # HBM bytes per launch of a kernel class from `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE` on `bench.py --probe`,
 # scaled by the counters' readings for the 2^30-byte copy of the same run (2048 and 1024 bytes per unit) and
 # averaged over the launches of one certify call; counters cannot be read inside this process, so the figure is
@@ -107,17 +108,24 @@ def main():
                              "TFLOPs": round(v["flops"] / (v["ms"] * 1e-3) / 1e12, 2) if v["ms"] else 0.0}
         dom = max(prof, key=lambda k: prof[k]["ms"])
         d = prof[dom]
-        # at this size every class, the contractions included, sits under the HBM roof (K = N = 128:
-        # 32 flop/byte against a ridge of 20); the class is reported against the roof that bounds it
+        # the roof that bounds the class: its arithmetic intensity against the ridge of its own compute roof.
+        # The affine layers run on the bf16 matrix cores with six products per fp32 product (three bf16 pieces per
+        # operand), so their compute roof is the dense bf16 peak / 6 in fp32-equivalent flops; the dot-product
+        # contractions use the fp32 MFMA instructions.
+        compute_peak = BF16_SPLIT_PEAK_TF if dom == "affine_gemm" else MFMA_FP32_PEAK_TF
         ai = d["flops"] / max(d["bytes"], 1.0)
-        if dom in MFMA_KINDS and ai > MFMA_FP32_PEAK_TF * 1e12 / (HBM_PEAK_GBS * 1e9):
-            ach = d["flops"] / (d["ms"] * 1e-3) / 1e12
-            roofline = {"kernel": dom, "bound": "mfma", "achieved": round(ach, 2), "peak": MFMA_FP32_PEAK_TF,
-                        "unit": "TFLOP/s", "frac": round(ach / MFMA_FP32_PEAK_TF, 4), "traffic": None}
+        tf = d["flops"] / (d["ms"] * 1e-3) / 1e12
+        gbs = d["bytes"] / (d["ms"] * 1e-3) / 1e9
+        if dom in MFMA_KINDS and ai > compute_peak * 1e12 / (HBM_PEAK_GBS * 1e9):
+            roofline = {"kernel": dom, "bound": "mfma", "achieved": round(tf, 2), "peak": round(compute_peak, 1),
+                        "unit": "TFLOP/s", "frac": round(tf / compute_peak, 4), "traffic": None}
         else:
-            ach = d["bytes"] / (d["ms"] * 1e-3) / 1e9
-            roofline = {"kernel": dom, "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS,
-                        "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None}
+            roofline = {"kernel": dom, "bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS,
+                        "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None}
+        if dom in MFMA_KINDS:
+            roofline["arithmetic_intensity_flop_per_byte"] = round(ai, 1)
+            roofline["algorithmic_TFLOPs"] = round(tf, 2)
+            roofline["compute_roof_TFLOPs"] = round(compute_peak, 1)
         roofline["traffic"] = PMC_TRAFFIC.get(args.workload, {}).get(dom)
         roofline["avg_launch_us"] = round(d["ms"] * 1e3 / d["launches"], 2)
         roofline["algorithmic_bytes_per_launch"] = d["bytes"] / d["launches"]

@@ -15,8 +15,8 @@
 // four contractions read and write dense slabs.
 //
 // The radius of the bias row is second order (a slack times a half-width): the MFMA products form it
-// as a difference of O(1) terms, which fp32 cannot hold, so two small kernels recompute that one row
-// from slacks and half-widths (no cancellation) and overwrite it.
+// as a difference of O(1) terms, which fp32 cannot hold, so the preparation kernels also form that one
+// row from slacks and half-widths (no cancellation) and a copy puts it over the products' result.
 #include "common.h"
 
 namespace tv {
@@ -37,12 +37,25 @@ struct Ranges {   // concretized ranges of q, k, v: arrays [B][L][rld] (+ column
   int rld;
 };
 
-// coefficient matrices for q k^T from the concretized ranges of q and k
-//   coef[b][h][plane][j][kk]   (kk < dh: on S_q ; kk >= dh: on R_q),  lqs[plane][b][i][D]
-__global__ void qk_prep_kernel(Ranges rg, int B, int L, int H, int dh, float scale, float *coef, float *lqs) {
+// ---- preparation for q k^T, one kernel.  Elementwise part (grid-stride over [B][L][D]):
+//   coef[b][h][plane][j][kk]   (kk < dh: on S_q ; kk >= dh: on R_q), from k's range
+//   lqs[plane][b][i][D] = scale * {l_q, |l_q|}
+// Tiled part, one 16 x 16 tile of (i, j) per workgroup and head, operands staged through LDS:
+//   cst[b][h][plane][i][j] = -scale * sum_d l_q[i,d] * {mid_k, half_k}[j,d]          constants of the centre plane
+//   fix[b][h][i][j] = scale * sum_d ( half_k[j,d] (S_q_b - l_q)[i,d] + (|u_k|+|l_k|)/2 [j,d] R_q_b[i,d]
+//                                      + |l_q[i,d]| R_k_b[j,d] )
+// fix is the bias row of the radius plane of the scores, formed from slacks and half-widths (no cancellation);
+// it replaces what the MFMA products leave in that row.
+constexpr int kTile = 16, kChunk = 32;
+
+__global__ __launch_bounds__(256) void qk_pre_kernel(Ranges rg, const float *qR, const float *kR, int ld, int B, int L,
+                                                     int H, int dh, int C, float scale, float *coef, float *lqs,
+                                                     float *cst, float *fix) {
   const int D = H * dh;
   const long total = (long)B * L * D;
-  for (long i = (long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long)gridDim.x * blockDim.x) {
+  const long nblk = (long)gridDim.x * gridDim.y * gridDim.z;
+  const long bid = blockIdx.x + (long)gridDim.x * (blockIdx.y + (long)gridDim.y * blockIdx.z);
+  for (long i = bid * 256 + threadIdx.x; i < total; i += nblk * 256) {
     const int dfull = (int)(i % D);
     const long bj = i / D;
     const int j = (int)(bj % L), b = (int)(bj / L);
@@ -60,58 +73,66 @@ __global__ void qk_prep_kernel(Ranges rg, int B, int L, int H, int dh, float sca
     lqs[i] = q * scale;
     lqs[total + i] = fabsf(q) * scale;
   }
-}
 
-// constants of the centre plane: cst[b][h][plane][i][j] = -scale * sum_d lq[i,d] * {mid_k, half_k}[j,d]
-__global__ void qk_const_kernel(Ranges rg, int B, int L, int H, int dh, float scale, float *cst) {
-  const long total = (long)B * H * L * L;
-  for (long t = (long)blockIdx.x * blockDim.x + threadIdx.x; t < total; t += (long)gridDim.x * blockDim.x) {
-    const int j = (int)(t % L);
-    long r = t / L;
-    const int i = (int)(r % L); r /= L;
-    const int h = (int)(r % H), b = (int)(r / H);
-    const long oq = ((long)b * L + i) * rg.rld + h * dh, ok = ((long)b * L + j) * rg.rld + h * dh;
-    float s = 0.f, rr = 0.f;
-    for (int d = 0; d < dh; ++d) {
-      const float q = rg.mq[oq + d] - rg.hq[oq + d];
-      s = fmaf(q, rg.mk[ok + d], s);
-      rr = fmaf(q, rg.hk[ok + d], rr);
+  __shared__ float qs[3][kTile][kChunk + 1];     // l_q, slack of q, R_q bias
+  __shared__ float ks[4][kTile][kChunk + 1];     // mid_k, half_k, (|u_k|+|l_k|)/2, R_k bias
+  const int tiles = (L + kTile - 1) / kTile;
+  const int i0 = (blockIdx.x / tiles) * kTile, j0 = (blockIdx.x % tiles) * kTile;
+  const int h = blockIdx.y, b = blockIdx.z;
+  const int ti = threadIdx.x / kTile, tj = threadIdx.x % kTile;
+  float s = 0.f, rr = 0.f, fx = 0.f;
+  for (int d0 = 0; d0 < dh; d0 += kChunk) {
+    for (int e = threadIdx.x; e < kTile * kChunk; e += 256) {
+      const int r = e / kChunk, d = e % kChunk;
+      const bool dok = d0 + d < dh;
+      const int i = i0 + r, j = j0 + r;
+      float lq = 0.f, sq = 0.f, qb = 0.f, mk = 0.f, hk = 0.f, sk = 0.f, kb = 0.f;
+      if (dok && i < L) {
+        const long o = ((long)b * L + i) * rg.rld + h * dh + d0 + d;
+        lq = rg.mq[o] - rg.hq[o]; sq = rg.sq[o];
+        qb = qR[(((long)b * C + C - 1) * L + i) * ld + h * dh + d0 + d];
+      }
+      if (dok && j < L) {
+        const long o = ((long)b * L + j) * rg.rld + h * dh + d0 + d;
+        mk = rg.mk[o]; hk = rg.hk[o];
+        float dif;
+        abs_parts(mk, hk, dif, sk);
+        kb = kR[(((long)b * C + C - 1) * L + j) * ld + h * dh + d0 + d];
+      }
+      qs[0][r][d] = lq; qs[1][r][d] = sq; qs[2][r][d] = qb;
+      ks[0][r][d] = mk; ks[1][r][d] = hk; ks[2][r][d] = sk; ks[3][r][d] = kb;
     }
+    __syncthreads();
+#pragma unroll 8
+    for (int d = 0; d < kChunk; ++d) {
+      const float lq = qs[0][ti][d], hk = ks[1][tj][d];
+      s = fmaf(lq, ks[0][tj][d], s);
+      rr = fmaf(lq, hk, rr);
+      fx += hk * qs[1][ti][d] + ks[2][tj][d] * qs[2][ti][d] + fabsf(lq) * ks[3][tj][d];
+    }
+    __syncthreads();
+  }
+  const int i = i0 + ti, j = j0 + tj;
+  if (i < L && j < L) {
     float *o = cst + (((long)b * H + h) * 2) * L * L + (long)i * L + j;
     o[0] = -scale * s;
     o[(long)L * L] = -scale * rr;
+    fix[(((long)b * H + h) * L + i) * L + j] = scale * fx;
   }
 }
 
-// bias row of the radius plane of the scores, from slacks and half-widths:
-//   R_s_b[i,j] = scale * sum_d ( half_k[j,d] (S_q_b - l_q)[i,d] + (|u_k|+|l_k|)/2 [j,d] R_q_b[i,d] + |l_q[i,d]| R_k_b[j,d] )
-__global__ void qk_fix_kernel(Ranges rg, const float *qR, const float *kR, int ld, int B, int L, int H, int dh, int C,
-                              float scale, float *sR) {
-  const long total = (long)B * H * L * L;
-  for (long t = (long)blockIdx.x * blockDim.x + threadIdx.x; t < total; t += (long)gridDim.x * blockDim.x) {
-    const int j = (int)(t % L);
-    long r = t / L;
-    const int i = (int)(r % L); r /= L;
-    const int h = (int)(r % H), b = (int)(r / H);
-    const long oq = ((long)b * L + i) * rg.rld + h * dh, ok = ((long)b * L + j) * rg.rld + h * dh;
-    const float *qb = qR + (((long)b * C + C - 1) * L + i) * ld + h * dh;
-    const float *kb = kR + (((long)b * C + C - 1) * L + j) * ld + h * dh;
-    float acc = 0.f;
-    for (int d = 0; d < dh; ++d) {
-      float dif, sum;
-      abs_parts(rg.mk[ok + d], rg.hk[ok + d], dif, sum);
-      const float lq = rg.mq[oq + d] - rg.hq[oq + d];
-      acc += rg.hk[ok + d] * rg.sq[oq + d] + sum * qb[d] + fabsf(lq) * kb[d];
-    }
-    sR[((((long)b * H + h) * C + C - 1) * L + i) * L + j] = scale * acc;
-  }
-}
-
-// coefficient matrices for p v:  coef[b][h][plane][d][kk]  (kk < L: on S_p[.., j=kk] ; kk >= L: on R_p)
-__global__ void pv_prep_kernel(Ranges rg, int B, int L, int H, int dh, float *coef) {
+// ---- preparation for p v, one kernel.  Elementwise part: coef[b][h][plane][d][kk] (kk < L: on S_p[.., j = kk];
+// kk >= L: on R_p) from v's range.  Tiled part, one 16 x 16 tile of (i, dfull) per workgroup:
+//   cst[plane][b][i][D] = - sum_j lp[b,h,i,j] * {mid_v, half_v}[b,j,dfull]
+//   fix[b][i][D] = sum_j ( half_v[j,d] (S_p_b - l_p)[i,j] + (|u_v|+|l_v|)/2 [j,d] R_p_b[i,j] + l_p[i,j] R_v_b[j,d] )
+__global__ __launch_bounds__(256) void pv_pre_kernel(Ranges rg, const float *lp, const float *slack_p, const float *pR,
+                                                     const float *vR, int ld, int B, int L, int H, int dh, int C,
+                                                     float *coef, float *cst, float *fix) {
   const int D = H * dh;
   const long total = (long)B * L * D;
-  for (long i = (long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long)gridDim.x * blockDim.x) {
+  const long nblk = (long)gridDim.x * gridDim.y;
+  const long bid = blockIdx.x + (long)gridDim.x * blockIdx.y;
+  for (long i = bid * 256 + threadIdx.x; i < total; i += nblk * 256) {
     const int dfull = (int)(i % D);
     const long bj = i / D;
     const int j = (int)(bj % L), b = (int)(bj / L);
@@ -126,51 +147,84 @@ __global__ void pv_prep_kernel(Ranges rg, int B, int L, int H, int dh, float *co
     c1[j] = rg.hv[ri];
     c1[L + j] = sum;
   }
-}
 
-// cst[plane][b][i][D] = - sum_j lp[b,h,i,j] * {mid_v, half_v}[b,j,dfull]
-__global__ void pv_const_kernel(Ranges rg, const float *lp, int B, int L, int H, int dh, float *cst) {
-  const int D = H * dh;
-  const long total = (long)B * L * D;
-  for (long t = (long)blockIdx.x * blockDim.x + threadIdx.x; t < total; t += (long)gridDim.x * blockDim.x) {
-    const int dfull = (int)(t % D);
-    const long bi = t / D;
-    const int i = (int)(bi % L), b = (int)(bi / L);
-    const int h = dfull / dh;
-    const float *pp = lp + (((long)b * H + h) * L + i) * L;
-    float s = 0.f, rr = 0.f;
-    for (int j = 0; j < L; ++j) {
-      const long k = ((long)b * L + j) * rg.rld + dfull;
-      s = fmaf(pp[j], rg.mv[k], s);
-      rr = fmaf(pp[j], rg.hv[k], rr);
+  __shared__ float ps[3][kTile][kChunk + 1];     // l_p, slack of p, R_p bias          [i][j]
+  __shared__ float vs[4][kChunk][kTile + 1];     // mid_v, half_v, (|u_v|+|l_v|)/2, R_v bias   [j][d]
+  const int itiles = (L + kTile - 1) / kTile;
+  const int i0 = (blockIdx.x % itiles) * kTile, d0 = (blockIdx.x / itiles) * kTile;   // d0 runs over the full width D
+  const int b = blockIdx.y;
+  const int ti = threadIdx.x / kTile, td = threadIdx.x % kTile;
+  const int dcol = d0 + td;                       // this thread's output column
+  const int hcol = dcol < D ? dcol / dh : 0;
+  // the p-side operands depend on the head of the column: staged through LDS when the tile lies in one head
+  const bool one_head = d0 / dh == (min(d0 + kTile, D) - 1) / dh;
+  const int h0 = d0 / dh;
+  float s = 0.f, rr = 0.f, fx = 0.f;
+  for (int j0 = 0; j0 < L; j0 += kChunk) {
+    for (int e = threadIdx.x; e < kChunk * kTile; e += 256) {
+      const int jj = e / kTile, dd = e % kTile;
+      const int j = j0 + jj, dc = d0 + dd;
+      float mv = 0.f, hv = 0.f, sv = 0.f, vb = 0.f;
+      if (j < L && dc < D) {
+        const long o = ((long)b * L + j) * rg.rld + dc;
+        mv = rg.mv[o]; hv = rg.hv[o];
+        float dif;
+        abs_parts(mv, hv, dif, sv);
+        vb = vR[(((long)b * C + C - 1) * L + j) * ld + dc];
+      }
+      vs[0][jj][dd] = mv; vs[1][jj][dd] = hv; vs[2][jj][dd] = sv; vs[3][jj][dd] = vb;
     }
+    if (one_head) {
+      for (int e = threadIdx.x; e < kTile * kChunk; e += 256) {
+        const int r = e / kChunk, jj = e % kChunk;
+        const int i = i0 + r, j = j0 + jj;
+        float a = 0.f, sl = 0.f, pb = 0.f;
+        if (i < L && j < L) {
+          const long op = (((long)b * H + h0) * L + i) * L + j;
+          a = lp[op]; sl = slack_p[op];
+          pb = pR[((((long)b * H + h0) * C + C - 1) * L + i) * L + j];
+        }
+        ps[0][r][jj] = a; ps[1][r][jj] = sl; ps[2][r][jj] = pb;
+      }
+    }
+    __syncthreads();
+    const int i = i0 + ti;
+    if (one_head) {
+#pragma unroll 8
+      for (int jj = 0; jj < kChunk; ++jj) {        // entries beyond L are zeros
+        const float lpv = ps[0][ti][jj];
+        s = fmaf(lpv, vs[0][jj][td], s);
+        rr = fmaf(lpv, vs[1][jj][td], rr);
+        fx += vs[1][jj][td] * ps[1][ti][jj] + vs[2][jj][td] * ps[2][ti][jj] + lpv * vs[3][jj][td];
+      }
+    } else if (i < L && dcol < D) {
+      const long op = (((long)b * H + hcol) * L + i) * L;
+      const float *pb = pR + ((((long)b * H + hcol) * C + C - 1) * L + i) * L;
+      const int jn = min(kChunk, L - j0);
+      for (int jj = 0; jj < jn; ++jj) {
+        const float lpv = lp[op + j0 + jj];
+        s = fmaf(lpv, vs[0][jj][td], s);
+        rr = fmaf(lpv, vs[1][jj][td], rr);
+        fx += vs[1][jj][td] * slack_p[op + j0 + jj] + vs[2][jj][td] * pb[j0 + jj] + lpv * vs[3][jj][td];
+      }
+    }
+    __syncthreads();
+  }
+  const int i = i0 + ti;
+  if (i < L && dcol < D) {
+    const long t = ((long)b * L + i) * D + dcol;
     cst[t] = -s;
     cst[total + t] = -rr;
+    fix[t] = fx;
   }
 }
 
-// bias row of the radius plane of the attention output:
-//   R_o_b[i,d] = sum_j ( half_v[j,d] (S_p_b - l_p)[i,j] + (|u_v|+|l_v|)/2 [j,d] R_p_b[i,j] + l_p[i,j] R_v_b[j,d] )
-__global__ void pv_fix_kernel(Ranges rg, const float *lp, const float *slack_p, const float *pR, const float *vR,
-                              int ld, int B, int L, int H, int dh, int C, float *oR) {
-  const int D = H * dh;
-  const long total = (long)B * L * D;
+// dst[(g * C + C - 1) * X + x] = src[g * X + x]: puts recomputed bias rows into a state plane
+__global__ void bias_row_put_kernel(const float *src, float *dst, long groups, int C, long X) {
+  const long total = groups * X;
   for (long t = (long)blockIdx.x * blockDim.x + threadIdx.x; t < total; t += (long)gridDim.x * blockDim.x) {
-    const int dfull = (int)(t % D);
-    const long bi = t / D;
-    const int i = (int)(bi % L), b = (int)(bi / L);
-    const int h = dfull / dh;
-    const long op = (((long)b * H + h) * L + i) * L;
-    const float *pb = pR + ((((long)b * H + h) * C + C - 1) * L + i) * L;
-    float acc = 0.f;
-    for (int j = 0; j < L; ++j) {
-      const long k = ((long)b * L + j) * rg.rld + dfull;
-      float dif, sum;
-      abs_parts(rg.mv[k], rg.hv[k], dif, sum);
-      const float vb = vR[(((long)b * C + C - 1) * L + j) * ld + dfull];
-      acc += rg.hv[k] * slack_p[op + j] + sum * pb[j] + lp[op + j] * vb;
-    }
-    oR[(((long)b * C + C - 1) * L + i) * D + dfull] = acc;
+    const long g = t / X, x = t % X;
+    dst[(g * C + C - 1) * X + x] = src[t];
   }
 }
 
@@ -182,15 +236,16 @@ unsigned blocks_for(long total) {
 size_t align_up(size_t x) { return (x + 63) & ~(size_t)63; }   // in floats: keeps 256-byte alignment
 
 struct AttnLayout {
-  size_t rmid, rhalf, rslack, coef_qk, lqs, cst_qk, sS, sR, lp, slack_p, coef_pv, cst_pv, total;
+  size_t rmid, rhalf, rslack, coef_qk, lqs, cst_qk, fix_qk, sS, sR, lp, slack_p, coef_pv, cst_pv, fix_pv, total;
   AttnLayout(int B, int L, int H, int D, int P, bool own_scores) {
     const size_t bld = (size_t)B * L * D, C = (size_t)P * D + 1;
     size_t o = 0;
     auto take = [&](size_t n) { size_t r = o; o += align_up(n); return r; };
     rmid = take(3 * bld); rhalf = take(3 * bld); rslack = take(3 * bld);
     coef_qk = take(4 * bld); lqs = take(2 * bld); cst_qk = take((size_t)2 * B * H * L * L);
+    fix_qk = take((size_t)B * H * L * L);
     lp = take((size_t)B * H * L * L); slack_p = take((size_t)B * H * L * L);
-    coef_pv = take(4 * bld); cst_pv = take(2 * bld);
+    coef_pv = take(4 * bld); cst_pv = take(2 * bld); fix_pv = take(bld);
     const size_t plane = (size_t)B * H * C * L * L;
     sS = take(own_scores ? plane : 0); sR = take(own_scores ? plane : 0);
     total = o;
@@ -236,12 +291,11 @@ int attention(CState q, CState k, CState v, int ld, int B, int L, int H, int D, 
     if (int rc = concretize(v, B, P, D, L, D, 1, pn, eps, rm + 2 * bld, rh + 2 * bld, nullptr, 1, st)) return rc;
     rg = Ranges{rm, rh, rs, rm + bld, rh + bld, rm + 2 * bld, rh + 2 * bld, D};
   }
+  const int tiles = (L + kTile - 1) / kTile;
   {
     ProfScope prof(K_PREP, st, 0.0, 0.0);
-    hipLaunchKernelGGL(qk_prep_kernel, dim3(blocks_for(bld)), dim3(256), 0, st, rg, B, L, H, dh, scale,
-                       w + lay.coef_qk, w + lay.lqs);
-    hipLaunchKernelGGL(qk_const_kernel, dim3(blocks_for((long)B * H * L * L)), dim3(256), 0, st, rg, B, L, H, dh, scale,
-                       w + lay.cst_qk);
+    hipLaunchKernelGGL(qk_pre_kernel, dim3(tiles * tiles, H, B), dim3(256), 0, st, rg, q.R, k.R, ld, B, L, H, dh, C, scale,
+                       w + lay.coef_qk, w + lay.lqs, w + lay.cst_qk, w + lay.fix_qk);
   }
   TV_HIP(hipGetLastError());
 
@@ -276,8 +330,8 @@ int attention(CState q, CState k, CState v, int ld, int B, int L, int H, int D, 
   }
   {
     ProfScope prof(K_PREP, st, 0.0, 0.0);
-    hipLaunchKernelGGL(qk_fix_kernel, dim3(blocks_for((long)B * H * L * L)), dim3(256), 0, st, rg, q.R, k.R, ld, B, L, H,
-                       dh, C, scale, s.R);
+    hipLaunchKernelGGL(bias_row_put_kernel, dim3(blocks_for((long)B * H * L * L)), dim3(256), 0, st, w + lay.fix_qk, s.R,
+                       (long)B * H, C, (long)L * L);
   }
   TV_HIP(hipGetLastError());
   if (stop_after == 1) return TV_OK;
@@ -288,8 +342,8 @@ int attention(CState q, CState k, CState v, int ld, int B, int L, int H, int D, 
 
   {
     ProfScope prof(K_PREP, st, 0.0, 0.0);
-    hipLaunchKernelGGL(pv_prep_kernel, dim3(blocks_for(bld)), dim3(256), 0, st, rg, B, L, H, dh, w + lay.coef_pv);
-    hipLaunchKernelGGL(pv_const_kernel, dim3(blocks_for(bld)), dim3(256), 0, st, rg, lp, B, L, H, dh, w + lay.cst_pv);
+    hipLaunchKernelGGL(pv_pre_kernel, dim3(tiles * ((D + kTile - 1) / kTile), B), dim3(256), 0, st, rg, lp, slp, s.R, v.R, ld,
+                       B, L, H, dh, C, w + lay.coef_pv, w + lay.cst_pv, w + lay.fix_pv);
   }
   TV_HIP(hipGetLastError());
   {  // o, part 1: [S_p | R_p] x coefficients from v's range
@@ -322,8 +376,8 @@ int attention(CState q, CState k, CState v, int ld, int B, int L, int H, int D, 
   }
   {
     ProfScope prof(K_PREP, st, 0.0, 0.0);
-    hipLaunchKernelGGL(pv_fix_kernel, dim3(blocks_for(bld)), dim3(256), 0, st, rg, lp, slp, s.R, v.R, ld, B, L, H, dh, C,
-                       o.R);
+    hipLaunchKernelGGL(bias_row_put_kernel, dim3(blocks_for(bld)), dim3(256), 0, st, w + lay.fix_pv, o.R, (long)B, C,
+                       (long)L * D);
   }
   TV_HIP(hipGetLastError());
   return TV_OK;
