@@ -198,8 +198,9 @@ __device__ __forceinline__ Map2 form_map(const Form &f) {
   m.sSd = 0.5 * (f.pL + f.qL + f.pU + f.qU);
   m.sRd = 0.5 * (-f.pL + f.qL + f.pU - f.qU);
   m.sCd = 0.5 * (f.cL + f.cU);
-  m.rSd = 0.5 * (f.pU + f.qU - f.pL - f.qL);
-  m.rRd = 0.5 * (f.pU - f.qU + f.pL - f.qL);
+  // differences of corresponding members first: coinciding lines give exactly zero
+  m.rSd = 0.5 * ((f.pU - f.pL) + (f.qU - f.qL));
+  m.rRd = 0.5 * ((f.pU + f.pL) - (f.qU + f.qL));
   m.rCd = 0.5 * (f.cU - f.cL);
   m.sS = (float)m.sSd; m.sR = (float)m.sRd; m.rS = (float)m.rSd; m.rR = (float)m.rRd;
   return m;

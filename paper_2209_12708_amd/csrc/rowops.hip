@@ -327,7 +327,7 @@ __global__ __launch_bounds__(kThreads) void activation_kernel(const float *S, co
       // bias values of g's two lines, as centre / radius in double
       const Form &f = fg[i];
       const double gS = 0.5 * ((f.pL + f.qL + f.pU + f.qU) * xS[i] + (-f.pL + f.qL + f.pU - f.qU) * xR[i] + f.cL + f.cU);
-      const double gR = 0.5 * ((f.pU + f.qU - f.pL - f.qL) * xS[i] + (f.pU - f.qU + f.pL - f.qL) * xR[i] + f.cU - f.cL);
+      const double gR = 0.5 * (((f.pU - f.pL) + (f.qU - f.qL)) * xS[i] + ((f.pU + f.pL) - (f.qU + f.qL)) * xR[i] + (f.cU - f.cL));
       double lg, ug;
       range_of(gS, gR, e, NL[i], NU[i], lg, ug);
       bad |= !(finite_d(lg) && finite_d(ug));
