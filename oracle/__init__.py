@@ -9,7 +9,8 @@ Pins (tests/test_oracle_*.py, tests/test_golden.py): closed forms of Eq. (1) and
 plain forward pass and its Jacobian, sampled soundness of every operator and of the whole encoder, brute force
 on tiny models, identities between the operators.  Parity unpinned: which of several sound lines the paper's
 own relaxations pick for ReLU / tanh / exp / reciprocal / sqrt / products (its figures for them are not in the
-text); the choices made here are listed in the design document and are pinned for soundness only.
+text); the choices made here are stated in the docstrings of relaxations.py and verifier.py and are pinned for
+soundness only.
 """
 from . import bounds, relaxations, verifier  # noqa: F401
 from .verifier import certify, is_verified, verify  # noqa: F401

@@ -12,7 +12,7 @@ eps for which the predicted class provably cannot change (`certify`).
 The paper gives Eq. (1) (concretization) and Eq. (2) (affine rule) and names the
 remaining operators; the encoder layout, softmax / LayerNorm / GELU
 decompositions, head, decision rule and binary search below are this
-implementation's reading (listed in the design document); they are pinned by
+implementation's reading (each stated where it is implemented below); they are pinned by
 soundness, eps=0 collapse, the Jacobian at eps=0 and closed forms, not by
 numbers printed in the paper.
 

@@ -10,7 +10,8 @@ Deeper or harsher cases (three tanh layers, the GELU chain, the stress-scaled mo
 the floor that fp32 *storage* of the states sets: the second-order (eps^2) part of a bound's width is
 a difference of O(1) centre values that fp32 holds to 6e-8, and later layers amplify it.  Running the
 float64 oracle with nothing but its states rounded to fp32 already moves those bounds by 3e-5..8e-4
-relative (measured; see the design document), so these cases use rtol 5e-4 / 2e-3 instead of 1e-4.
+relative (measured by running the oracle with that rounding added), so these cases use rtol 5e-4 / 2e-3 instead
+of 1e-4.
 """
 import numpy as np
 import pytest
