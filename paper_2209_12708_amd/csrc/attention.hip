@@ -300,6 +300,9 @@ int attention(CState q, CState k, CState v, int ld, int B, int L, int H, int D, 
   TV_HIP(hipGetLastError());
 
   const long cll = (long)C * L * L, clx = (long)C * L * ld, cld = (long)C * L * D;   // per-group plane sizes
+  // Both halves of a product in one launch (the half over y's state accumulated from fragments loaded straight
+  // from memory) when the shapes allow; otherwise two launches, the second accumulating through memory.
+  const bool fused_products = L % 32 == 0 && dh % 32 == 0;
   {  // scores, part 1: [S_q | R_q] x coefficients from k's range  -> both planes of s
     GemmArgs g;
     g.A = q.S; g.A2 = q.R; g.K1 = dh; g.lda = ld;
@@ -313,9 +316,14 @@ int attention(CState q, CState k, CState v, int ld, int B, int L, int H, int D, 
     g.sB[0] = (long)L * 2 * dh; g.sB[1] = 2L * L * 2 * dh; g.sB[2] = (long)H * 2 * L * 2 * dh;
     g.sC[0] = s.R - s.S; g.sC[1] = cll; g.sC[2] = (long)H * cll;
     g.sBias[0] = (long)L * L; g.sBias[1] = 2L * L * L; g.sBias[2] = (long)H * 2 * L * L;
+    if (fused_products) {   // + sum_d lqs[i, d] * k-state[(r, j), d]
+      g.pA = w + lay.lqs; g.pA_ld = D; g.pB = k.S; g.pB_ld = ld; g.pB_mode = 0; g.pL = L; g.pK = dh;
+      g.spA[0] = bld; g.spA[1] = dh; g.spA[2] = (long)L * D;
+      g.spB[0] = k.R - k.S; g.spB[1] = dh; g.spB[2] = clx;
+    }
     if (int rc = gemm(g, st)) return rc;
   }
-  {  // scores, part 2: coefficients from q's range x the state of k, accumulated.  n = (r, j)
+  if (!fused_products) {  // scores, part 2: coefficients from q's range x the state of k, accumulated.  n = (r, j)
     GemmArgs g;
     g.A = w + lay.lqs; g.lda = D;
     g.B = k.S; g.ldb = ld; g.b_mode = 0;
@@ -359,9 +367,14 @@ int attention(CState q, CState k, CState v, int ld, int B, int L, int H, int D, 
     g.sB[0] = (long)dh * 2 * L; g.sB[1] = 2L * dh * 2 * L; g.sB[2] = (long)H * 2 * dh * 2 * L;
     g.sC[0] = o.R - o.S; g.sC[1] = dh; g.sC[2] = cld;
     g.sBias[0] = bld; g.sBias[1] = dh; g.sBias[2] = (long)L * D;
+    if (fused_products) {   // + sum_j lp[i, j] * v-state[(r, j), d]   (lp >= 0 after the clamp, so |lp| = lp)
+      g.pA = lp; g.pA_ld = L; g.pB = v.S; g.pB_ld = ld; g.pB_mode = 1; g.pL = L; g.pK = L;
+      g.spA[0] = 0; g.spA[1] = (long)L * L; g.spA[2] = (long)H * L * L;
+      g.spB[0] = v.R - v.S; g.spB[1] = dh; g.spB[2] = clx;
+    }
     if (int rc = gemm(g, st)) return rc;
   }
-  {  // o, part 2: lp x the state of v, accumulated (lp >= 0 after the clamp, so |lp| = lp).  n = (r, d)
+  if (!fused_products) {  // o, part 2: lp x the state of v, accumulated.  n = (r, d)
     GemmArgs g;
     g.A = lp; g.lda = L;
     g.B = v.S; g.ldb = ld; g.b_mode = 1; g.cq = dh; g.b_cstride = (long)L * ld;

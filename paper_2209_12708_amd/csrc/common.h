@@ -63,6 +63,15 @@ struct GemmArgs {
   int kind = K_MISC;              // timing class
   long sA[3] = {0, 0, 0}, sA2[3] = {0, 0, 0}, sB[3] = {0, 0, 0}, sC[3] = {0, 0, 0}, sAdd[3] = {0, 0, 0},
        sBias[3] = {0, 0, 0};
+  // Optional second product accumulated into the same tile before the epilogue, for rows m = r * pL + i:
+  //   C[m][n] += sum_t pA[i][t] * Y(r, t, n),   Y = pB[(r * pL + n) * pB_ld + t]  (pB_mode 0, t contiguous)
+  //                                             Y = pB[(r * pL + t) * pB_ld + n]  (pB_mode 1, n contiguous)
+  // (the operand-of-y half of a dot-product bound: pA holds the multipliers from x's range, pB is the state of
+  // y).  Operands go from memory straight to MFMA fragments.  Needs pL % 32 == 0, pK % 32 == 0, M % 32 == 0.
+  const float *pA = nullptr; long pA_ld = 0;
+  const float *pB = nullptr; long pB_ld = 0;
+  int pB_mode = 0, pL = 0, pK = 0;
+  long spA[3] = {0, 0, 0}, spB[3] = {0, 0, 0};
 };
 int gemm(const GemmArgs &g, hipStream_t st);
 

@@ -24,7 +24,7 @@ __device__ __forceinline__ long remap_col(int n, int cq, long cstride) {
   return cq ? (long)(n / cq) * cstride + (n % cq) : (long)n;
 }
 
-template <int BM, int BN, int WM, int WN, int BMODE, int BK>
+template <int BM, int BN, int WM, int WN, int BMODE, int BK, bool DUAL>
 __global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs g, int mtiles, int ntiles) {
   constexpr int LS = BK + 4;              // padded LDS row length (floats) for [row][k] tiles
   constexpr int KQ = BK / 4;              // float4 groups per row of a stage
@@ -195,6 +195,48 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs g, int mtiles,
     }
   }
 
+  // ---- second product (see GemmArgs): both operands go from memory to fragments.  Lane half h of MFMA step s
+  // holds k = c + 16 h + s of the 32-wide chunk c, a contiguous run of 16 floats per lane in the k-contiguous layouts.
+  if (DUAL) {
+    const float *pA = g.pA + z0 * g.spA[0] + z1 * g.spA[1] + z2 * g.spA[2];
+    const float *pB = g.pB + z0 * g.spB[0] + z1 * g.spB[1] + z2 * g.spB[2];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      const int row0 = m0 + wm * (BM / WM) + i * 32;
+      if (row0 >= M) continue;                                   // wave-uniform
+      const int r = row0 / g.pL, i0 = row0 % g.pL;
+      const float *pa = pA + (long)(i0 + l32) * g.pA_ld + 16 * half;
+      for (int c = 0; c < g.pK; c += 32) {
+        float a2[16];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const float4 v = *reinterpret_cast<const float4 *>(pa + c + 4 * q);
+          a2[4 * q] = v.x; a2[4 * q + 1] = v.y; a2[4 * q + 2] = v.z; a2[4 * q + 3] = v.w;
+        }
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          int n = n0 + wn * (BN / WN) + j * 32 + l32;
+          if (n >= N) n = N - 1;                                 // loaded, never stored
+          float b2[16];
+          if (g.pB_mode == 0) {
+            const float *pb = pB + ((long)r * g.pL + n) * g.pB_ld + c + 16 * half;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              const float4 v = *reinterpret_cast<const float4 *>(pb + 4 * q);
+              b2[4 * q] = v.x; b2[4 * q + 1] = v.y; b2[4 * q + 2] = v.z; b2[4 * q + 3] = v.w;
+            }
+          } else {
+            const float *pb = pB + ((long)r * g.pL + c + 16 * half) * g.pB_ld + n;
+#pragma unroll
+            for (int q = 0; q < 16; ++q) b2[q] = pb[(long)q * g.pB_ld];
+          }
+#pragma unroll
+          for (int q = 0; q < 16; ++q) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a2[q], b2[q], acc[i][j], 0, 0, 0);
+        }
+      }
+    }
+  }
+
   // ---- epilogue.  Accumulator v of lane l holds row 8*(v/4) + 4*(l/32) + v%4, column l%32.
   // does this tile contain rows of a bias block at all?  (one scalar test; 1 in C row blocks does)
   bool tile_has_bias = false;
@@ -257,10 +299,15 @@ int launch(const GemmArgs &g, hipStream_t st) {
   const long nz = (long)g.nz0 * g.nz1 * g.nz2;
   TV_REQUIRE(groups < (1L << 31) && nz <= 65535L * 32768L, TV_E_SHAPE, "gemm: grid too large");
   dim3 grid((unsigned)groups, (unsigned)nz, 1), block(256, 1, 1);
-  if (g.b_mode == 0)
-    hipLaunchKernelGGL((gemm_kernel<BM, BN, WM, WN, 0, BK>), grid, block, 0, st, g, mtiles, ntiles);
+  if (g.pA) {
+    if (g.b_mode == 0)
+      hipLaunchKernelGGL((gemm_kernel<BM, BN, WM, WN, 0, BK, true>), grid, block, 0, st, g, mtiles, ntiles);
+    else
+      hipLaunchKernelGGL((gemm_kernel<BM, BN, WM, WN, 1, BK, true>), grid, block, 0, st, g, mtiles, ntiles);
+  } else if (g.b_mode == 0)
+    hipLaunchKernelGGL((gemm_kernel<BM, BN, WM, WN, 0, BK, false>), grid, block, 0, st, g, mtiles, ntiles);
   else
-    hipLaunchKernelGGL((gemm_kernel<BM, BN, WM, WN, 1, BK>), grid, block, 0, st, g, mtiles, ntiles);
+    hipLaunchKernelGGL((gemm_kernel<BM, BN, WM, WN, 1, BK, false>), grid, block, 0, st, g, mtiles, ntiles);
   TV_HIP(hipGetLastError());
   return TV_OK;
 }
@@ -276,11 +323,16 @@ int gemm(const GemmArgs &g, hipStream_t st) {
   TV_REQUIRE(g.b_mode == 0 || (g.N % 4 == 0 && (g.cq == 0 || g.cq % 4 == 0)), TV_E_SHAPE,
              "gemm: column groups must be multiples of 4");
   TV_REQUIRE(g.bias == nullptr || (g.bias_T > 0 && g.bias_C > 0), TV_E_ARG, "gemm: bias without row structure");
+  TV_REQUIRE(g.pA == nullptr || (g.pB && g.pL > 0 && g.pL % 32 == 0 && g.pK > 0 && g.pK % 32 == 0 && g.M % 32 == 0 &&
+                                 g.pA_ld % 4 == 0 && g.pB_ld % 4 == 0 && (g.pB_mode == 0 || g.pB_mode == 1)),
+             TV_E_SHAPE, "gemm: second product needs pL, pK, M multiples of 32 (pL=%d pK=%d M=%d)", g.pL, g.pK, g.M);
   GemmArgs a = g;
   if (!a.A2) a.K1 = a.K;
   const double nz = (double)g.nz0 * g.nz1 * g.nz2, mn = (double)g.M * g.N;
-  ProfScope prof(g.kind, st, 2.0 * mn * g.K * nz,
-                 4.0 * nz * ((double)g.M * g.K + (double)g.N * g.K + mn * (g.Cadd ? 2.0 : 1.0)));
+  const double k2 = g.pA ? g.pK : 0;      // the second product reads its y operand once: M / pL blocks of pL x pK
+  ProfScope prof(g.kind, st, 2.0 * mn * (g.K + k2) * nz,
+                 4.0 * nz * ((double)g.M * g.K + (double)g.N * g.K + mn * (g.Cadd ? 2.0 : 1.0) +
+                             (g.pA ? (double)g.M * (g.pB_mode == 0 ? k2 * g.N / g.pL : (double)g.N * k2 / g.pL) : 0.0)));
   // tile shape by problem shape: small M (per-batch contractions over tokens) vs small N (head width)
   if (a.M <= 32) return launch<32, 128, 1, 4>(a, st);
   if (a.M <= 64) return launch<64, 128, 2, 2>(a, st);
