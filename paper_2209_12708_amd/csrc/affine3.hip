@@ -64,7 +64,8 @@ __global__ __launch_bounds__(256) void affine3_kernel(const Affine3Args g, int m
   constexpr int A_F4 = BM * 8 / 256;               // float4 loads of A per thread and stage
   constexpr int B_CH = 3 * BN * 4 / 256;           // 16-byte chunks of the weight pieces per thread and stage
   static_assert(A_F4 >= 1 && B_CH >= 1 && (3 * BN * 4) % 256 == 0 && (BM * 8) % 256 == 0, "tile too small");
-  __shared__ __attribute__((aligned(16))) unsigned char lds[3 * A_P + 3 * B_P];
+  constexpr int STAGE_BYTES = 3 * A_P + 3 * B_P, TILE_BYTES = BM * (BN + 4) * 4;   // stage buffers / staged output tile
+  __shared__ __attribute__((aligned(16))) unsigned char lds[STAGE_BYTES > TILE_BYTES ? STAGE_BYTES : TILE_BYTES];
   unsigned char *As = lds, *Bs = lds + 3 * A_P;
 
   // XCD-aware tile order (see gemm.hip)
@@ -200,53 +201,44 @@ __global__ __launch_bounds__(256) void affine3_kernel(const Affine3Args g, int m
     }
   }
 
-  // ---- epilogue.  Accumulator v of lane l holds row 8*(v/4) + 4*(l/32) + v%4, column l%32.
+  // ---- epilogue.  Accumulator v of lane l holds row 8*(v/4) + 4*(l/32) + v%4, column l%32: stored as is, a wave
+  // instruction would write two 128-byte pieces.  The tile goes through LDS once instead (the stage buffers are
+  // free after the last barrier) and leaves as 16 bytes per lane along rows - 512 contiguous bytes per row of a
+  // 128-wide tile - which is what the HBM write path wants; the residual is read the same way.
+  constexpr int CS = BN + 4;                       // padded row stride of the staged tile (floats)
+  float *Ct = reinterpret_cast<float *>(lds);
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int row = wm * (BM / WM) + i * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
+        Ct[row * CS + wn * (BN / WN) + j * 32 + l32] = acc[i][j][v];
+      }
+  __syncthreads();
   bool tile_has_bias = false;
   if (bias) {   // does this tile contain rows of a bias block at all?
     const int ba = m0 / g.bias_T, bb = (min(m0 + BM, M) - 1) / g.bias_T;
     tile_has_bias = (ba % g.bias_C) + (bb - ba) >= g.bias_C - 1;
   }
-  int col[TN]; bool con[TN];
+  constexpr int NQ = BN / 4;
 #pragma unroll
-  for (int j = 0; j < TN; ++j) {
-    col[j] = n0 + wn * (BN / WN) + j * 32 + l32;
-    con[j] = col[j] < N;
-  }
-#pragma unroll
-  for (int i = 0; i < TM; ++i) {
-    const int mb = m0 + wm * (BM / WM) + i * 32 + 4 * half;
+  for (int f = tid; f < BM * NQ; f += 256) {
+    const int row = f / NQ, c4 = f % NQ;
+    const int m = m0 + row, n = n0 + c4 * 4;
+    if (m >= M || n >= N) continue;
+    float4 v = *reinterpret_cast<const float4 *>(Ct + row * CS + c4 * 4);
     if (Cadd) {
-#pragma unroll
-      for (int j = 0; j < TN; ++j) {
-        float add[16];
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int m = mb + 8 * (v >> 2) + (v & 3);
-          add[v] = (m < M && con[j]) ? Cadd[(long)m * N + col[j]] : 0.f;
-        }
-#pragma unroll
-        for (int v = 0; v < 16; ++v) acc[i][j][v] += add[v];
-      }
+      const float4 a = *reinterpret_cast<const float4 *>(Cadd + (long)m * N + n);
+      v.x += a.x; v.y += a.y; v.z += a.z; v.w += a.w;
     }
-    if (tile_has_bias) {
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int m = mb + 8 * (v >> 2) + (v & 3);
-        if (m < M && (m / g.bias_T) % g.bias_C == g.bias_C - 1) {
-#pragma unroll
-          for (int j = 0; j < TN; ++j)
-            if (con[j]) acc[i][j][v] += bias[col[j]];
-        }
-      }
+    if (tile_has_bias && (m / g.bias_T) % g.bias_C == g.bias_C - 1) {
+      // rows are ordered (group, coefficient row, t); the last coefficient row is the bias row
+      const float4 b = *reinterpret_cast<const float4 *>(bias + n);
+      v.x += b.x; v.y += b.y; v.z += b.z; v.w += b.w;
     }
-#pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const int m = mb + 8 * (v >> 2) + (v & 3);
-      if (m >= M) continue;
-#pragma unroll
-      for (int j = 0; j < TN; ++j)
-        if (con[j]) C[(long)m * N + col[j]] = acc[i][j][v];
-    }
+    *reinterpret_cast<float4 *>(C + (long)m * N + n) = v;
   }
 }
 
