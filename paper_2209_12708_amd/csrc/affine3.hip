@@ -282,6 +282,8 @@ int affine_split(const float *xS, long xplane, long M, int C, int T, int K, int 
   ProfScope prof(K_AFFINE, st, planes * 2.0 * mn * K,
                  planes * 4.0 * ((double)M * K + (double)N * K + mn * (addS ? 2.0 : 1.0)));
   if (N <= 64) return launch3<128, 64, 2, 2>(g, planes, st);
+  // wide layers: 64 x 64 per wave halves the LDS traffic per MFMA (measured +4..13 % from K = 256, N = 512 up)
+  if (K >= 256 && N >= 512 && M >= 128 * 256) return launch3<128, 128, 2, 2>(g, planes, st);
   return launch3<64, 128, 2, 2>(g, planes, st);
 }
 
