@@ -35,6 +35,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="c2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-ceilings", action="store_true", help="skip the copy / fill / MFMA issue-rate probes")
     ap.add_argument("--no-kernel-timing", action="store_true",
                     help="leave the per-launch HIP events out of the timed region")
     ap.add_argument("--probe", action="store_true",
@@ -71,6 +72,39 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"probe": "copy of 2^30 bytes, then one verify sweep", "workload": args.workload}))
         return
+
+    def ceilings():
+        """Achievable ceilings of this part as it runs (the published peaks are the roofline's denominators):
+        a device copy and a fill of 1 GiB, and the issue rate of the two matrix-core instructions."""
+        n = 1 << 28
+        a = torch.empty(n, dtype=torch.float32, device=dev).normal_()
+        b = torch.empty_like(a)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+        def timed(fn, reps):
+            fn()
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(reps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) * 1e-3 / reps
+
+        out = {"copy_GBps": round(2 * 4 * n / timed(lambda: b.copy_(a), 5) / 1e9, 1),
+               "fill_GBps": round(4 * n / timed(lambda: b.fill_(1.0), 5) / 1e9, 1)}
+        buf = torch.empty(2048 * 256, dtype=torch.float32, device=dev)
+        for name, bf16, iters in (("mfma_f32_TFLOPs", 0, 4000), ("mfma_bf16_TFLOPs", 1, 8000)):
+            fl = [0.0]
+
+            def launch():
+                fl[0] = tv.probe_mfma(bf16, 2048, iters, buf)
+            t = timed(launch, 3)
+            out[name] = round(fl[0] / t / 1e12, 1)
+        del a, b, buf
+        return out
+
+    ceil = None if args.no_ceilings else ceilings()
 
     def step():
         out = None
@@ -163,7 +197,7 @@ def main():
                                f"{w.steps} bisection probes on [{w.eps_lo}, {w.eps_hi}]",
                    "certifications_per_step": n_cert, "workspace_bytes": int(ws.numel()),
                    "batch_resident": bool(ws.numel() >= full), "kernel_timing_in_timed_region": not args.no_kernel_timing},
-        "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels,
+        "roofline": roofline, "cpu_baseline": cpu, "measured_ceilings": ceil, "kernels": kernels,
     }
     print(json.dumps(line))
 

@@ -121,6 +121,13 @@ int tv_certify(const tv_model *m, const int32_t *tokens, int B, int L, const int
                int32_t *out_labels, int32_t *status, void *workspace, size_t workspace_bytes,
                void *stream);
 
+/* Measurement aid: launches `workgroups` x 4 waves that each issue iters * 16 independent matrix-core
+ * instructions (bf16 == 0: v_mfma_f32_32x32x2_f32, the instruction of the dot-product contractions; bf16 != 0:
+ * v_mfma_f32_32x32x16_bf16, the instruction of the affine layers) and sets *flops (host pointer) to the flops of
+ * the launch.  out: device, workgroups * 256 floats.  The caller times the launch on `stream`: the result is
+ * the issue-rate ceiling of the part as it runs (clocks, power), to be read next to the published peak. */
+int tv_probe_mfma(int bf16, int workgroups, int iters, float *out, double *flops, void *stream);
+
 /* ---- single operators on bound states (the kernels behind tv_verify; exported for unit parity
  * tests and per-kernel benchmarks).  S*, R* are the two planes of a state, [groups][C][T][n];
  * eps is indexed by group / groups_per_sentence. -------------------------------------------------- */

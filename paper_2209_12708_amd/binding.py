@@ -42,7 +42,7 @@ class _Weights(C.Structure):
 _lib = None
 
 EXPORTS = ("tv_version", "tv_last_error", "tv_model_create", "tv_model_destroy", "tv_workspace_query", "tv_verify",
-           "tv_certify", "tv_op_concretize", "tv_op_abs", "tv_op_affine", "tv_op_split3", "tv_op_affine_split", "tv_op_activation", "tv_op_layernorm",
+           "tv_certify", "tv_op_concretize", "tv_op_abs", "tv_op_affine", "tv_op_split3", "tv_op_affine_split", "tv_probe_mfma", "tv_op_activation", "tv_op_layernorm",
            "tv_attention_workspace", "tv_op_attention", "tv_profile_enable", "tv_profile_reset",
            "tv_profile_kinds", "tv_profile_get")
 
@@ -70,6 +70,7 @@ def lib():
         L.tv_op_abs.argtypes = [vp, vp, sz, vp]
         L.tv_op_affine.argtypes = [vp, vp, i, i, i, i, i, i, vp, vp, vp, vp, vp, vp, vp, vp]
         L.tv_op_split3.argtypes = [vp, vp, sz, i, vp]
+        L.tv_probe_mfma.argtypes = [i, i, i, vp, C.POINTER(C.c_double), vp]
         L.tv_op_affine_split.argtypes = [vp, vp, i, i, i, i, i, i, vp, vp, vp, vp, vp, vp, vp, vp]
         L.tv_op_activation.argtypes = [i, vp, vp, i, i, i, i, i, i, i, vp, vp, vp, vp, vp]
         L.tv_op_layernorm.argtypes = [vp, vp, i, i, i, i, i, i, i, vp, vp, vp, f, vp, vp, vp, vp]
@@ -274,6 +275,13 @@ def op_attention(q, k, v, H, P, p_norm, eps, stop_after=0):
                                  P, p_norm, _ptr(eps), _ptr(So), _ptr(Ro), _ptr(Ss), _ptr(Rs), stop_after,
                                  _ptr(status), _ptr(ws), nbytes, _stream()))
     return (So, Ro), (Ss, Rs), status
+
+
+def probe_mfma(bf16, workgroups, iters, out):
+    """Launches the matrix-core issue probe; returns the flops of the launch (time it with events)."""
+    fl = C.c_double()
+    _check(lib().tv_probe_mfma(1 if bf16 else 0, workgroups, iters, _ptr(out), C.byref(fl), _stream()))
+    return fl.value
 
 
 # ---- per-kernel-class timing --------------------------------------------------------------------

@@ -55,6 +55,36 @@ __global__ void split3_kernel(const float *in, unsigned short *out, size_t count
   }
 }
 
+// Issue-rate probes for the two matrix-core instructions the library uses: every wave runs `iters` rounds of four
+// independent accumulation chains.  Timed by the caller; gives the achievable ceiling next to the published peak.
+template <int BF16>
+__global__ __launch_bounds__(256) void mfma_probe_kernel(float *out, int iters, float seed) {
+  f32x16 acc[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
+  const float a = seed + (float)threadIdx.x, b = 0.5f * seed;
+  bf16x8 xa, xb;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) { xa[e] = (__bf16)(a + (float)e); xb[e] = (__bf16)(b - (float)e); }
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        if (BF16) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa, xb, acc[i], 0, 0, 0);
+        else acc[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc[i], 0, 0, 0);
+      }
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) s += acc[i][v];
+  out[(size_t)blockIdx.x * 256 + threadIdx.x] = s;
+}
+
 template <int BM, int BN, int WM, int WN, int PF, int PB>
 __global__ __launch_bounds__(256) void affine3_kernel(const Affine3Args g, int mtiles, int ntiles) {
   constexpr int BK = 32;
@@ -254,6 +284,16 @@ int launch3(const Affine3Args &g, int planes, hipStream_t st) {
 }
 
 }  // namespace
+
+int mfma_probe(int bf16, int workgroups, int iters, float *out, double *flops, hipStream_t st) {
+  TV_REQUIRE(out && flops && workgroups > 0 && iters > 0, TV_E_ARG, "mfma_probe: bad argument");
+  if (bf16) hipLaunchKernelGGL(mfma_probe_kernel<1>, dim3(workgroups), dim3(256), 0, st, out, iters, 1.0f);
+  else hipLaunchKernelGGL(mfma_probe_kernel<0>, dim3(workgroups), dim3(256), 0, st, out, iters, 1.0f);
+  TV_HIP(hipGetLastError());
+  // per wave and round: 16 instructions of 32 x 32 x k multiply-adds
+  *flops = (double)workgroups * 4.0 * iters * 16.0 * 2.0 * 32.0 * 32.0 * (bf16 ? 16.0 : 2.0);
+  return TV_OK;
+}
 
 int split_bf16x3(const float *in, unsigned short *out, size_t count, bool take_abs, hipStream_t st) {
   TV_REQUIRE(in && out, TV_E_NULL, "split_bf16x3: null pointer");

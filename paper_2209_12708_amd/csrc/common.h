@@ -76,6 +76,9 @@ struct GemmArgs {
 int gemm(const GemmArgs &g, hipStream_t st);
 
 // ---- affine layers with constant weights on the bf16 matrix cores at fp32 accuracy (affine3.hip) ----
+// matrix-core issue probe: `workgroups` x 4 waves x `iters` rounds of 16 MFMA instructions (fp32 32x32x2 or bf16
+// 32x32x16); out holds workgroups * 256 floats; *flops = the multiply-add flops of the launch
+int mfma_probe(int bf16, int workgroups, int iters, float *out, double *flops, hipStream_t st);
 // out[p][i] = p-th bf16 piece of in[i] (or of |in[i]|), p = 0..2: in = out[0] + out[1] + out[2]
 int split_bf16x3(const float *in, unsigned short *out, size_t count, bool take_abs, hipStream_t st);
 // y = x W^T (+ bias on bias rows of the centre plane) (+ add) for both planes in one launch.  W3pair:

@@ -618,6 +618,10 @@ int tv_profile_get(int kind, char *name, int name_len, double *total_ms, long lo
   return TV_OK;
 }
 
+int tv_probe_mfma(int bf16, int workgroups, int iters, float *out, double *flops, void *stream) {
+  return mfma_probe(bf16, workgroups, iters, out, flops, static_cast<hipStream_t>(stream));
+}
+
 // ---- single operators --------------------------------------------------------------------------
 int tv_op_concretize(const float *S, const float *R, int groups, int P, int E, int T, int n, int gps, int pn,
                      const float *eps, float *l, float *u, void *stream) {
