@@ -294,40 +294,53 @@ __global__ __launch_bounds__(kThreads) void activation_kernel(const float *S, co
   const double e = eps[blockIdx.x / gps];
   float NL[4 * VEC], NU[4 * VEC], bS[4 * VEC], bR[4 * VEC];
   column_norms<VEC>(S, R, lc, P, E, ge, pn, nullptr, red, NL, NU, bS, bR);
-  Map2 maps[4 * VEC];
+  // Every row slot holds the same norms for the same columns.  The relaxation of a column (double precision; a
+  // bisection for tanh) is computed once: row slot s takes column s of each float4 group (VEC = 1: four slots, one
+  // column each) and publishes the map through LDS.  With 64 lanes per row a slot is a wave, so the other waves
+  // skip the code instead of repeating it.
+  static_assert(VEC == 1, "one float4 group per lane");
+  __shared__ Map2 smap[4 * kWave];
+  __shared__ LineCoef slc[4 * kWave];
+  Map2 maps[4];
   bool bad = false;
   if (ACT != TV_ACT_GELU) {
 #pragma unroll
-    for (int i = 0; i < 4 * VEC; ++i) {
+    for (int i = 0; i < 4; ++i) {
+      if (ge.slot != i) continue;
       double l, u;
       range_of(bS[i], bR[i], e, NL[i], NU[i], l, u);
       bad |= !(finite_d(l) && finite_d(u));
       const Line2 ln = ACT == TV_ACT_RELU ? relax_relu(l, u) : relax_tanh(l, u);
-      maps[i] = form_map(form_sub(form_identity(), ln));
+      smap[4 * ge.g + i] = form_map(form_sub(form_identity(), ln));
     }
   } else {
-    Form fg[4 * VEC];
-    LineCoef lcf[4 * VEC];
-    double lx[4 * VEC], ux[4 * VEC];
-    float xS[4 * VEC], xR[4 * VEC];
+    Form fg = form_identity();                // of this thread's own column
+    double lx = 0.0, xS = 0.0, xR = 0.0;
 #pragma unroll
-    for (int i = 0; i < 4 * VEC; ++i) {
-      range_of(bS[i], bR[i], e, NL[i], NU[i], lx[i], ux[i]);
-      bad |= !(finite_d(lx[i]) && finite_d(ux[i]));
+    for (int i = 0; i < 4; ++i) {
+      if (ge.slot != i) continue;
+      double ux;
+      range_of(bS[i], bR[i], e, NL[i], NU[i], lx, ux);
+      bad |= !(finite_d(lx) && finite_d(ux));
       double lb, ub;
-      const Form b = gelu_inner(lx[i], ux[i], lb, ub);
-      fg[i] = form_mul(form_identity(), b, lx[i], lb, ub);     // g = x * b
-      lcf[i] = LineCoef{(float)(fg[i].pL + fg[i].qL), (float)(fg[i].qL - fg[i].pL), (float)(fg[i].pU + fg[i].qU),
-                        (float)(fg[i].pU - fg[i].qU)};
-      xS[i] = bS[i]; xR[i] = bR[i];
+      const Form b = gelu_inner(lx, ux, lb, ub);
+      fg = form_mul(form_identity(), b, lx, lb, ub);     // g = x * b
+      slc[4 * ge.g + i] = LineCoef{(float)(fg.pL + fg.qL), (float)(fg.qL - fg.pL), (float)(fg.pU + fg.qU),
+                                   (float)(fg.pU - fg.qU)};
+      xS = bS[i]; xR = bR[i];
     }
+    __syncthreads();
+    LineCoef lcf[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) lcf[i] = slc[4 * ge.g + i];
     column_norms<VEC>(S, R, lc, P, E, ge, pn, lcf, red, NL, NU, bS, bR);
 #pragma unroll
-    for (int i = 0; i < 4 * VEC; ++i) {
+    for (int i = 0; i < 4; ++i) {
+      if (ge.slot != i) continue;
       // bias values of g's two lines, as centre / radius in double
-      const Form &f = fg[i];
-      const double gS = 0.5 * ((f.pL + f.qL + f.pU + f.qU) * xS[i] + (-f.pL + f.qL + f.pU - f.qU) * xR[i] + f.cL + f.cU);
-      const double gR = 0.5 * (((f.pU - f.pL) + (f.qU - f.qL)) * xS[i] + ((f.pU + f.pL) - (f.qU + f.qL)) * xR[i] + (f.cU - f.cL));
+      const Form &f = fg;
+      const double gS = 0.5 * ((f.pL + f.qL + f.pU + f.qU) * xS + (-f.pL + f.qL + f.pU - f.qU) * xR + f.cL + f.cU);
+      const double gR = 0.5 * (((f.pU - f.pL) + (f.qU - f.qL)) * xS + ((f.pU + f.pL) - (f.qU + f.qL)) * xR + (f.cU - f.cL));
       double lg, ug;
       range_of(gS, gR, e, NL[i], NU[i], lg, ug);
       bad |= !(finite_d(lg) && finite_d(ug));
@@ -335,9 +348,12 @@ __global__ __launch_bounds__(kThreads) void activation_kernel(const float *S, co
       double lt, ut;
       line_range(th, lg, ug, lt, ut);
       const Form h = form_sub(form_sub(f, th), 0.5, 0.5, 0.5, 0.5);
-      maps[i] = form_map(form_mul(form_identity(), h, lx[i], 0.5 * lt + 0.5, 0.5 * ut + 0.5));
+      smap[4 * ge.g + i] = form_map(form_mul(form_identity(), h, lx, 0.5 * lt + 0.5, 0.5 * ut + 0.5));
     }
   }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 4; ++i) maps[i] = smap[4 * ge.g + i];
   if (bad) status[blockIdx.x / gps] = 1;
   apply_maps<VEC>(S, R, So, Ro, lc, ge, maps);
 }
