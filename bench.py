@@ -38,6 +38,8 @@ def main():
     ap.add_argument("--no-ceilings", action="store_true", help="skip the copy / fill / MFMA issue-rate probes")
     ap.add_argument("--no-kernel-timing", action="store_true",
                     help="leave the per-launch HIP events out of the timed region")
+    ap.add_argument("--op-sweep", action="store_true",
+                    help="time single operators over sentence length and hidden size instead of the certify benchmark")
     ap.add_argument("--probe", action="store_true",
                     help="counter probe: a 1 GiB device copy (known traffic) followed by one verify sweep, no timing")
     args = ap.parse_args()
@@ -58,6 +60,59 @@ def main():
     tok_d, pos_d = torch.as_tensor(tokens, device=dev), torch.as_tensor(positions, device=dev)
     ws = model.workspace(w.batch, w.seq_len, w.n_perturbed)
     full, _ = model.workspace_query(w.batch, w.seq_len, w.n_perturbed)
+
+    if args.op_sweep:
+        # Single operators over sentence length (hidden 128) and hidden size (length 16), after the paper's
+        # operator-level figures (Sec. 6.2: affine, ReLU, tanh, dot product); synthetic states, 32 sentences, P = 1.
+        def timed(fn, reps=20):
+            for _ in range(3):
+                fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) * 1e3 / reps
+
+        def state(Bn, C, L, n):
+            S = torch.randn(Bn, C, L, n, device=dev) * 0.05
+            R = torch.rand(Bn, C, L, n, device=dev) * 0.01
+            return S, R
+
+        Bn, p = 32, 2
+        eps = torch.full((Bn,), 1e-3, device=dev)
+        points = [(L, 128) for L in (4, 8, 16, 32, 64, 128)] + [(16, D) for D in (64, 192, 256, 384, 512, 640)]
+        for L, D in points:
+            C = D + 1
+            x = state(Bn, C, L, D)
+            W = torch.randn(D, D, device=dev) * 0.05
+            b = torch.randn(D, device=dev)
+            byts = 2 * 4 * Bn * C * L * D
+            rec = {"op_sweep": {"length": L, "hidden": D, "sentences": Bn, "state_MB": round(byts / 1e6, 2)}}
+            W3, Wa3 = tv.op_split3(W), tv.op_split3(W, True)
+            Sy, Ry = torch.empty_like(x[0]), torch.empty_like(x[1])
+            L_ = tv.lib()
+            us = timed(lambda: tv._check(L_.tv_op_affine_split(tv._ptr(x[0]), tv._ptr(x[1]), Bn, 1, D, L, D, D, tv._ptr(W3),
+                                                                 tv._ptr(Wa3), tv._ptr(b), None, None, tv._ptr(Sy),
+                                                                 tv._ptr(Ry), tv._stream())))
+            rec["affine_us"] = round(us, 1)
+            rec["affine_TFLOPs"] = round(2 * 2.0 * Bn * C * L * D * D / us / 1e6, 1)
+            rec["affine_GBps"] = round(2 * byts / us / 1e3, 0)
+            for act, nm in ((0, "relu"), (1, "tanh")):
+                us = timed(lambda: tv.op_activation(act, x[0], x[1], 1, D, 1, p, eps))
+                rec[nm + "_us"] = round(us, 1)
+                rec[nm + "_GBps"] = round(2 * byts / us / 1e3, 0)
+            if D % 4 == 0 and (D // 4) % 4 == 0:
+                q, k, v = x, state(Bn, C, L, D), state(Bn, C, L, D)
+                us = timed(lambda: tv.op_attention(q, k, v, 4, 1, p, eps, stop_after=1), reps=10)
+                rec["dot_product_us"] = round(us, 1)      # concretization of q, k, v + preparation + the q k^T bound
+                del q, k, v
+            print(json.dumps(rec), flush=True)
+            del x, Sy, Ry
+            torch.cuda.empty_cache()
+        return
 
     if args.probe:
         # for `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE`: the copy kernel moves exactly 2^30 bytes each way
