@@ -24,7 +24,7 @@ BF16_SPLIT_PEAK_TF = 2500.0 / 6.0   # dense bf16 peak over the six bf16 products
 # scaled by the counters' readings for the 2^30-byte copy of the same run (2048 and 1024 bytes per unit) and
 # averaged over the launches of one certify call; counters cannot be read inside this process, so the figure is
 # a constant of the workload and is reported only for the workload it was collected on
-PMC_TRAFFIC = {"c2": {"affine_gemm": 422.2e6, "layernorm": 246.6e6, "activation": 371.0e6, "softmax": 126.4e6}}
+PMC_TRAFFIC = {"c2": {"affine_gemm": 422.0e6, "layernorm": 246.6e6, "activation": 371.0e6, "softmax": 126.4e6}}
 MFMA_KINDS = ("affine_gemm", "qk_gemm_x", "qk_gemm_y", "pv_gemm_x", "pv_gemm_y", "head_gemm")
 
 
@@ -167,11 +167,39 @@ def main():
             out = model.certify(tok_d, pos_d, p, w.eps_lo, w.eps_hi, w.steps, workspace=ws)
         return out
 
-    for _ in range(args.warmup):
+    def breakdown(prof, nsteps):
+        total_ms = sum(v["ms"] for v in prof.values())
+        out = {}
+        for name, v in sorted(prof.items(), key=lambda kv: -kv[1]["ms"]):
+            out[name] = {"share": round(v["ms"] / total_ms, 4), "launches_per_step": v["launches"] // nsteps,
+                         "avg_us": round(v["ms"] * 1e3 / v["launches"], 2),
+                         "GBps": round(v["bytes"] / (v["ms"] * 1e-3) / 1e9, 1) if v["ms"] else 0.0,
+                         "TFLOPs": round(v["flops"] / (v["ms"] * 1e-3) / 1e12, 2) if v["ms"] else 0.0}
+        return out
+
+    # Two HIP events per launch cost a few microseconds each (about 8 % of a step when every class is timed), so the
+    # class breakdown is taken during the last warm-up step and the timed region times only the dominant class: its
+    # launch duration is still measured live over exactly the timed steps.
+    timing = not args.no_kernel_timing
+    kernels, dom = {}, None
+    for i in range(args.warmup):
+        last_warm = timing and i == args.warmup - 1
+        if last_warm:
+            torch.cuda.synchronize()
+            tv.profile_select(None)
+            tv.profile_reset()
+            tv.profile_enable(True)
         step()
+        if last_warm:
+            torch.cuda.synchronize()
+            tv.profile_enable(False)
+            prof = tv.profile_read()
+            kernels = breakdown(prof, 1)
+            dom = max(prof, key=lambda k: prof[k]["ms"])
     torch.cuda.synchronize()
-    if not args.no_kernel_timing:
+    if timing:
         tv.profile_reset()
+        tv.profile_select([dom] if dom else None)
         tv.profile_enable(True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -180,22 +208,17 @@ def main():
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     tv.profile_enable(False)
+    tv.profile_select(None)
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     n_cert = w.batch * len(w.p_norms)
     value = n_cert / (ms_per_step * 1e-3)
 
     roofline = None
-    kernels = {}
-    if not args.no_kernel_timing:
+    if timing:
         prof = tv.profile_read()
-        total_ms = sum(v["ms"] for v in prof.values())
-        for name, v in sorted(prof.items(), key=lambda kv: -kv[1]["ms"]):
-            avg_us = v["ms"] * 1e3 / v["launches"]
-            kernels[name] = {"share": round(v["ms"] / total_ms, 4), "launches_per_step": v["launches"] // args.steps,
-                             "avg_us": round(avg_us, 2),
-                             "GBps": round(v["bytes"] / (v["ms"] * 1e-3) / 1e9, 1) if v["ms"] else 0.0,
-                             "TFLOPs": round(v["flops"] / (v["ms"] * 1e-3) / 1e12, 2) if v["ms"] else 0.0}
-        dom = max(prof, key=lambda k: prof[k]["ms"])
+        if not kernels:                      # no warm-up step: every class was timed in the timed region
+            kernels = breakdown(prof, args.steps)
+        dom = dom or max(prof, key=lambda k: prof[k]["ms"])
         d = prof[dom]
         # the roof that bounds the class: its arithmetic intensity against the ridge of its own compute roof.
         # The affine layers run on the bf16 matrix cores with six products per fp32 product (three bf16 pieces per
@@ -217,6 +240,7 @@ def main():
             roofline["compute_roof_TFLOPs"] = round(compute_peak, 1)
         roofline["traffic"] = PMC_TRAFFIC.get(args.workload, {}).get(dom)
         roofline["avg_launch_us"] = round(d["ms"] * 1e3 / d["launches"], 2)
+        roofline["launches_timed"] = d["launches"]
         roofline["algorithmic_bytes_per_launch"] = d["bytes"] / d["launches"]
         roofline["algorithmic_flops_per_launch"] = d["flops"] / d["launches"]
 
@@ -251,7 +275,9 @@ def main():
                                f"position(s), balls p={list(w.p_norms)} (0 = inf), batch {w.batch}, "
                                f"{w.steps} bisection probes on [{w.eps_lo}, {w.eps_hi}]",
                    "certifications_per_step": n_cert, "workspace_bytes": int(ws.numel()),
-                   "batch_resident": bool(ws.numel() >= full), "kernel_timing_in_timed_region": not args.no_kernel_timing},
+                   "batch_resident": bool(ws.numel() >= full),
+                   "timed_region_times": ("the dominant kernel class" if timing else "nothing"),
+                   "class_breakdown_from": ("last warm-up step" if timing and args.warmup > 0 else "timed region")},
         "roofline": roofline, "cpu_baseline": cpu, "measured_ceilings": ceil, "kernels": kernels,
     }
     print(json.dumps(line))

@@ -192,6 +192,9 @@ int tv_op_attention(const float *Sq, const float *Rq, const float *Sk, const flo
  * contractions: 2 M N K per plane; memory-bound passes: one read and one write of the state).
  * Not thread-safe; do not enable while capturing a HIP graph. */
 int tv_profile_enable(int on);
+/* Restricts the timing to the kernel classes whose bit (1 << class index, see tv_profile_get) is set; two event
+ * records cost a few microseconds per launch, so a benchmark times only the class it reports.  Default: all. */
+int tv_profile_select(unsigned kind_mask);
 int tv_profile_reset(void);
 int tv_profile_kinds(void);
 int tv_profile_get(int kind, char *name, int name_len, double *total_ms, long long *launches, double *flops,

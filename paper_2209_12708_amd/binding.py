@@ -42,7 +42,7 @@ class _Weights(C.Structure):
 _lib = None
 
 EXPORTS = ("tv_version", "tv_last_error", "tv_model_create", "tv_model_destroy", "tv_workspace_query", "tv_verify",
-           "tv_certify", "tv_op_concretize", "tv_op_abs", "tv_op_affine", "tv_op_split3", "tv_op_affine_split", "tv_probe_mfma", "tv_op_activation", "tv_op_layernorm",
+           "tv_certify", "tv_op_concretize", "tv_op_abs", "tv_op_affine", "tv_op_split3", "tv_op_affine_split", "tv_probe_mfma", "tv_profile_select", "tv_op_activation", "tv_op_layernorm",
            "tv_attention_workspace", "tv_op_attention", "tv_profile_enable", "tv_profile_reset",
            "tv_profile_kinds", "tv_profile_get")
 
@@ -287,6 +287,21 @@ def probe_mfma(bf16, workgroups, iters, out):
 # ---- per-kernel-class timing --------------------------------------------------------------------
 def profile_enable(on=True):
     _check(lib().tv_profile_enable(1 if on else 0))
+
+
+def profile_select(names=None):
+    """Time only the named kernel classes (None: all)."""
+    if names is None:
+        _check(lib().tv_profile_select(0xFFFFFFFF))
+        return
+    mask = 0
+    for k in range(lib().tv_profile_kinds()):
+        name = C.create_string_buffer(64)
+        ms, fl, by, n = C.c_double(), C.c_double(), C.c_double(), C.c_longlong()
+        _check(lib().tv_profile_get(k, name, 64, C.byref(ms), C.byref(n), C.byref(fl), C.byref(by)))
+        if name.value.decode() in names:
+            mask |= 1 << k
+    _check(lib().tv_profile_select(mask))
 
 
 def profile_reset():

@@ -22,6 +22,7 @@ int fail(int code, const char *fmt, ...) {
 // ---- event timing ------------------------------------------------------------------------------
 struct ProfRec { int kind; hipEvent_t a, b; double flops, bytes; };
 static bool g_prof_on = false;
+static unsigned g_prof_mask = ~0u;       // kernel classes that are timed while profiling is on
 static std::vector<ProfRec> g_prof_recs;
 static std::vector<hipEvent_t> g_prof_pool;
 static const char *kKindNames[K_COUNT] = {"affine_gemm", "qk_gemm_x", "qk_gemm_y", "pv_gemm_x", "pv_gemm_y", "head_gemm",
@@ -35,7 +36,7 @@ static hipEvent_t prof_event() {
 }
 
 ProfScope::ProfScope(int kind, hipStream_t st, double flops, double bytes) : kind_(kind), st_(st), rec_(nullptr) {
-  if (!g_prof_on) return;
+  if (!g_prof_on || !((g_prof_mask >> kind) & 1u)) return;
   ProfRec *r = new ProfRec{kind, prof_event(), prof_event(), flops, bytes};
   (void)hipEventRecord(r->a, st);
   rec_ = r;
@@ -589,6 +590,11 @@ int tv_certify(const tv_model *m, const int32_t *tokens, int B, int L, const int
 // ---- timing ------------------------------------------------------------------------------------
 int tv_profile_enable(int on) {
   g_prof_on = on != 0;
+  return TV_OK;
+}
+
+int tv_profile_select(unsigned kind_mask) {
+  g_prof_mask = kind_mask;
   return TV_OK;
 }
 
