@@ -282,31 +282,19 @@ __device__ __forceinline__ Form gelu_inner(double lx, double ux, double &lb, dou
   return form_sub(a, k * c3, k, k * c3, k);
 }
 
-template <int VEC, int ACT, int PN>
-__global__ __launch_bounds__(kThreads) void activation_kernel(const float *S, const float *R, int P, int E, int X,
-                                                              int G, int gps, const float *eps,
-                                                              float *So, float *Ro, int32_t *status) {
-  constexpr int pn = PN;
-  __shared__ float red[4 * kWave * 8 * VEC];
-  const int chunk = 4 * G * VEC, c0 = blockIdx.y * chunk;
-  const Geo ge(G, min(chunk, X - c0) / 4);
-  const Loc lc{(long)blockIdx.x, P * E + 1, 1, 0, X, c0};
-  const double e = eps[blockIdx.x / gps];
-  float NL[4 * VEC], NU[4 * VEC], bS[4 * VEC], bR[4 * VEC];
-  column_norms<VEC>(S, R, lc, P, E, ge, pn, nullptr, red, NL, NU, bS, bR);
-  // Every row slot holds the same norms for the same columns.  The relaxation of a column (double precision; a
-  // bisection for tanh) is computed once: row slot s takes column s of each float4 group (VEC = 1: four slots, one
-  // column each) and publishes the map through LDS.  With 64 lanes per row a slot is a wave, so the other waves
-  // skip the code instead of repeating it.
-  static_assert(VEC == 1, "one float4 group per lane");
-  __shared__ Map2 smap[4 * kWave];
-  __shared__ LineCoef slc[4 * kWave];
-  Map2 maps[4];
-  bool bad = false;
+// Relaxation of this thread's four columns from their norms and bias values, as centre / radius maps.
+// Every row slot holds the same norms for the same columns.  The relaxation of a column (double precision; a root
+// search for tanh) is computed once: four row slots, one in each wave, take one column of each float4 group each
+// and publish the map through LDS, so a wave runs the code for one column instead of four.  second_norms(lcf, NL, NU): the norms of the lines lcf of the state (GELU's inner product).
+template <int ACT, typename NormFn>
+__device__ __forceinline__ void relax_columns(const Geo &ge, double e, float (&NL)[4], float (&NU)[4],
+                                              const float (&bS)[4], const float (&bR)[4], NormFn second_norms,
+                                              Map2 *smap, LineCoef *slc, Map2 (&maps)[4], bool &bad) {
+  const int own = ge.NS / 4;     // column i belongs to row slot i * NS / 4: one owner per wave when a wave holds several slots
   if (ACT != TV_ACT_GELU) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      if (ge.slot != i) continue;
+      if (ge.slot != i * own) continue;
       double l, u;
       range_of(bS[i], bR[i], e, NL[i], NU[i], l, u);
       bad |= !(finite_d(l) && finite_d(u));
@@ -318,7 +306,7 @@ __global__ __launch_bounds__(kThreads) void activation_kernel(const float *S, co
     double lx = 0.0, xS = 0.0, xR = 0.0;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      if (ge.slot != i) continue;
+      if (ge.slot != i * own) continue;
       double ux;
       range_of(bS[i], bR[i], e, NL[i], NU[i], lx, ux);
       bad |= !(finite_d(lx) && finite_d(ux));
@@ -333,10 +321,10 @@ __global__ __launch_bounds__(kThreads) void activation_kernel(const float *S, co
     LineCoef lcf[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) lcf[i] = slc[4 * ge.g + i];
-    column_norms<VEC>(S, R, lc, P, E, ge, pn, lcf, red, NL, NU, bS, bR);
+    second_norms(lcf, NL, NU);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      if (ge.slot != i) continue;
+      if (ge.slot != i * own) continue;
       // bias values of g's two lines, as centre / radius in double
       const Form &f = fg;
       const double gS = 0.5 * ((f.pL + f.qL + f.pU + f.qU) * xS + (-f.pL + f.qL + f.pU - f.qU) * xR + f.cL + f.cU);
@@ -354,8 +342,121 @@ __global__ __launch_bounds__(kThreads) void activation_kernel(const float *S, co
   __syncthreads();
 #pragma unroll
   for (int i = 0; i < 4; ++i) maps[i] = smap[4 * ge.g + i];
+}
+
+template <int VEC, int ACT, int PN>
+__global__ __launch_bounds__(kThreads) void activation_kernel(const float *S, const float *R, int P, int E, int X,
+                                                              int G, int gps, const float *eps,
+                                                              float *So, float *Ro, int32_t *status) {
+  constexpr int pn = PN;
+  static_assert(VEC == 1, "one float4 group per lane");
+  __shared__ float red[4 * kWave * 8 * VEC];
+  __shared__ Map2 smap[4 * kWave];
+  __shared__ LineCoef slc[4 * kWave];
+  const int chunk = 4 * G * VEC, c0 = blockIdx.y * chunk;
+  const Geo ge(G, min(chunk, X - c0) / 4);
+  const Loc lc{(long)blockIdx.x, P * E + 1, 1, 0, X, c0};
+  const double e = eps[blockIdx.x / gps];
+  float NL[4], NU[4], bS[4], bR[4];
+  column_norms<VEC>(S, R, lc, P, E, ge, pn, nullptr, red, NL, NU, bS, bR);
+  Map2 maps[4];
+  bool bad = false;
+  auto second = [&](const LineCoef (&lcf)[4], float (&nl)[4], float (&nu)[4]) {
+    float s0[4], r0[4];
+    column_norms<VEC>(S, R, lc, P, E, ge, pn, lcf, red, nl, nu, s0, r0);
+  };
+  relax_columns<ACT>(ge, e, NL, NU, bS, bR, second, smap, slc, maps, bad);
   if (bad) status[blockIdx.x / gps] = 1;
   apply_maps<VEC>(S, R, So, Ro, lc, ge, maps);
+}
+
+// Activation for small blocks (one perturbed position, at most ROWS coefficient rows per row slot): the chunk's rows
+// are read once, all loads in flight together, and stay in registers for the norms and the rescale - the
+// "loaded once" of the paper's sharing-oriented scheduling (Sec. 4.3) without the second pass through the cache.
+template <int ROWS, int ACT, int PN>
+__global__ __launch_bounds__(kThreads) void activation_cached_kernel(const float *S, const float *R, int nrows, int X,
+                                                                     int G, int gps, const float *eps, float *So,
+                                                                     float *Ro, int32_t *status) {
+  constexpr int pn = PN;
+  __shared__ float red[4 * kWave * 8];
+  __shared__ Map2 smap[4 * kWave];
+  __shared__ LineCoef slc[4 * kWave];
+  const int chunk = 4 * G, c0 = blockIdx.y * chunk;
+  const Geo ge(G, min(chunk, X - c0) / 4);
+  const Loc lc{(long)blockIdx.x, nrows + 1, 1, 0, X, c0};
+  const double e = eps[blockIdx.x / gps];
+  const bool colon = ge.g < ge.n4;
+
+  float xs[ROWS][4], xr[ROWS][4];
+#pragma unroll
+  for (int it = 0; it < ROWS; ++it) {
+    const int r = ge.slot + it * ge.NS;
+    float4 a = make_float4(0.f, 0.f, 0.f, 0.f), b = a;
+    if (r < nrows && colon) {
+      const long o = lc.off(r);
+      a = reinterpret_cast<const float4 *>(S + o)[ge.g];
+      b = reinterpret_cast<const float4 *>(R + o)[ge.g];
+    }
+    xs[it][0] = a.x; xs[it][1] = a.y; xs[it][2] = a.z; xs[it][3] = a.w;
+    xr[it][0] = b.x; xr[it][1] = b.y; xr[it][2] = b.z; xr[it][3] = b.w;
+  }
+  float bS[4], bR[4];
+  load_row<1>(S, R, lc, nrows, ge, bS, bR);
+
+  auto norms = [&](const LineCoef *lines, float (&nl)[4], float (&nu)[4]) {
+    float acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] = 0.f;
+#pragma unroll
+    for (int it = 0; it < ROWS; ++it) {
+      if (ge.slot + it * ge.NS < nrows) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          float a = xs[it][i] - xr[it][i], b = xs[it][i] + xr[it][i];
+          if (lines) {
+            a = lines[i].aS * xs[it][i] + lines[i].aR * xr[it][i];
+            b = lines[i].bS * xs[it][i] + lines[i].bR * xr[it][i];
+          }
+          acc[2 * i] = norm_acc(acc[2 * i], a, pn);
+          acc[2 * i + 1] = norm_acc(acc[2 * i + 1], b, pn);
+        }
+      }
+    }
+    slot_reduce<8>(acc, ge, pn == 1, red);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { nl[i] = norm_fin(acc[2 * i], pn); nu[i] = norm_fin(acc[2 * i + 1], pn); }
+  };
+  float NL[4], NU[4];
+  norms(nullptr, NL, NU);
+  Map2 maps[4];
+  bool bad = false;
+  auto second = [&](const LineCoef (&lcf)[4], float (&nl)[4], float (&nu)[4]) { norms(lcf, nl, nu); };
+  relax_columns<ACT>(ge, e, NL, NU, bS, bR, second, smap, slc, maps, bad);
+  if (bad) status[blockIdx.x / gps] = 1;
+
+#pragma unroll
+  for (int it = 0; it < ROWS; ++it) {
+    const int r = ge.slot + it * ge.NS;
+    if (r < nrows) {
+      float ys[4], yr[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        ys[i] = maps[i].sS * xs[it][i] + maps[i].sR * xr[it][i];
+        yr[i] = maps[i].rS * xs[it][i] + maps[i].rR * xr[it][i];
+      }
+      store_row<1>(So, Ro, lc, r, ge, ys, yr);
+    }
+  }
+  if (ge.slot == 0) {   // bias row: constants, double arithmetic
+    float ys[4], yr[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const double sb = bS[i], rb = bR[i];
+      ys[i] = (float)(maps[i].sSd * sb + maps[i].sRd * rb + maps[i].sCd);
+      yr[i] = (float)fmax(maps[i].rSd * sb + maps[i].rRd * rb + maps[i].rCd, 0.0);
+    }
+    store_row<1>(So, Ro, lc, nrows, ge, ys, yr);
+  }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -947,6 +1048,26 @@ int activation(int act, CState x, int groups, int P, int E, int T, int n, int gp
   chunk_geo(X, G, nch);
   const double C = (double)P * E + 1;
   ProfScope prof(K_ACTIVATION, st, 12.0 * groups * C * X, 16.0 * groups * C * X);
+  if (P == 1 && X % 64 == 0 && (E + 15) / 16 <= 8) {
+    // small blocks: 16 lanes (64 columns) per row and 16 row slots leave at most 8 rows per thread - read once
+    const int Gc = 16, nchc = (int)(X / 64);
+    dim3 gridc(groups, nchc), blockc(kThreads);
+#define ACTC_LAUNCH2(ROWS, A, PN)                                                                                   \
+  hipLaunchKernelGGL((activation_cached_kernel<ROWS, A, PN>), gridc, blockc, 0, st, x.S, x.R, E, (int)X, Gc, gps, eps, \
+                     y.S, y.R, status)
+#define ACTC_LAUNCH(PN)                                                                 \
+  do {                                                                                  \
+    const bool small = (E + 15) / 16 <= 4;                                              \
+    if (act == TV_ACT_RELU) { if (small) ACTC_LAUNCH2(4, TV_ACT_RELU, PN); else ACTC_LAUNCH2(8, TV_ACT_RELU, PN); } \
+    else if (act == TV_ACT_TANH) { if (small) ACTC_LAUNCH2(4, TV_ACT_TANH, PN); else ACTC_LAUNCH2(8, TV_ACT_TANH, PN); } \
+    else { if (small) ACTC_LAUNCH2(4, TV_ACT_GELU, PN); else ACTC_LAUNCH2(8, TV_ACT_GELU, PN); } \
+  } while (0)
+    NORM_SWITCH(pn, ACTC_LAUNCH);
+#undef ACTC_LAUNCH
+#undef ACTC_LAUNCH2
+    TV_HIP(hipGetLastError());
+    return TV_OK;
+  }
   dim3 grid(groups, nch), block(kThreads);
 #define ACT_LAUNCH(PN)                                                                                              \
   do {                                                                                                              \

@@ -131,9 +131,10 @@ def test_split3_pieces_sum_to_the_input(tv):
 
 @pytest.mark.parametrize("p", NORMS)
 @pytest.mark.parametrize("act,name", [(0, "relu"), (1, "tanh"), (2, "gelu")])
-def test_activation(tv, act, name, p):
+@pytest.mark.parametrize("shape", [(2, 3, 2, 24, 192), (2, 2, 1, 100, 96)])   # streaming kernel / register-resident kernel
+def test_activation(tv, act, name, p, shape):
     rng = np.random.default_rng(7 + act + 10 * p)
-    G, T, P, E, n, gps = 2, 3, 2, 24, 192, 1
+    (G, T, P, E, n), gps = shape, 1
     eps = 0.2
     X = quantize(random_state(rng, (G * T, n), P, E, eps, p, wscale=0.5), G)
     # include one-sided neurons
