@@ -148,11 +148,12 @@ int tv_op_affine(const float *Sx, const float *Rx, int groups, int P, int E, int
                  const float *Wabs, const float *bias, const float *Sadd, const float *Radd, float *Sy,
                  float *Ry, void *stream);
 
-/* out[p][i], p = 0..2: the three bf16 numbers whose sum is in[i] (|in[i]| when take_abs != 0), stored as
- * raw 16-bit patterns; out holds 3 * count values.  Prepares constant weights for tv_op_affine_split. */
-int tv_op_split3(const float *in, uint16_t *out, size_t count, int take_abs, void *stream);
+/* The three bf16 numbers whose sum is each weight of in [N][K] (its absolute value when take_abs != 0), as
+ * raw 16-bit patterns in the order tv_op_affine_split stages them: out[k / 32][p][n][k % 32], p = 0..2,
+ * K padded with zeros to Kp = 32 * ceil(K / 32); out holds 3 * N * Kp values. */
+int tv_op_split3(const float *in, uint16_t *out, int N, int K, int take_abs, void *stream);
 
-/* tv_op_affine with the weights given as bf16 pieces (W3, Wabs3: [3][N][K] from tv_op_split3): six
+/* tv_op_affine with the weights given as bf16 pieces (W3, Wabs3 from tv_op_split3): six
  * bf16 MFMA products per fp32 product, fp32 accumulation, accuracy of the fp32 kernel.  This is the
  * kernel tv_verify / tv_certify use for the weight matrices of the model.  K % 8 == 0, N % 4 == 0. */
 int tv_op_affine_split(const float *Sx, const float *Rx, int groups, int P, int E, int T, int K, int N,

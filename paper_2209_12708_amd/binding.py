@@ -69,7 +69,7 @@ def lib():
         L.tv_op_concretize.argtypes = [vp, vp, i, i, i, i, i, i, i, vp, vp, vp, vp]
         L.tv_op_abs.argtypes = [vp, vp, sz, vp]
         L.tv_op_affine.argtypes = [vp, vp, i, i, i, i, i, i, vp, vp, vp, vp, vp, vp, vp, vp]
-        L.tv_op_split3.argtypes = [vp, vp, sz, i, vp]
+        L.tv_op_split3.argtypes = [vp, vp, i, i, i, vp]
         L.tv_probe_mfma.argtypes = [i, i, i, vp, C.POINTER(C.c_double), vp]
         L.tv_op_affine_split.argtypes = [vp, vp, i, i, i, i, i, i, vp, vp, vp, vp, vp, vp, vp, vp]
         L.tv_op_activation.argtypes = [i, vp, vp, i, i, i, i, i, i, i, vp, vp, vp, vp, vp]
@@ -223,9 +223,10 @@ def op_affine(S, R, P, E, W, bias=None, add=None):
 
 
 def op_split3(x, take_abs=False):
-    """bf16 pieces [3, *x.shape] (int16 bit patterns) of x or |x|."""
-    out = torch.empty((3,) + tuple(x.shape), dtype=torch.int16, device=x.device)
-    _check(lib().tv_op_split3(_ptr(x), _ptr(out), x.numel(), 1 if take_abs else 0, _stream()))
+    """bf16 pieces (int16 bit patterns) of the matrix x [N, K] or of |x|, as [ceil(K / 32), 3, N, 32]."""
+    N, K = x.shape
+    out = torch.empty(((K + 31) // 32, 3, N, 32), dtype=torch.int16, device=x.device)
+    _check(lib().tv_op_split3(_ptr(x), _ptr(out), N, K, 1 if take_abs else 0, _stream()))
     return out
 
 

@@ -11,10 +11,12 @@
 // HBM roof.  The weights are split once when the model is created (split3); the state is split while
 // a tile is staged into LDS.
 //
-// Tiling as in gemm.hip: a workgroup of 4 waves owns a BM x BN tile, K advances in stages of 32 through
+// Tiling as in gemm.hip: a workgroup of 4 or 8 waves owns a BM x BN tile, K advances in stages of 32 through
 // LDS with a register prefetch of the next stage, XCD-aware tile order.  LDS holds the three pieces of
 // both operands as [row][k] bf16 with rows padded to 80 bytes, so the 16-byte fragment reads of 16
-// consecutive rows fall on distinct 16-byte bank groups.
+// consecutive rows fall on distinct 16-byte bank groups.  The weight pieces lie in memory stage by stage
+// (split3_kernel), so a stage of a tile's weights - 1.5 times the bytes of the state's stage, and the larger
+// part of the traffic between L2 and the CU - is read as whole cache lines.
 #include "common.h"
 
 namespace tv {
@@ -26,7 +28,7 @@ typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 
 struct Affine3Args {
   const float *A; long sA;              // [M][K] fp32; the two planes are sA floats apart
-  const unsigned short *W3; long sW;    // [3][N][K] bf16 pieces of W; planes (W, |W|) sW elements apart
+  const unsigned short *W3; long sW;    // [K/32][3][N][32] bf16 pieces of W (split3_kernel); planes (W, |W|) sW elements apart
   float *C; long sC;                    // [M][N]
   const float *Cadd; long sAdd;         // residual, same layout as C, or nullptr
   const float *bias; long sBias;        // [N] added on bias rows, or nullptr
@@ -43,15 +45,21 @@ __device__ __forceinline__ void split3(float x, __bf16 &a, __bf16 &b, __bf16 &c)
   c = (__bf16)r2;
 }
 
-__global__ void split3_kernel(const float *in, unsigned short *out, size_t count, int take_abs) {
+// Pieces of a weight matrix [N][K] in the order the affine kernel stages them: out[k / 32][piece][n][k % 32], K
+// padded with zeros to a multiple of 32 (Kp).  One stage of a tile's weights is then three contiguous runs of
+// BN * 64 bytes, read as whole cache lines.
+__global__ void split3_kernel(const float *in, unsigned short *out, int N, int K, int Kp, int take_abs) {
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x, count = (size_t)N * Kp;
   __bf16 *o = reinterpret_cast<__bf16 *>(out);
   for (; i < count; i += stride) {
-    const float x = take_abs ? fabsf(in[i]) : in[i];
+    const int n = (int)(i / Kp), k = (int)(i % Kp);
+    float x = k < K ? in[(size_t)n * K + k] : 0.f;
+    if (take_abs) x = fabsf(x);
     __bf16 a, b, c;
     split3(x, a, b, c);
-    o[i] = a; o[count + i] = b; o[2 * count + i] = c;
+    const size_t at = ((size_t)(k / 32) * 3 * N + n) * 32 + k % 32, piece = (size_t)N * 32;
+    o[at] = a; o[at + piece] = b; o[at + 2 * piece] = c;
   }
 }
 
@@ -85,15 +93,26 @@ __global__ __launch_bounds__(256) void mfma_probe_kernel(float *out, int iters, 
   out[(size_t)blockIdx.x * 256 + threadIdx.x] = s;
 }
 
+// LDS of one workgroup: the stage buffers (three pieces of both operands, rows of 80 bytes) or the staged output tile
+constexpr int affine3_lds(int BM, int BN) {
+  return 3 * 80 * (BM + BN) > BM * (BN + 4) * 4 ? 3 * 80 * (BM + BN) : BM * (BN + 4) * 4;
+}
+// waves per SIMD when LDS (160 KB per CU) decides the number of resident workgroups: the register budget to aim for
+constexpr int affine3_waves(int BM, int BN, int WM, int WN) {
+  return (160 * 1024 / affine3_lds(BM, BN)) * WM * WN / 4;
+}
+
 template <int BM, int BN, int WM, int WN, int PF, int PB>
-__global__ __launch_bounds__(256) void affine3_kernel(const Affine3Args g, int mtiles, int ntiles) {
+__global__ __launch_bounds__(WM * WN * 64) __attribute__((amdgpu_waves_per_eu(affine3_waves(BM, BN, WM, WN))))
+void affine3_kernel(const Affine3Args g, int mtiles, int ntiles) {
   constexpr int BK = 32;
   constexpr int RS = 80;                           // LDS row stride in bytes (32 bf16 + 16 bytes of padding)
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
   constexpr int A_P = BM * RS, B_P = BN * RS;      // bytes per piece
-  constexpr int A_F4 = BM * 8 / 256;               // float4 loads of A per thread and stage
-  constexpr int B_CH = 3 * BN * 4 / 256;           // 16-byte chunks of the weight pieces per thread and stage
-  static_assert(A_F4 >= 1 && B_CH >= 1 && (3 * BN * 4) % 256 == 0 && (BM * 8) % 256 == 0, "tile too small");
+  constexpr int NT = WM * WN * 64;                 // threads
+  constexpr int A_F4 = BM * 8 / NT;                // float4 loads of A per thread and stage
+  constexpr int B_CH = 3 * BN * 4 / NT;            // 16-byte chunks of the weight pieces per thread and stage
+  static_assert(A_F4 >= 1 && B_CH >= 1 && (3 * BN * 4) % NT == 0 && (BM * 8) % NT == 0, "tile too small");
   constexpr int STAGE_BYTES = 3 * A_P + 3 * B_P, TILE_BYTES = BM * (BN + 4) * 4;   // stage buffers / staged output tile
   __shared__ __attribute__((aligned(16))) unsigned char lds[STAGE_BYTES > TILE_BYTES ? STAGE_BYTES : TILE_BYTES];
   unsigned char *As = lds, *Bs = lds + 3 * A_P;
@@ -126,19 +145,19 @@ __global__ __launch_bounds__(256) void affine3_kernel(const Affine3Args g, int m
   const float *a_ptr[A_F4]; int a_k[A_F4], a_lds[A_F4];
 #pragma unroll
   for (int i = 0; i < A_F4; ++i) {
-    const int f = tid + 256 * i, row = f / 8, kq = f % 8;
+    const int f = tid + NT * i, row = f / 8, kq = f % 8;
     int m = m0 + row; if (m >= M) m = M - 1;
     a_ptr[i] = A + (long)m * K;
     a_k[i] = kq * 4;
     a_lds[i] = row * RS + kq * 8;
   }
-  const __bf16 *b_ptr[B_CH]; int b_k[B_CH], b_lds[B_CH];
+  const __bf16 *b_ptr[B_CH]; int b_lds[B_CH];
+  const long b_stage = 3L * N * 32;                // elements from one 32-wide stage of the weights to the next
 #pragma unroll
   for (int i = 0; i < B_CH; ++i) {
-    const int f = tid + 256 * i, piece = f / (BN * 4), rem = f % (BN * 4), row = rem / 4, c = rem % 4;
+    const int f = tid + NT * i, piece = f / (BN * 4), rem = f % (BN * 4), row = rem / 4, c = rem % 4;
     int n = n0 + row; if (n >= N) n = N - 1;
-    b_ptr[i] = W3 + (long)piece * N * K + (long)n * K;
-    b_k[i] = c * 8;
+    b_ptr[i] = W3 + ((long)piece * N + n) * 32 + c * 8;
     b_lds[i] = piece * B_P + row * RS + c * 16;
   }
 
@@ -152,12 +171,10 @@ __global__ __launch_bounds__(256) void affine3_kernel(const Affine3Args g, int m
       r[i] = k < K ? *reinterpret_cast<const float4 *>(a_ptr[i] + k) : make_float4(0.f, 0.f, 0.f, 0.f);
     }
   };
-  auto load_b = [&](uint4 (&r)[B_CH], int k0) {
+  auto load_b = [&](uint4 (&r)[B_CH], int kt) {     // stage kt < KT (the pieces are zero-padded to whole stages)
 #pragma unroll
-    for (int i = 0; i < B_CH; ++i) {
-      const int k = k0 + b_k[i];
-      r[i] = k < K ? *reinterpret_cast<const uint4 *>(b_ptr[i] + k) : make_uint4(0u, 0u, 0u, 0u);
-    }
+    for (int i = 0; i < B_CH; ++i)
+      r[i] = *reinterpret_cast<const uint4 *>(b_ptr[i] + kt * b_stage);
   };
   auto store_stage = [&](const float4 (&xa)[A_F4], const uint4 (&xb)[B_CH]) {
 #pragma unroll
@@ -190,7 +207,7 @@ __global__ __launch_bounds__(256) void affine3_kernel(const Affine3Args g, int m
 #pragma unroll
   for (int s = 0; s < PF; ++s) load_a(ra[s], s * BK);          // stages beyond K load zeros (never used)
 #pragma unroll
-  for (int s = 0; s < PB; ++s) load_b(rb[s], s * BK);
+  for (int s = 0; s < PB; ++s) load_b(rb[s], s < KT ? s : 0);
   for (int kt0 = 0; kt0 < KT; kt0 += PF) {
 #pragma unroll
     for (int s = 0; s < PF; ++s) {
@@ -199,7 +216,7 @@ __global__ __launch_bounds__(256) void affine3_kernel(const Affine3Args g, int m
         store_stage(ra[s], rb[s % PB]);
         __syncthreads();
         if (kt + PF < KT) load_a(ra[s], (kt + PF) * BK);
-        if (kt + PB < KT) load_b(rb[s % PB], (kt + PB) * BK);
+        if (kt + PB < KT) load_b(rb[s % PB], kt + PB);
         // lane l holds k = 8 (l / 32) .. + 7 of each 16-wide MFMA step, for row / column l % 32
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) {
@@ -236,6 +253,20 @@ __global__ __launch_bounds__(256) void affine3_kernel(const Affine3Args g, int m
   // free after the last barrier) and leaves as 16 bytes per lane along rows - 512 contiguous bytes per row of a
   // 128-wide tile - which is what the HBM write path wants; the residual is read the same way.
   constexpr int CS = BN + 4;                       // padded row stride of the staged tile (floats)
+  constexpr int NQ = BN / 4, EP = BM * NQ / NT;   // 16-byte pieces per row / per thread
+  // the residual's loads go out first: their latency passes while the tile is staged
+  float4 radd[EP];
+  if (Cadd) {
+#pragma unroll
+    for (int it = 0; it < EP; ++it) {
+      const int f = tid + NT * it, row = f / NQ, c4 = f % NQ;
+      const int m = m0 + row, n = n0 + c4 * 4;
+      radd[it] = (m < M && n < N) ? *reinterpret_cast<const float4 *>(Cadd + (long)m * N + n) : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+  } else {
+#pragma unroll
+    for (int it = 0; it < EP; ++it) radd[it] = make_float4(0.f, 0.f, 0.f, 0.f);
+  }
   float *Ct = reinterpret_cast<float *>(lds);
 #pragma unroll
   for (int i = 0; i < TM; ++i)
@@ -252,17 +283,13 @@ __global__ __launch_bounds__(256) void affine3_kernel(const Affine3Args g, int m
     const int ba = m0 / g.bias_T, bb = (min(m0 + BM, M) - 1) / g.bias_T;
     tile_has_bias = (ba % g.bias_C) + (bb - ba) >= g.bias_C - 1;
   }
-  constexpr int NQ = BN / 4;
 #pragma unroll
-  for (int f = tid; f < BM * NQ; f += 256) {
-    const int row = f / NQ, c4 = f % NQ;
+  for (int it = 0; it < EP; ++it) {
+    const int f = tid + NT * it, row = f / NQ, c4 = f % NQ;
     const int m = m0 + row, n = n0 + c4 * 4;
     if (m >= M || n >= N) continue;
     float4 v = *reinterpret_cast<const float4 *>(Ct + row * CS + c4 * 4);
-    if (Cadd) {
-      const float4 a = *reinterpret_cast<const float4 *>(Cadd + (long)m * N + n);
-      v.x += a.x; v.y += a.y; v.z += a.z; v.w += a.w;
-    }
+    v.x += radd[it].x; v.y += radd[it].y; v.z += radd[it].z; v.w += radd[it].w;
     if (tile_has_bias && (m / g.bias_T) % g.bias_C == g.bias_C - 1) {
       // rows are ordered (group, coefficient row, t); the last coefficient row is the bias row
       const float4 b = *reinterpret_cast<const float4 *>(bias + n);
@@ -277,7 +304,7 @@ int launch3(const Affine3Args &g, int planes, hipStream_t st) {
   const int mtiles = (g.M + BM - 1) / BM, ntiles = (g.N + BN - 1) / BN;
   const long groups = mtiles >= 8 ? (long)((mtiles + 7) / 8) * 8 * ntiles : (long)mtiles * ntiles;
   TV_REQUIRE(groups < (1L << 31), TV_E_SHAPE, "affine: grid too large");
-  hipLaunchKernelGGL((affine3_kernel<BM, BN, WM, WN, PF, PB>), dim3((unsigned)groups, (unsigned)planes, 1), dim3(256), 0, st, g,
+  hipLaunchKernelGGL((affine3_kernel<BM, BN, WM, WN, PF, PB>), dim3((unsigned)groups, (unsigned)planes, 1), dim3(WM * WN * 64), 0, st, g,
                      mtiles, ntiles);
   TV_HIP(hipGetLastError());
   return TV_OK;
@@ -295,11 +322,13 @@ int mfma_probe(int bf16, int workgroups, int iters, float *out, double *flops, h
   return TV_OK;
 }
 
-int split_bf16x3(const float *in, unsigned short *out, size_t count, bool take_abs, hipStream_t st) {
+int split_bf16x3(const float *in, unsigned short *out, int N, int K, bool take_abs, hipStream_t st) {
   TV_REQUIRE(in && out, TV_E_NULL, "split_bf16x3: null pointer");
-  if (count == 0) return TV_OK;
+  TV_REQUIRE(N > 0 && K > 0, TV_E_SHAPE, "split_bf16x3: empty matrix");
+  const int Kp = (K + 31) / 32 * 32;
+  const size_t count = (size_t)N * Kp;
   const unsigned blocks = (unsigned)((count + 255) / 256 > 4096 ? 4096 : (count + 255) / 256);
-  hipLaunchKernelGGL(split3_kernel, dim3(blocks), dim3(256), 0, st, in, out, count, take_abs ? 1 : 0);
+  hipLaunchKernelGGL(split3_kernel, dim3(blocks), dim3(256), 0, st, in, out, N, K, Kp, take_abs ? 1 : 0);
   TV_HIP(hipGetLastError());
   return TV_OK;
 }
@@ -313,7 +342,7 @@ int affine_split(const float *xS, long xplane, long M, int C, int T, int K, int 
   TV_REQUIRE(bpair == nullptr || (T > 0 && C > 0), TV_E_ARG, "affine: bias without row structure");
   Affine3Args g;
   g.A = xS; g.sA = xplane;
-  g.W3 = W3pair; g.sW = 3L * N * K;
+  g.W3 = W3pair; g.sW = 3L * N * ((K + 31) / 32 * 32);
   g.C = yS; g.sC = yplane;
   g.Cadd = addS; g.sAdd = addplane;
   g.bias = bpair; g.sBias = N; g.bias_T = T; g.bias_C = C;
@@ -321,9 +350,13 @@ int affine_split(const float *xS, long xplane, long M, int C, int T, int K, int 
   const double mn = (double)M * N;
   ProfScope prof(K_AFFINE, st, planes * 2.0 * mn * K,
                  planes * 4.0 * ((double)M * K + (double)N * K + mn * (addS ? 2.0 : 1.0)));
+  const bool big = M >= 128 * 256;
   if (N <= 64) return launch3<128, 64, 2, 2>(g, planes, st);
   // wide layers: 64 x 64 per wave halves the LDS traffic per MFMA (measured +4..13 % from K = 256, N = 512 up)
-  if (K >= 256 && N >= 512 && M >= 128 * 256) return launch3<128, 128, 2, 2>(g, planes, st);
+  if (K >= 256 && N >= 512 && big) return launch3<128, 128, 2, 2>(g, planes, st);
+  // many rows, narrow layers: eight waves on a 128 x 128 tile fetch the weight pieces once per 128 rows and keep
+  // 16 waves per CU resident (measured +2..7 % against four waves on 64 x 128)
+  if (big) return launch3<128, 128, 4, 2>(g, planes, st);
   return launch3<64, 128, 2, 2>(g, planes, st);
 }
 

@@ -79,10 +79,11 @@ int gemm(const GemmArgs &g, hipStream_t st);
 // matrix-core issue probe: `workgroups` x 4 waves x `iters` rounds of 16 MFMA instructions (fp32 32x32x2 or bf16
 // 32x32x16); out holds workgroups * 256 floats; *flops = the multiply-add flops of the launch
 int mfma_probe(int bf16, int workgroups, int iters, float *out, double *flops, hipStream_t st);
-// out[p][i] = p-th bf16 piece of in[i] (or of |in[i]|), p = 0..2: in = out[0] + out[1] + out[2]
-int split_bf16x3(const float *in, unsigned short *out, size_t count, bool take_abs, hipStream_t st);
+// bf16 pieces of a weight matrix in [N][K] (or of its absolute value): out[k / 32][p][n][k % 32], p = 0..2, the
+// three pieces sum to the weight; K is padded with zeros to a multiple of 32, out holds 3 * N * Kp values
+int split_bf16x3(const float *in, unsigned short *out, int N, int K, bool take_abs, hipStream_t st);
 // y = x W^T (+ bias on bias rows of the centre plane) (+ add) for both planes in one launch.  W3pair:
-// [2][3][N][K] bf16 pieces of (W, |W|); bpair: [2][N] = (b, 0) or nullptr; planes of x / add / y are xplane /
+// split_bf16x3 of W, then of |W| (3 * N * Kp values each); bpair: [2][N] = (b, 0) or nullptr; planes of x / add / y are xplane /
 // addplane / yplane floats apart; rows are (group, coefficient row of C, t of T).  K % 8 == 0.
 int affine_split(const float *xS, long xplane, long M, int C, int T, int K, int N, const unsigned short *W3pair,
                  const float *bpair, const float *addS, long addplane, float *yS, long yplane, hipStream_t st,

@@ -206,6 +206,7 @@ Plan make_plan(const tv_config &c, int Bc, int L, int P, bool cache0 = false) {
   const size_t C = (size_t)P * D + 1;
   const size_t rows = (size_t)Bc * L;
   size_t o = 0;
+  auto pad32 = [](size_t k) { return (k + 31) / 32 * 32; };
   auto take = [&](size_t n) { size_t r = o; o += align_up(n); return r; };
   Plan p;
   p.NP = (2 * c.n_classes - 1 + 3) / 4 * 4;
@@ -423,6 +424,7 @@ int tv_model_create(const tv_config *cfg, const tv_weights *w, tv_model **out) {
   m->cfg = c;
   m->layers.resize(c.n_layers);
   size_t o = 0;
+  auto pad32 = [](size_t k) { return (k + 31) / 32 * 32; };
   auto take = [&](size_t n) { size_t r = o; o += align_up(n); return r; };
   const size_t o_tok = take((size_t)c.vocab * D), o_pos = take((size_t)c.max_len * D);
   const size_t o_wc = take((size_t)c.n_classes * D), o_bc = take(c.n_classes);
@@ -435,8 +437,8 @@ int tv_model_create(const tv_config *cfg, const tv_weights *w, tv_model **out) {
     f.W1 = take(2 * F * D); f.b1 = take(2 * F);
     f.W2 = take(2 * D * F); f.b2 = take(2 * D);
     f.g1 = take(D); f.be1 = take(D); f.g2 = take(D); f.be2 = take(D);
-    // bf16 pieces [2][3][n] of each matrix: 6 n halves = 3 n floats
-    f.Wqkv3 = take(3 * 3 * D * D); f.Wo3 = take(3 * D * D); f.W13 = take(3 * F * D); f.W23 = take(3 * D * F);
+    // bf16 pieces of (W, |W|): 2 * 3 * N * pad32(K) values of 2 bytes = 3 N pad32(K) floats
+    f.Wqkv3 = take(3 * 3 * D * pad32(D)); f.Wo3 = take(3 * D * pad32(D)); f.W13 = take(3 * F * pad32(D)); f.W23 = take(3 * D * pad32(F));
   }
   m->blob_floats = o;
   hipError_t e = hipMalloc(&m->blob, o * sizeof(float));
@@ -449,10 +451,10 @@ int tv_model_create(const tv_config *cfg, const tv_weights *w, tv_model **out) {
   auto put_abs = [&](size_t base, size_t n) {   // second copy = |first copy|
     if (e == hipSuccess && tv::vec_abs(m->blob + base, m->blob + base + n, n, nullptr) != TV_OK) e = hipErrorUnknown;
   };
-  auto put_split = [&](size_t src, size_t dst, size_t n) {   // pieces of the first copy, then of its absolute value
+  auto put_split = [&](size_t src, size_t dst, int N, int K) {   // pieces of the first copy, then of its absolute value
     unsigned short *o3 = reinterpret_cast<unsigned short *>(m->blob + dst);
-    if (e == hipSuccess && (tv::split_bf16x3(m->blob + src, o3, n, false, nullptr) != TV_OK ||
-                            tv::split_bf16x3(m->blob + src, o3 + 3 * n, n, true, nullptr) != TV_OK))
+    if (e == hipSuccess && (tv::split_bf16x3(m->blob + src, o3, N, K, false, nullptr) != TV_OK ||
+                            tv::split_bf16x3(m->blob + src, o3 + 3 * (size_t)N * pad32(K), N, K, true, nullptr) != TV_OK))
       e = hipErrorUnknown;
   };
   put(o_tok, w->tok_emb, (size_t)c.vocab * D); put(o_pos, w->pos_emb, (size_t)c.max_len * D);
@@ -473,13 +475,13 @@ int tv_model_create(const tv_config *cfg, const tv_weights *w, tv_model **out) {
     d.W1 = m->blob + f.W1; d.b1 = m->blob + f.b1; d.W2 = m->blob + f.W2; d.b2 = m->blob + f.b2;
     d.ln1_g = m->blob + f.g1; d.ln1_b = m->blob + f.be1; d.ln2_g = m->blob + f.g2; d.ln2_b = m->blob + f.be2;
     if (D % 8 == 0) {
-      put_split(f.Wqkv, f.Wqkv3, 3 * D * D); put_split(f.Wo, f.Wo3, D * D); put_split(f.W1, f.W13, F * D);
+      put_split(f.Wqkv, f.Wqkv3, 3 * (int)D, (int)D); put_split(f.Wo, f.Wo3, (int)D, (int)D); put_split(f.W1, f.W13, (int)F, (int)D);
       d.Wqkv3 = reinterpret_cast<unsigned short *>(m->blob + f.Wqkv3);
       d.Wo3 = reinterpret_cast<unsigned short *>(m->blob + f.Wo3);
       d.W13 = reinterpret_cast<unsigned short *>(m->blob + f.W13);
     }
     if (F % 8 == 0) {
-      put_split(f.W2, f.W23, D * F);
+      put_split(f.W2, f.W23, (int)D, (int)F);
       d.W23 = reinterpret_cast<unsigned short *>(m->blob + f.W23);
     }
   }
@@ -659,8 +661,8 @@ int tv_op_affine(const float *Sx, const float *Rx, int groups, int P, int E, int
   return gemm(g, st);
 }
 
-int tv_op_split3(const float *in, uint16_t *out, size_t count, int take_abs, void *stream) {
-  return split_bf16x3(in, out, count, take_abs != 0, static_cast<hipStream_t>(stream));
+int tv_op_split3(const float *in, uint16_t *out, int N, int K, int take_abs, void *stream) {
+  return split_bf16x3(in, out, N, K, take_abs != 0, static_cast<hipStream_t>(stream));
 }
 
 int tv_op_affine_split(const float *Sx, const float *Rx, int groups, int P, int E, int T, int K, int N,

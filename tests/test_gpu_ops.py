@@ -119,11 +119,16 @@ def test_affine_split_weights(tv, G, T, P, E, K, N, bias, add):
 
 def test_split3_pieces_sum_to_the_input(tv):
     rng = np.random.default_rng(5)
-    x = (rng.standard_normal(4096) * 10.0 ** rng.uniform(-6, 6, 4096)).astype(np.float32)
-    x[:4] = [0.0, -0.0, 1.0, -3.0e-39]
+    N, K = 96, 40                                   # K is padded to 64 in the staged layout
+    x = (rng.standard_normal((N, K)) * 10.0 ** rng.uniform(-6, 6, (N, K))).astype(np.float32)
+    x[0, :4] = [0.0, -0.0, 1.0, -3.0e-39]
     for take_abs in (False, True):
         pieces = tv.op_split3(dev(x), take_abs).cpu().numpy().view(np.uint16).astype(np.uint32) << 16
-        total = pieces.view(np.float32).astype(np.float64).sum(0)
+        assert pieces.shape == (2, 3, N, 32)
+        total = pieces.view(np.float32).astype(np.float64).sum(1)          # [K / 32][N][32]
+        total = total.transpose(1, 0, 2).reshape(N, 64)
+        assert np.all(total[:, K:] == 0.0)
+        total = total[:, :K]
         ref = np.abs(x) if take_abs else x
         # denormal inputs may be flushed: allow the smallest normal number as absolute slack
         assert np.all(np.abs(total - ref) <= 2.0 ** -23 * np.abs(ref) + 1.2e-38)
