@@ -25,6 +25,7 @@ namespace {
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 
 struct Affine3Args {
   const float *A; long sA;              // [M][K] fp32; the two planes are sA floats apart
@@ -163,7 +164,7 @@ void affine3_kernel(const Affine3Args g, int mtiles, int ntiles) {
 
   // Register prefetch, PF stages of the state and PB of the weight pieces ahead of the products.  One stage
   // each measured fastest on the layer shapes of the benchmark (deeper rings cost a workgroup per CU).
-  float4 ra[PF][A_F4]; uint4 rb[PB][B_CH];
+  float4 ra[PF][A_F4]; u32x4 rb[PB][B_CH];
   auto load_a = [&](float4 (&r)[A_F4], int k0) {
 #pragma unroll
     for (int i = 0; i < A_F4; ++i) {
@@ -171,12 +172,12 @@ void affine3_kernel(const Affine3Args g, int mtiles, int ntiles) {
       r[i] = k < K ? *reinterpret_cast<const float4 *>(a_ptr[i] + k) : make_float4(0.f, 0.f, 0.f, 0.f);
     }
   };
-  auto load_b = [&](uint4 (&r)[B_CH], int kt) {     // stage kt < KT (the pieces are zero-padded to whole stages)
+  auto load_b = [&](u32x4 (&r)[B_CH], int kt) {     // stage kt < KT (the pieces are zero-padded to whole stages)
 #pragma unroll
     for (int i = 0; i < B_CH; ++i)
-      r[i] = *reinterpret_cast<const uint4 *>(b_ptr[i] + kt * b_stage);
+      r[i] = *reinterpret_cast<const u32x4 *>(b_ptr[i] + kt * b_stage);
   };
-  auto store_stage = [&](const float4 (&xa)[A_F4], const uint4 (&xb)[B_CH]) {
+  auto store_stage = [&](const float4 (&xa)[A_F4], const u32x4 (&xb)[B_CH]) {
 #pragma unroll
     for (int i = 0; i < A_F4; ++i) {
       bf16x4 p0, p1, p2;
@@ -192,7 +193,7 @@ void affine3_kernel(const Affine3Args g, int mtiles, int ntiles) {
       *reinterpret_cast<bf16x4 *>(As + 2 * A_P + a_lds[i]) = p2;
     }
 #pragma unroll
-    for (int i = 0; i < B_CH; ++i) *reinterpret_cast<uint4 *>(Bs + b_lds[i]) = xb[i];
+    for (int i = 0; i < B_CH; ++i) *reinterpret_cast<u32x4 *>(Bs + b_lds[i]) = xb[i];
   };
 
   f32x16 acc[TM][TN];
