@@ -825,12 +825,18 @@ __global__ __launch_bounds__(NT) void layernorm_cached_kernel(const float *S, co
 // (g, i).   shift by max_j u_j ; e = exp (relaxed) ; sigma = sum_j e ; rho = 1 / sigma ; p = e * rho.
 // Sweeps: norms of s; norm of sigma; output p (and the norm of p's lower line for its concretized
 // lower bound).  Writes lp (clamped to [0, 1]) and the slack S_p_b - lp.
+// The double-precision scalars are computed once per workgroup: the exp relaxation by one lane per column
+// (a wave chosen by the block index, so the work spreads over the SIMDs of a CU), everything per row and the
+// bias row by row slot 0; the other threads read the float coefficients from LDS.
 template <int VEC, int PN>
 __global__ __launch_bounds__(kThreads) void softmax_kernel(float *S, float *R, int P, int E, int T_, int n, int G,
                                                            int gps, const float *eps, float *lp_out,
                                                            float *slack_out, int32_t *status) {
   constexpr int pn = PN;
   __shared__ float red[4 * kWave * 8 * VEC];
+  extern __shared__ double col_dyn[];                    // [6][n]  in: l, u (shifted), shift; out: kL, hk, dk, hc, dc, le
+  __shared__ float tokf[8];
+  auto col_d = [&](int k, int col) -> double & { return col_dyn[k * n + col]; };
   const int C = P * E + 1;
   const Geo ge(G, n / 4);
   const Loc lc{(long)(blockIdx.x / T_), C, T_, (int)(blockIdx.x % T_), n, 0};
@@ -843,29 +849,47 @@ __global__ __launch_bounds__(kThreads) void softmax_kernel(float *S, float *R, i
 
   float NLs[4 * VEC], NU[4 * VEC], bS[4 * VEC], bR[4 * VEC];
   column_norms<VEC>(S, R, lc, P, E, ge, pn, nullptr, red, NLs, NU, bS, bR);
-  double ls[4 * VEC], us[4 * VEC];
-  float mx = -FLT_MAX;
+  if (ge.slot == 0) {
+    double ls[4 * VEC], us[4 * VEC];
+    float mx = -FLT_MAX;
 #pragma unroll
-  for (int i = 0; i < 4 * VEC; ++i) {
-    range_of(bS[i], bR[i], e, NLs[i], NU[i], ls[i], us[i]);
-    if (colon[i / 4]) { bad |= !(finite_d(ls[i]) && finite_d(us[i])); mx = fmaxf(mx, (float)us[i]); }
+    for (int i = 0; i < 4 * VEC; ++i) {
+      range_of(bS[i], bR[i], e, NLs[i], NU[i], ls[i], us[i]);
+      if (colon[i / 4]) { bad |= !(finite_d(ls[i]) && finite_d(us[i])); mx = fmaxf(mx, (float)us[i]); }
+    }
+    const double shift = row_max(mx, ge.G);
+#pragma unroll
+    for (int i = 0; i < 4 * VEC; ++i) {
+      if (colon[i / 4]) {
+        const int col = 4 * (ge.g + ge.G * (i / 4)) + i % 4;
+        col_d(0, col) = ls[i] - shift; col_d(1, col) = us[i] - shift; col_d(2, col) = shift;
+      }
+    }
   }
-  const double shift = row_max(mx, ge.G);
+  __syncthreads();
   // exp relaxation per column on the shifted range (both slopes positive).  With the shift folded into
   // the intercepts:  S_e = hk S + dk R + hc [bias],  R_e = dk S + hk R + dc [bias]
   //   hk = (kL+kU)/2, dk = (kU-kL)/2, hc = (cL+cU)/2, dc = (cU-cL)/2
-  double kLe[4 * VEC], hk[4 * VEC], dk[4 * VEC], hc[4 * VEC], dc[4 * VEC], le[4 * VEC];
-  float hkf[4 * VEC], dkf[4 * VEC];
+  {
+    const int first = (blockIdx.x & 3) * kWave;          // the wave that owns the columns of this block
+    for (int col = ((int)threadIdx.x - first + kThreads) % kThreads; col < n; col += kThreads) {
+      const double l = col_d(0, col), u = col_d(1, col), shift = col_d(2, col);
+      const Line2 ex = relax_exp(l, u);
+      const double cL = ex.cL - ex.kL * shift, cU = ex.cU - ex.kU * shift;
+      col_d(0, col) = ex.kL;
+      col_d(1, col) = 0.5 * (ex.kL + ex.kU); col_d(2, col) = 0.5 * (ex.kU - ex.kL);
+      col_d(3, col) = 0.5 * (cL + cU); col_d(4, col) = 0.5 * (cU - cL);
+      col_d(5, col) = ex.kL * l + ex.cL;
+    }
+  }
+  __syncthreads();
+  float hkf[4 * VEC], dkf[4 * VEC], lef[4 * VEC];
 #pragma unroll
   for (int i = 0; i < 4 * VEC; ++i) {
+    const int col = 4 * (ge.g + ge.G * (i / 4)) + i % 4;
     const bool on = colon[i / 4];
-    const Line2 ex = relax_exp(on ? ls[i] - shift : 0.0, on ? us[i] - shift : 0.0);
-    const double cL = ex.cL - ex.kL * shift, cU = ex.cU - ex.kU * shift;
-    kLe[i] = on ? ex.kL : 0.0;
-    hk[i] = on ? 0.5 * (ex.kL + ex.kU) : 0.0; dk[i] = on ? 0.5 * (ex.kU - ex.kL) : 0.0;
-    hc[i] = on ? 0.5 * (cL + cU) : 0.0; dc[i] = on ? 0.5 * (cU - cL) : 0.0;
-    le[i] = on ? ex.kL * (ls[i] - shift) + ex.cL : 0.0;
-    hkf[i] = (float)hk[i]; dkf[i] = (float)dk[i];
+    hkf[i] = on ? (float)col_d(1, col) : 0.f; dkf[i] = on ? (float)col_d(2, col) : 0.f;
+    lef[i] = on ? (float)col_d(5, col) : 0.f;
   }
   // e's planes for one coefficient row and sigma's planes
   auto e_row = [&](const float (&xs)[4 * VEC], const float (&xr)[4 * VEC], float (&eS)[4 * VEC], float (&eR)[4 * VEC],
@@ -879,21 +903,26 @@ __global__ __launch_bounds__(kThreads) void softmax_kernel(float *S, float *R, i
     }
     sgS = row_sum<float>(a, ge.G); sgR = row_sum<float>(b, ge.G);
   };
-  // the bias row in double
-  double eSb[4 * VEC], eRb[4 * VEC], sgSb, sgRb;
-  {
+  // the bias row in double (row slot 0)
+  double kLe[4 * VEC], le[4 * VEC], eSb[4 * VEC], eRb[4 * VEC], sgSb = 0.0, sgRb = 0.0;
+  if (ge.slot == 0) {
     double a = 0.0, b = 0.0;
 #pragma unroll
     for (int i = 0; i < 4 * VEC; ++i) {
-      eSb[i] = hk[i] * bS[i] + dk[i] * bR[i] + hc[i];
-      eRb[i] = dk[i] * bS[i] + hk[i] * bR[i] + dc[i];
+      const int col = 4 * (ge.g + ge.G * (i / 4)) + i % 4;
+      const bool on = colon[i / 4];
+      const double hk = on ? col_d(1, col) : 0.0, dk = on ? col_d(2, col) : 0.0;
+      kLe[i] = on ? col_d(0, col) : 0.0; le[i] = on ? col_d(5, col) : 0.0;
+      eSb[i] = hk * bS[i] + dk * bR[i] + (on ? col_d(3, col) : 0.0);
+      eRb[i] = dk * bS[i] + hk * bR[i] + (on ? col_d(4, col) : 0.0);
       a += eSb[i]; b += eRb[i];
     }
     sgSb = row_sum<double>(a, ge.G); sgRb = row_sum<double>(b, ge.G);
   }
 
   // ---- sweep 2: concretize sigma
-  double lsg, usg;
+  Map2 mr;
+  Mul2 mc;
   {
     float NLg = 0.f, NUg = 0.f;
     for (int pb = 0; pb < P; ++pb) {
@@ -909,20 +938,30 @@ __global__ __launch_bounds__(kThreads) void softmax_kernel(float *S, float *R, i
       slot_reduce<2>(acc, ge, pn == 1, red);
       NLg += norm_fin(acc[0], pn); NUg += norm_fin(acc[1], pn);
     }
-    range_of(sgSb, sgRb, e, NLg, NUg, lsg, usg);
+    if (ge.slot == 0) {
+      double lsg, usg;
+      range_of(sgSb, sgRb, e, NLg, NUg, lsg, usg);
+      bad |= !(finite_d(lsg) && finite_d(usg)) || !(lsg >= kRecipMin);
+      const Line2 rcp = relax_recip(lsg, usg);
+      double lr, ur;
+      line_range(rcp, lsg, usg, lr, ur);
+      mr = form_map(form_sub(form_identity(), rcp));      // rho relative to sigma
+      mc = mul_coeffs(lr, ur);
+      if (bad) status[sent] = 1;
+      if (ge.g == 0) {
+        tokf[0] = mr.sS; tokf[1] = mr.sR; tokf[2] = mr.rS; tokf[3] = mr.rR;
+        tokf[4] = mc.a1; tokf[5] = mc.a2; tokf[6] = mc.a3; tokf[7] = mc.a4;
+      }
+    }
   }
-  bad |= !(finite_d(lsg) && finite_d(usg)) || !(lsg >= kRecipMin);
-  const Line2 rcp = relax_recip(lsg, usg);
-  double lr, ur;
-  line_range(rcp, lsg, usg, lr, ur);
-  const Map2 mr = form_map(form_sub(form_identity(), rcp));      // rho relative to sigma
-  const Mul2 mc = mul_coeffs(lr, ur);
-  if (bad) status[sent] = 1;
+  __syncthreads();
+  const float m_sS = tokf[0], m_sR = tokf[1], m_rS = tokf[2], m_rR = tokf[3];
+  const float c_a1 = tokf[4], c_a2 = tokf[5], c_a3 = tokf[6], c_a4 = tokf[7];
 
   // ---- sweep 3: p = e * rho (x = e_j with multiplier range of rho; y = rho with multiplier le_j)
-  float lef[4 * VEC], NLp[4 * VEC];
+  float NLp[4 * VEC];
 #pragma unroll
-  for (int i = 0; i < 4 * VEC; ++i) { lef[i] = (float)le[i]; NLp[i] = 0.f; }
+  for (int i = 0; i < 4 * VEC; ++i) NLp[i] = 0.f;
   for (int pb = 0; pb < P; ++pb) {
     float acc[4 * VEC];
 #pragma unroll
@@ -932,11 +971,11 @@ __global__ __launch_bounds__(kThreads) void softmax_kernel(float *S, float *R, i
       load_row<VEC>(S, R, lc, r, ge, xs, xr);
       float sgS, sgR;
       e_row(xs, xr, eS, eR, sgS, sgR);
-      const float rhoS = mr.sS * sgS + mr.sR * sgR, rhoR = mr.rS * sgS + mr.rR * sgR;
+      const float rhoS = m_sS * sgS + m_sR * sgR, rhoR = m_rS * sgS + m_rR * sgR;
 #pragma unroll
       for (int i = 0; i < 4 * VEC; ++i) {
-        ps[i] = mc.a1 * eS[i] + mc.a2 * eR[i] + lef[i] * rhoS;
-        pr[i] = mc.a3 * eS[i] + mc.a4 * eR[i] + fabsf(lef[i]) * rhoR;
+        ps[i] = c_a1 * eS[i] + c_a2 * eR[i] + lef[i] * rhoS;
+        pr[i] = c_a3 * eS[i] + c_a4 * eR[i] + fabsf(lef[i]) * rhoR;
         acc[i] = norm_acc(acc[i], ps[i] - pr[i], pn);
       }
       store_row<VEC>(S, R, lc, r, ge, ps, pr);
@@ -1146,8 +1185,8 @@ int softmax(State s, int groups, int P, int E, int T, int n, int gps, int pn, co
   ProfScope prof(K_SOFTMAX, st, 40.0 * rows * C * n, 16.0 * rows * C * n);
   dim3 grid((unsigned)(groups * T)), block(kThreads);
 #define SM_LAUNCH2(V, PN)                                                                                    \
-  hipLaunchKernelGGL((softmax_kernel<V, PN>), grid, block, 0, st, s.S, s.R, P, E, T, n, G, gps, eps, lp, slack, \
-                     status)
+  hipLaunchKernelGGL((softmax_kernel<V, PN>), grid, block, 6 * (size_t)n * sizeof(double), st, s.S, s.R, P, E, T, n, \
+                     G, gps, eps, lp, slack, status)
 #define SM_LAUNCH(PN)                 \
   switch (VEC) {                      \
     case 1: SM_LAUNCH2(1, PN); break; \
