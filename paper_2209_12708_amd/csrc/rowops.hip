@@ -452,8 +452,9 @@ __global__ __launch_bounds__(kThreads) void activation_cached_kernel(const float
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const double sb = bS[i], rb = bR[i];
-      ys[i] = (float)(maps[i].sSd * sb + maps[i].sRd * rb + maps[i].sCd);
-      yr[i] = (float)fmax(maps[i].rSd * sb + maps[i].rRd * rb + maps[i].rCd, 0.0);
+      const Map2 &md = smap[4 * ge.g + i];     // the double-precision part is read here only: 48 registers less
+      ys[i] = (float)(md.sSd * sb + md.sRd * rb + md.sCd);
+      yr[i] = (float)fmax(md.rSd * sb + md.rRd * rb + md.rCd, 0.0);
     }
     store_row<1>(So, Ro, lc, nrows, ge, ys, yr);
   }
@@ -661,7 +662,8 @@ __global__ __launch_bounds__(kThreads) void layernorm_kernel(const float *S, con
 // float4 per lane): the token's block is read once, all loads in flight together, and kept centred in
 // registers for the three sweeps.
 template <int ROWS, int NT, int PN>
-__global__ __launch_bounds__(NT) void layernorm_cached_kernel(const float *S, const float *R, int nrows, int T_,
+__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2)))
+void layernorm_cached_kernel(const float *S, const float *R, int nrows, int T_,
                                                                     int n, int G, int gps, const float *eps,
                                                                     const float *gamma, const float *beta,
                                                                     float ln_eps_f, float *So, float *Ro,
@@ -700,9 +702,10 @@ __global__ __launch_bounds__(NT) void layernorm_cached_kernel(const float *S, co
   // LDS: the other waves of the workgroup do not issue that code at all.
   __shared__ float colf[2][4 * kWave];      // slope of the square relaxation, lower bound of c, per column
   __shared__ float tokf[8];                 // rho's map and the product coefficients, per token
+  // Row slot 0 keeps its double-precision column values (range and centred bias of c, the norm of c's lower
+  // line) in LDS between the sweeps: held in registers they would cost the second workgroup per CU.
+  __shared__ double park[5][4 * kWave];
   // ---- sweep 1: range of c, slope of the square relaxation
-  double cl[4], cu[4], csb[4], crb[4];      // slot 0 only
-  float NLc[4];
   {
     float acc[8];
 #pragma unroll
@@ -720,16 +723,20 @@ __global__ __launch_bounds__(NT) void layernorm_cached_kernel(const float *S, co
     slot_reduce<8, NW>(acc, ge, pn == 1, red);
     if (ge.slot == 0) {
       float xs[4], xr[4];
+      double cl[4], cu[4], csb[4], crb[4];
       load_row<1>(S, R, lc, C - 1, ge, xs, xr);
       ln_centre<1, double>(xs, xr, n, ge, csb, crb);
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        NLc[i] = norm_fin(acc[2 * i], pn);
-        range_of(csb[i], crb[i], e, NLc[i], norm_fin(acc[2 * i + 1], pn), cl[i], cu[i]);
+        const float NLc = norm_fin(acc[2 * i], pn);
+        range_of(csb[i], crb[i], e, NLc, norm_fin(acc[2 * i + 1], pn), cl[i], cu[i]);
         if (colon) bad |= !(finite_d(cl[i]) && finite_d(cu[i]));
         else { cl[i] = cu[i] = 0.0; csb[i] = crb[i] = 0.0; }
         colf[0][4 * ge.g + i] = (float)(cl[i] + cu[i]);
         colf[1][4 * ge.g + i] = (float)cl[i];
+        park[0][4 * ge.g + i] = cl[i]; park[1][4 * ge.g + i] = cu[i];
+        park[2][4 * ge.g + i] = csb[i]; park[3][4 * ge.g + i] = crb[i];
+        park[4][4 * ge.g + i] = (double)NLc;
       }
     }
   }
@@ -738,7 +745,8 @@ __global__ __launch_bounds__(NT) void layernorm_cached_kernel(const float *S, co
 #pragma unroll
   for (int i = 0; i < 4; ++i) { kq[i] = colf[0][4 * ge.g + i]; lcf[i] = colf[1][4 * ge.g + i]; }
   // ---- sweep 2: v = mean_d q + ln_eps, one value per coefficient row
-  float vS[ROWS], vR[ROWS];
+  // v's planes per coefficient row stay in LDS until the output sweep (one value per row slot and row)
+  __shared__ float vrow[2][ROWS][NT / 4];
   double vSb = 0.0, vRb = 0.0;
   Map2 mr;
   Mul2 mc;
@@ -750,10 +758,10 @@ __global__ __launch_bounds__(NT) void layernorm_cached_kernel(const float *S, co
         float a = 0.f, b = 0.f;
 #pragma unroll
         for (int i = 0; i < 4; ++i) { a += kq[i] * cs[it][i]; b += fabsf(kq[i]) * cr[it][i]; }
-        vS[it] = row_sum<float>(a, ge.G) * inv;
-        vR[it] = row_sum<float>(b, ge.G) * inv;
-        acc[0] = norm_acc(acc[0], vS[it] - vR[it], pn);
-        acc[1] = norm_acc(acc[1], vS[it] + vR[it], pn);
+        const float vS = row_sum<float>(a, ge.G) * inv, vR = row_sum<float>(b, ge.G) * inv;
+        if (ge.g == 0) { vrow[0][it][ge.slot] = vS; vrow[1][it][ge.slot] = vR; }
+        acc[0] = norm_acc(acc[0], vS - vR, pn);
+        acc[1] = norm_acc(acc[1], vS + vR, pn);
       }
     }
     slot_reduce<2, NW>(acc, ge, pn == 1, red);
@@ -761,9 +769,10 @@ __global__ __launch_bounds__(NT) void layernorm_cached_kernel(const float *S, co
       double a = 0.0, b = 0.0;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const double k = cl[i] + cu[i], m = 0.5 * k, w = cu[i] - cl[i];
-        a += k * csb[i] - 0.5 * (m * m + cl[i] * cu[i]);
-        b += fabs(k) * crb[i] + 0.125 * w * w;
+        const double cl = park[0][4 * ge.g + i], cu = park[1][4 * ge.g + i];
+        const double k = cl + cu, m = 0.5 * k, w = cu - cl;
+        a += k * park[2][4 * ge.g + i] - 0.5 * (m * m + cl * cu);
+        b += fabs(k) * park[3][4 * ge.g + i] + 0.125 * w * w;
       }
       vSb = row_sum<double>(a, ge.G) / (double)n + ln_eps;
       vRb = row_sum<double>(b, ge.G) / (double)n;
@@ -794,7 +803,8 @@ __global__ __launch_bounds__(NT) void layernorm_cached_kernel(const float *S, co
   for (int it = 0; it < ROWS; ++it) {
     const int r = ge.slot + it * ge.NS;
     if (r < nrows) {
-      const float rhoS = m_sS * vS[it] + m_sR * vR[it], rhoR = m_rS * vS[it] + m_rR * vR[it];
+      const float vS = vrow[0][it][ge.slot], vR = vrow[1][it][ge.slot];
+      const float rhoS = m_sS * vS + m_sR * vR, rhoR = m_rS * vS + m_rR * vR;
       float ys[4], yr[4];
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
@@ -810,9 +820,10 @@ __global__ __launch_bounds__(NT) void layernorm_cached_kernel(const float *S, co
     float ys[4], yr[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const double slack = crb[i] + e * (double)NLc[i];        // S_c_b - l_c without cancellation
-      const double yS = mc.a1d * csb[i] + mc.a2d * crb[i] + cl[i] * rhoS - cl[i] * mc.a1d;
-      const double yR = mc.a3d * slack + mc.a4d * crb[i] + fabs(cl[i]) * rhoR;
+      const double cl = park[0][4 * ge.g + i], csb = park[2][4 * ge.g + i], crb = park[3][4 * ge.g + i];
+      const double slack = crb + e * park[4][4 * ge.g + i];    // S_c_b - l_c without cancellation
+      const double yS = mc.a1d * csb + mc.a2d * crb + cl * rhoS - cl * mc.a1d;
+      const double yR = mc.a3d * slack + mc.a4d * crb + fabs(cl) * rhoR;
       ys[i] = (float)((double)gm[i] * yS + (double)bt[i]);
       yr[i] = (float)fmax(fabs((double)gm[i]) * yR, 0.0);
     }
@@ -1136,11 +1147,12 @@ int layernorm(CState x, int groups, int P, int E, int T, int n, int gps, int pn,
   const double C = (double)P * E + 1, rows = (double)groups * T;
   ProfScope prof(K_LAYERNORM, st, 40.0 * rows * C * n, 16.0 * rows * C * n);
   dim3 grid((unsigned)(groups * T)), block(kThreads);
-  // small blocks: the token's block fits the register file of one workgroup (at most 8 rows per thread) and is
-  // read once.  512 threads halve the rows per thread where 256 would need more than 8.
+  // small blocks: the token's block fits the register file of one workgroup (at most 16 rows per thread) and is
+  // read once.  Four waves with 16 rows each leave room for a second workgroup on the CU, whose loads and stores
+  // overlap the first one's scalar sections; eight waves with 8 rows each fill the register file with one.
   const int crows = P * E;
-  const int per256 = (crows + kThreads / G - 1) / (kThreads / G), per512 = (crows + 512 / G - 1) / (512 / G);
-  if (P <= 1 && VEC == 1 && per512 <= 8) {
+  const int per256 = (crows + kThreads / G - 1) / (kThreads / G);
+  if (P <= 1 && VEC == 1 && per256 <= 16) {
 #define LNC_LAUNCH(PN)                                                                                           \
   do {                                                                                                           \
     if (per256 <= 4)                                                                                             \
@@ -1150,7 +1162,7 @@ int layernorm(CState x, int groups, int P, int E, int T, int n, int gps, int pn,
       hipLaunchKernelGGL((layernorm_cached_kernel<8, 256, PN>), grid, dim3(256), 0, st, x.S, x.R, crows, T, n, G, gps, \
                          eps, gamma, beta, ln_eps, y.S, y.R, status);                                            \
     else                                                                                                         \
-      hipLaunchKernelGGL((layernorm_cached_kernel<8, 512, PN>), grid, dim3(512), 0, st, x.S, x.R, crows, T, n, G, gps, \
+      hipLaunchKernelGGL((layernorm_cached_kernel<16, 256, PN>), grid, dim3(256), 0, st, x.S, x.R, crows, T, n, G, gps, \
                          eps, gamma, beta, ln_eps, y.S, y.R, status);                                            \
   } while (0)
     NORM_SWITCH(pn, LNC_LAUNCH);
