@@ -847,6 +847,7 @@ __global__ __launch_bounds__(kThreads) void softmax_kernel(float *S, float *R, i
   __shared__ float red[4 * kWave * 8 * VEC];
   extern __shared__ double col_dyn[];                    // [6][n]  in: l, u (shifted), shift; out: kL, hk, dk, hc, dc, le
   __shared__ float tokf[8];
+  __shared__ double tokd[6];                             // rho's map and the product coefficients in double, for the bias row
   auto col_d = [&](int k, int col) -> double & { return col_dyn[k * n + col]; };
   const int C = P * E + 1;
   const Geo ge(G, n / 4);
@@ -914,26 +915,25 @@ __global__ __launch_bounds__(kThreads) void softmax_kernel(float *S, float *R, i
     }
     sgS = row_sum<float>(a, ge.G); sgR = row_sum<float>(b, ge.G);
   };
-  // the bias row in double (row slot 0)
-  double kLe[4 * VEC], le[4 * VEC], eSb[4 * VEC], eRb[4 * VEC], sgSb = 0.0, sgRb = 0.0;
+  // the bias row in double (row slot 0); e's bias values replace the intercepts in LDS until the last sweep
+  double sgSb = 0.0, sgRb = 0.0;
   if (ge.slot == 0) {
     double a = 0.0, b = 0.0;
 #pragma unroll
     for (int i = 0; i < 4 * VEC; ++i) {
       const int col = 4 * (ge.g + ge.G * (i / 4)) + i % 4;
-      const bool on = colon[i / 4];
-      const double hk = on ? col_d(1, col) : 0.0, dk = on ? col_d(2, col) : 0.0;
-      kLe[i] = on ? col_d(0, col) : 0.0; le[i] = on ? col_d(5, col) : 0.0;
-      eSb[i] = hk * bS[i] + dk * bR[i] + (on ? col_d(3, col) : 0.0);
-      eRb[i] = dk * bS[i] + hk * bR[i] + (on ? col_d(4, col) : 0.0);
-      a += eSb[i]; b += eRb[i];
+      if (colon[i / 4]) {
+        const double hk = col_d(1, col), dk = col_d(2, col);
+        const double eSb = hk * bS[i] + dk * bR[i] + col_d(3, col);
+        const double eRb = dk * bS[i] + hk * bR[i] + col_d(4, col);
+        col_d(3, col) = eSb; col_d(4, col) = eRb;
+        a += eSb; b += eRb;
+      }
     }
     sgSb = row_sum<double>(a, ge.G); sgRb = row_sum<double>(b, ge.G);
   }
 
   // ---- sweep 2: concretize sigma
-  Map2 mr;
-  Mul2 mc;
   {
     float NLg = 0.f, NUg = 0.f;
     for (int pb = 0; pb < P; ++pb) {
@@ -956,12 +956,15 @@ __global__ __launch_bounds__(kThreads) void softmax_kernel(float *S, float *R, i
       const Line2 rcp = relax_recip(lsg, usg);
       double lr, ur;
       line_range(rcp, lsg, usg, lr, ur);
-      mr = form_map(form_sub(form_identity(), rcp));      // rho relative to sigma
-      mc = mul_coeffs(lr, ur);
+      const Map2 mr = form_map(form_sub(form_identity(), rcp));      // rho relative to sigma
+      const Mul2 mc = mul_coeffs(lr, ur);
       if (bad) status[sent] = 1;
       if (ge.g == 0) {
         tokf[0] = mr.sS; tokf[1] = mr.sR; tokf[2] = mr.rS; tokf[3] = mr.rR;
         tokf[4] = mc.a1; tokf[5] = mc.a2; tokf[6] = mc.a3; tokf[7] = mc.a4;
+        tokd[0] = mr.sSd * sgSb + mr.sRd * sgRb + mr.sCd;             // rho's bias values
+        tokd[1] = mr.rSd * sgSb + mr.rRd * sgRb + mr.rCd;
+        tokd[2] = mc.a1d; tokd[3] = mc.a2d; tokd[4] = mc.a3d; tokd[5] = mc.a4d;
       }
     }
   }
@@ -996,13 +999,18 @@ __global__ __launch_bounds__(kThreads) void softmax_kernel(float *S, float *R, i
     for (int i = 0; i < 4 * VEC; ++i) NLp[i] += norm_fin(acc[i], pn);
   }
   if (ge.slot == 0) {   // bias row, in double; concretized lower bound of p and its slack
-    const double rhoS = mr.sSd * sgSb + mr.sRd * sgRb + mr.sCd, rhoR = mr.rSd * sgSb + mr.rRd * sgRb + mr.rCd;
+    const double rhoS = tokd[0], rhoR = tokd[1];
+    const double a1d = tokd[2], a2d = tokd[3], a3d = tokd[4], a4d = tokd[5];
     float ps[4 * VEC], pr[4 * VEC], lpv[4 * VEC], slv[4 * VEC];
 #pragma unroll
     for (int i = 0; i < 4 * VEC; ++i) {
-      const double slack_e = eRb[i] + e * kLe[i] * (double)NLs[i];     // e_S_b - le without cancellation
-      const double pS = mc.a1d * eSb[i] + mc.a2d * eRb[i] + le[i] * rhoS - le[i] * mc.a1d;
-      const double pR = mc.a3d * slack_e + mc.a4d * eRb[i] + fabs(le[i]) * rhoR;
+      const int col = 4 * (ge.g + ge.G * (i / 4)) + i % 4;
+      const bool on = colon[i / 4];
+      const double kLe = on ? col_d(0, col) : 0.0, le = on ? col_d(5, col) : 0.0;
+      const double eSb = on ? col_d(3, col) : 0.0, eRb = on ? col_d(4, col) : 0.0;
+      const double slack_e = eRb + e * kLe * (double)NLs[i];           // e_S_b - le without cancellation
+      const double pS = a1d * eSb + a2d * eRb + le * rhoS - le * a1d;
+      const double pR = a3d * slack_e + a4d * eRb + fabs(le) * rhoR;
       const double half = pR + e * (double)NLp[i];                     // S_p_b - (lower bound of p)
       const double lraw = pS - half;
       const double lcl = fmin(fmax(lraw, 0.0), 1.0);
