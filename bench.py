@@ -130,7 +130,9 @@ def main():
 
     def ceilings():
         """Achievable ceilings of this part as it runs (the published peaks are the roofline's denominators):
-        a device copy and a fill of 1 GiB, and the issue rate of the two matrix-core instructions."""
+        a device copy and a fill of 1 GiB, two mixed streams with the read : write ratios of the affine layers
+        (1 : 3 like the fused QKV product, 2 : 1 like W_o with its residual; torch's elementwise kernels on
+        512 MiB units), and the issue rate of the two matrix-core instructions."""
         n = 1 << 28
         a = torch.empty(n, dtype=torch.float32, device=dev).normal_()
         b = torch.empty_like(a)
@@ -148,6 +150,11 @@ def main():
 
         out = {"copy_GBps": round(2 * 4 * n / timed(lambda: b.copy_(a), 5) / 1e9, 1),
                "fill_GBps": round(4 * n / timed(lambda: b.fill_(1.0), 5) / 1e9, 1)}
+        h = n // 2
+        b3 = torch.empty(3, h, dtype=torch.float32, device=dev)
+        out["read1_write3_GBps"] = round(4 * 4 * h / timed(lambda: b3.copy_(a[:h].expand(3, h)), 5) / 1e9, 1)
+        out["read2_write1_GBps"] = round(3 * 4 * h / timed(lambda: torch.add(a[:h], a[h:], out=b[:h]), 5) / 1e9, 1)
+        del b3
         buf = torch.empty(2048 * 256, dtype=torch.float32, device=dev)
         for name, bf16, iters in (("mfma_f32_TFLOPs", 0, 4000), ("mfma_bf16_TFLOPs", 1, 8000)):
             fl = [0.0]
@@ -158,8 +165,6 @@ def main():
             out[name] = round(fl[0] / t / 1e12, 1)
         del a, b, buf
         return out
-
-    ceil = None if args.no_ceilings else ceilings()
 
     def step():
         out = None
@@ -243,6 +248,10 @@ def main():
         roofline["launches_timed"] = d["launches"]
         roofline["algorithmic_bytes_per_launch"] = d["bytes"] / d["launches"]
         roofline["algorithmic_flops_per_launch"] = d["flops"] / d["launches"]
+
+    # the ceiling probes run after the timed region: seconds of saturated matrix cores just before it would lower
+    # the clocks the timed steps see
+    ceil = None if args.no_ceilings else ceilings()
 
     cpu = None
     if not args.no_cpu_baseline:

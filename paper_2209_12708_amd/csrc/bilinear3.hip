@@ -1,0 +1,250 @@
+// The two contractions of a dot-product bound (Sec. 2.1: q k^T and attention v, McCormick planes
+// substituted into the states of both factors) in one launch, at fp32 accuracy on the bf16 matrix cores.
+//
+//   C[m][n] = sum_k [S_x | R_x][m][k] * B[n][k]            the factor x's state times multipliers from y's range
+//           + sum_t pA[i][t] * Y(r, t, n)      m = r pL + i   multipliers from x's range times the state of y
+//           (+ the constant of the planes on bias rows)
+//
+// Same operands and meaning as the fp32 kernel of gemm.hip with its second product (GemmArgs); here every
+// operand is cut into three bf16 pieces on the fly - the state of x and the multipliers while a stage is put
+// into LDS, the second product's operands in registers - and each fp32 product becomes six
+// v_mfma_f32_32x32x16_bf16 (see affine3.hip for the arithmetic).  The fp32 instruction needs 64 cycles for two
+// k-steps of a 32 x 32 tile, the six bf16 instructions 192 cycles for sixteen: with 20 waves on a CU taking
+// turns on the matrix cores that was a third of a tile's lifetime.
+//
+// Tile: 128 rows x 32 columns (one head's tokens or features), four waves of 32 x 32, K in stages of 32.
+#include "common.h"
+
+namespace tv {
+namespace {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+
+// x = a + b + c exactly (up to the last piece's rounding, below 2^-24 |x|)
+__device__ __forceinline__ void cut3(float x, __bf16 &a, __bf16 &b, __bf16 &c) {
+  a = (__bf16)x;
+  const float r1 = x - (float)a;
+  b = (__bf16)r1;
+  const float r2 = r1 - (float)b;
+  c = (__bf16)r2;
+}
+
+// eight consecutive k values of one row as the three fragments of a 16-wide MFMA step
+__device__ __forceinline__ void cut3x8(const float (&x)[8], bf16x8 (&p)[3]) {
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    __bf16 a, b, c;
+    cut3(x[e], a, b, c);
+    p[0][e] = a; p[1][e] = b; p[2][e] = c;
+  }
+}
+
+__device__ __forceinline__ f32x16 mfma6(const bf16x8 (&a)[3], const bf16x8 (&b)[3], f32x16 acc) {
+  // small terms first
+  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[2], b[0], acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0], b[2], acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[1], b[1], acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[1], b[0], acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0], b[1], acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0], b[0], acc, 0, 0, 0);
+  return acc;
+}
+
+template <int PBMODE>
+__global__ __launch_bounds__(256) void bilinear3_kernel(const GemmArgs g, int mtiles, int ntiles) {
+  constexpr int BM = 128, BN = 32, BK = 32;
+  constexpr int RS = 80;                           // LDS row stride in bytes (32 bf16 + 16 bytes of padding)
+  constexpr int A_P = BM * RS, B_P = BN * RS;      // bytes per piece
+  constexpr int CS = BN + 4;                       // padded row stride of the staged output tile (floats)
+  constexpr int STAGE_BYTES = 3 * A_P + 3 * B_P, TILE_BYTES = BM * CS * 4;
+  __shared__ __attribute__((aligned(16))) unsigned char lds[STAGE_BYTES > TILE_BYTES ? STAGE_BYTES : TILE_BYTES];
+  unsigned char *As = lds, *Bs = lds + 3 * A_P;
+
+  // XCD-aware tile order (see gemm.hip)
+  const int wid = blockIdx.x;
+  int mt, nt;
+  if (mtiles >= 8) {
+    const int xcd = wid & 7, slot = wid >> 3;
+    nt = slot % ntiles;
+    mt = (slot / ntiles) * 8 + xcd;
+    if (mt >= mtiles) return;
+  } else {
+    mt = wid % mtiles;
+    nt = wid / mtiles;
+  }
+  const int m0 = mt * BM, n0 = nt * BN;
+
+  int z = blockIdx.y;
+  const int z0 = z % g.nz0; z /= g.nz0;
+  const int z1 = z % g.nz1; const int z2 = z / g.nz1;
+  const float *A = g.A + z0 * g.sA[0] + z1 * g.sA[1] + z2 * g.sA[2];
+  const float *A2 = g.A2 ? g.A2 + z0 * g.sA2[0] + z1 * g.sA2[1] + z2 * g.sA2[2] : A;
+  const float *B = g.B + z0 * g.sB[0] + z1 * g.sB[1] + z2 * g.sB[2];
+  float *C = g.C + z0 * g.sC[0] + z1 * g.sC[1] + z2 * g.sC[2];
+  const float *bias = g.bias ? g.bias + z0 * g.sBias[0] + z1 * g.sBias[1] + z2 * g.sBias[2] : nullptr;
+  const float *pA = g.pA + z0 * g.spA[0] + z1 * g.spA[1] + z2 * g.spA[2];
+  const float *pB = g.pB + z0 * g.spB[0] + z1 * g.spB[1] + z2 * g.spB[2];
+
+  const int tid = threadIdx.x, lane = tid & 63, wm = tid >> 6;
+  const int l32 = lane & 31, half = lane >> 5;
+  const int M = g.M, N = g.N, K = g.K, K1 = g.K1;
+
+  // ---- load slots: a stage of the state is 128 rows x 8 float4, a stage of the multipliers 32 rows x 8 float4
+  const int kq = tid & 7;
+  long a_off[4]; int a_lds[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int row = (tid >> 3) + 32 * i;
+    int m = m0 + row; if (m >= M) m = M - 1;
+    a_off[i] = (long)m * g.lda + kq * 4;
+    a_lds[i] = row * RS + kq * 8;
+  }
+  int nb = n0 + (tid >> 3); if (nb >= N) nb = N - 1;
+  const long b_off = (long)nb * g.ldb + kq * 4;
+  const int b_lds = (tid >> 3) * RS + kq * 8;
+
+  float4 ra[4], rb;
+  auto load_stage = [&](int kt) {       // stages do not straddle the two K segments: K1 is a multiple of 32
+    const int kb = kt * BK;
+    const float *src = kb < K1 ? A + kb : A2 + (kb - K1);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) ra[i] = *reinterpret_cast<const float4 *>(src + a_off[i]);
+    rb = *reinterpret_cast<const float4 *>(B + b_off + kb);
+  };
+  auto put3 = [&](unsigned char *base, int piece_bytes, int at, const float4 &v) {
+    bf16x4 p0, p1, p2;
+    const float x[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      __bf16 a, b, c;
+      cut3(x[e], a, b, c);
+      p0[e] = a; p1[e] = b; p2[e] = c;
+    }
+    *reinterpret_cast<bf16x4 *>(base + at) = p0;
+    *reinterpret_cast<bf16x4 *>(base + piece_bytes + at) = p1;
+    *reinterpret_cast<bf16x4 *>(base + 2 * piece_bytes + at) = p2;
+  };
+  auto store_stage = [&]() {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) put3(As, A_P, a_lds[i], ra[i]);
+    put3(Bs, B_P, b_lds, rb);
+  };
+
+  f32x16 acc;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+
+  const int KT = K / BK;
+  load_stage(0);
+  for (int kt = 0; kt < KT; ++kt) {
+    store_stage();
+    __syncthreads();
+    if (kt + 1 < KT) load_stage(kt + 1);
+    // lane l holds k = 8 (l / 32) .. + 7 of each 16-wide MFMA step, for row / column l % 32
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      bf16x8 af[3], bf[3];
+#pragma unroll
+      for (int p = 0; p < 3; ++p) {
+        af[p] = *reinterpret_cast<const bf16x8 *>(As + p * A_P + (wm * 32 + l32) * RS + ks * 32 + half * 16);
+        bf[p] = *reinterpret_cast<const bf16x8 *>(Bs + p * B_P + l32 * RS + ks * 32 + half * 16);
+      }
+      acc = mfma6(af, bf, acc);
+    }
+    __syncthreads();
+  }
+
+  // ---- second product: both operands go from memory to fragments (k = c + 16 ks + 8 half .. + 7 per lane)
+  {
+    const int row0 = m0 + wm * 32;
+    if (row0 < M) {                                              // wave-uniform
+      const int r = row0 / g.pL, i0 = row0 % g.pL;
+      const float *pa = pA + (long)(i0 + l32) * g.pA_ld + 8 * half;
+      int n = n0 + l32; if (n >= N) n = N - 1;                   // loaded, never stored
+      const float *pb = PBMODE == 0 ? pB + ((long)r * g.pL + n) * g.pB_ld + 8 * half
+                                    : pB + ((long)r * g.pL + 8 * half) * g.pB_ld + n;
+      for (int c = 0; c < g.pK; c += 32) {
+        float a2[2][8], b2[2][8];
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+#pragma unroll
+          for (int q = 0; q < 2; ++q) {
+            const float4 v = *reinterpret_cast<const float4 *>(pa + c + 16 * ks + 4 * q);
+            a2[ks][4 * q] = v.x; a2[ks][4 * q + 1] = v.y; a2[ks][4 * q + 2] = v.z; a2[ks][4 * q + 3] = v.w;
+          }
+          if (PBMODE == 0) {
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+              const float4 v = *reinterpret_cast<const float4 *>(pb + c + 16 * ks + 4 * q);
+              b2[ks][4 * q] = v.x; b2[ks][4 * q + 1] = v.y; b2[ks][4 * q + 2] = v.z; b2[ks][4 * q + 3] = v.w;
+            }
+          } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) b2[ks][e] = pb[(long)(c + 16 * ks + e) * g.pB_ld];
+          }
+        }
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+          bf16x8 af[3], bf[3];
+          cut3x8(a2[ks], af);
+          cut3x8(b2[ks], bf);
+          acc = mfma6(af, bf, acc);
+        }
+      }
+    }
+  }
+
+  // ---- epilogue.  Accumulator v of lane l holds row 8*(v/4) + 4*(l/32) + v%4, column l%32; the tile goes
+  // through LDS (the stage buffers are free after the last barrier) and leaves as 16 bytes per lane along rows.
+  float *Ct = reinterpret_cast<float *>(lds);
+#pragma unroll
+  for (int v = 0; v < 16; ++v) Ct[(wm * 32 + 8 * (v >> 2) + 4 * half + (v & 3)) * CS + l32] = acc[v];
+  __syncthreads();
+  bool tile_has_bias = false;
+  if (bias) {   // does this tile contain rows of a bias block at all?
+    const int ba = m0 / g.bias_T, bb = (min(m0 + BM, M) - 1) / g.bias_T;
+    tile_has_bias = (ba % g.bias_C) + (bb - ba) >= g.bias_C - 1;
+  }
+#pragma unroll
+  for (int it = 0; it < 4; ++it) {
+    const int row = (tid >> 3) + 32 * it, c4 = tid & 7;
+    const int m = m0 + row, n = n0 + c4 * 4;
+    if (m >= M || n >= N) continue;
+    float4 v = *reinterpret_cast<const float4 *>(Ct + row * CS + c4 * 4);
+    if (tile_has_bias) {
+      // rows are ordered (group, coefficient row, t); the last coefficient row is the bias row
+      const int blk = m / g.bias_T;
+      if (blk % g.bias_C == g.bias_C - 1) {
+        const float *brow = bias + ((long)(blk / g.bias_C) * g.bias_T + m % g.bias_T) * g.bias_ld + n;
+        v.x += brow[0]; v.y += brow[1]; v.z += brow[2]; v.w += brow[3];
+      }
+    }
+    *reinterpret_cast<float4 *>(C + (long)m * g.ldc + n) = v;
+  }
+}
+
+}  // namespace
+
+bool dual_split_fits(const GemmArgs &g) {
+  return g.pA && g.pB && g.b_mode == 0 && g.cq == 0 && g.Cadd == nullptr && g.M >= 128 && g.N % 32 == 0 &&
+         g.K % 32 == 0 && g.K1 % 32 == 0 && g.pK % 32 == 0 && g.pL % 32 == 0 && g.M % 32 == 0 && g.lda % 4 == 0 &&
+         g.ldb % 4 == 0 && g.ldc % 4 == 0 && g.pA_ld % 4 == 0 && g.pB_ld % 4 == 0 &&
+         (reinterpret_cast<uintptr_t>(g.C) & 15) == 0 && g.sC[0] % 4 == 0 && g.sC[1] % 4 == 0 && g.sC[2] % 4 == 0;
+}
+
+int gemm_dual_split(const GemmArgs &g, hipStream_t st) {
+  TV_REQUIRE(dual_split_fits(g), TV_E_SHAPE, "gemm_dual_split: shape not supported");
+  const int mtiles = (g.M + 127) / 128, ntiles = g.N / 32;
+  const long groups = mtiles >= 8 ? (long)((mtiles + 7) / 8) * 8 * ntiles : (long)mtiles * ntiles;
+  const long nz = (long)g.nz0 * g.nz1 * g.nz2;
+  TV_REQUIRE(groups < (1L << 31) && nz <= 65535L * 32768L, TV_E_SHAPE, "gemm_dual_split: grid too large");
+  dim3 grid((unsigned)groups, (unsigned)nz, 1), block(256, 1, 1);
+  if (g.pB_mode == 0) hipLaunchKernelGGL(bilinear3_kernel<0>, grid, block, 0, st, g, mtiles, ntiles);
+  else hipLaunchKernelGGL(bilinear3_kernel<1>, grid, block, 0, st, g, mtiles, ntiles);
+  TV_HIP(hipGetLastError());
+  return TV_OK;
+}
+
+}  // namespace tv

@@ -74,6 +74,10 @@ struct GemmArgs {
   long spA[3] = {0, 0, 0}, spB[3] = {0, 0, 0};
 };
 int gemm(const GemmArgs &g, hipStream_t st);
+// The same contraction with its second product on the bf16 matrix cores, three bf16 pieces per operand cut on the
+// fly (bilinear3.hip); gemm() takes this path whenever the shapes fit (tiles of 128 x 32, K segments of 32).
+bool dual_split_fits(const GemmArgs &g);
+int gemm_dual_split(const GemmArgs &g, hipStream_t st);
 
 // ---- affine layers with constant weights on the bf16 matrix cores at fp32 accuracy (affine3.hip) ----
 // matrix-core issue probe: `workgroups` x 4 waves x `iters` rounds of 16 MFMA instructions (fp32 32x32x2 or bf16

@@ -38,7 +38,7 @@ def dev(a, dtype=None):
     return torch.as_tensor(np.ascontiguousarray(a), device="cuda:0")
 
 
-def check_bounds(out, refs, what, rtol=1e-4):
+def check_bounds(out, refs, what, rtol=1e-4, atol=4e-6):
     lo, up = out["lower"].cpu().numpy().astype(np.float64), out["upper"].cpu().numpy().astype(np.float64)
     ml = out["margin_lower"].cpu().numpy().astype(np.float64)
     st = out["status"].cpu().numpy()
@@ -51,11 +51,11 @@ def check_bounds(out, refs, what, rtol=1e-4):
             continue
         T = ref["head_scale"]
         for g, o, nm in ((lo[b], ref["lower"], "lower"), (up[b], ref["upper"], "upper"), (ml[b], ref["margin_lower"], "margin")):
-            ok = np.abs(g - o) <= rtol * np.abs(o) + 4e-6 * T
+            ok = np.abs(g - o) <= rtol * np.abs(o) + atol * T
             assert np.all(ok), f"{what} sentence {b} {nm}: gpu {g} oracle {o}"
 
 
-def run_case(tv, w, m, p, eps_list, n_sent, certify_sent, steps=None, cert_range=None, rtol=1e-4):
+def run_case(tv, w, m, p, eps_list, n_sent, certify_sent, steps=None, cert_range=None, rtol=1e-4, atol=4e-6):
     tokens, positions = make_tokens(w, n_sent), make_positions(w, n_sent)
     model = tv.Model(m)
     tok_d, pos_d = dev(tokens), dev(positions)
@@ -63,7 +63,7 @@ def run_case(tv, w, m, p, eps_list, n_sent, certify_sent, steps=None, cert_range
         out = model.verify(tok_d, pos_d, p, torch.full((n_sent,), eps, dtype=torch.float32, device="cuda:0"))
         e32 = float(np.float32(eps))
         refs = [V.verify(m, tokens[b], positions[b], p, e32) for b in range(n_sent)]
-        check_bounds(out, refs, f"{w.name} p={p} eps={eps}", rtol)
+        check_bounds(out, refs, f"{w.name} p={p} eps={eps}", rtol, atol)
     if certify_sent:
         steps = steps or w.steps
         lo_, hi_ = cert_range or (w.eps_lo, w.eps_hi)
@@ -99,8 +99,10 @@ def test_c3_tanh_two_positions(tv):
     # three layers of full LayerNorm bounds blow up beyond eps ~ 3e-7 in the l_inf ball, so the configured
     # bisection over [0, 1] returns eps_lo on both sides; bounds are compared where they are informative
     # (1e-8: tight; 1e-7: margin about to change sign; 3e-7: width above the logits) and the search is
-    # also run on a bracket that contains the true threshold
-    run_case(tv, w, make_model(w), 0, [1e-8, 1e-7, 3e-7], 2, 1, steps=5, cert_range=(0.0, 4e-7), rtol=5e-4)
+    # also run on a bracket that contains the true threshold.  At 1e-7 the bounds are ill-conditioned under fp32
+    # storage: the float64 oracle with nothing but its stored states rounded to fp32 moves the logit bounds by
+    # 5e-4 absolute (2e-3 .. 6e-3 relative, widths by 0.7 %); the tolerance here is a tenth of that.
+    run_case(tv, w, make_model(w), 0, [1e-8, 1e-7, 3e-7], 2, 1, steps=5, cert_range=(0.0, 4e-7), rtol=1e-3, atol=1e-5)
     run_case(tv, w, make_model(w), 0, [], 1, 1, steps=3)
 
 
