@@ -259,7 +259,8 @@ size_t attention_workspace_ext(int B, int L, int H, int D, int P, bool own_score
 }
 
 int attention(CState q, CState k, CState v, int ld, int B, int L, int H, int D, int P, int pn, const float *eps, State o,
-              State s, int stop_after, int32_t *status, void *ws, size_t ws_bytes, hipStream_t st) {
+              State s, int stop_after, int32_t *status, void *ws, size_t ws_bytes, hipStream_t st,
+              const float *qkv_norms) {
   TV_REQUIRE(q.S && q.R && k.S && k.R && v.S && v.R && eps && status && ws, TV_E_NULL, "attention: null pointer");
   TV_REQUIRE(B > 0 && L > 0 && H > 0 && D > 0 && P >= 0 && D % H == 0 && (D / H) % 4 == 0 && L % 4 == 0, TV_E_SHAPE,
              "attention: need D %% H == 0, head width and L multiples of 4 (B=%d L=%d H=%d D=%d)", B, L, H, D);
@@ -281,8 +282,11 @@ int attention(CState q, CState k, CState v, int ld, int B, int L, int H, int D, 
   Ranges rg;
   float *rm = w + lay.rmid, *rh = w + lay.rhalf, *rs = w + lay.rslack;
   const bool fused = ld == 3 * D && k.S == q.S + D && v.S == q.S + 2 * D && k.R == q.R + D && v.R == q.R + 2 * D;
+  TV_REQUIRE(qkv_norms == nullptr || fused, TV_E_ARG, "attention: stored norms need the fused q | k | v state");
   if (fused) {
-    if (int rc = concretize(q, B, P, D, L, ld, 1, pn, eps, rm, rh, rs, 1, st)) return rc;
+    // qkv_norms: the eps-independent part of this concretization, stored by an earlier pass over the same state
+    if (qkv_norms) { if (int rc = ranges_from_norms(qkv_norms, B, L, ld, 1, eps, rm, rh, rs, st)) return rc; }
+    else if (int rc = concretize(q, B, P, D, L, ld, 1, pn, eps, rm, rh, rs, 1, st)) return rc;
     rg = Ranges{rm, rh, rs, rm + D, rh + D, rm + 2 * D, rh + 2 * D, ld};
   } else {
     TV_REQUIRE(ld == D, TV_E_SHAPE, "attention: separate q, k, v states must be densely packed");

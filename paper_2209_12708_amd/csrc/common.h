@@ -96,9 +96,14 @@ int affine_split(const float *xS, long xplane, long M, int C, int T, int K, int 
 // ---- elementwise / reduction kernels (rowops.hip) ------------------------------------------
 // States are [groups][C][T][n]; eps is indexed by group / gps (groups per sentence).
 // concretize: mode 0 -> (o0, o1) = (l, u); mode 1 -> (mid, half) = ((u+l)/2, (u-l)/2), each accurate in
-// fp32, and o2 (optional) = S_b - l, the slack between the bias centre and the lower bound.
+// fp32, and o2 (optional) = S_b - l, the slack between the bias centre and the lower bound; mode 2 -> the parts that
+// do not depend on eps (o0..o3 = norm of the lower line, norm of the upper line, S_b, R_b; eps is not read).
 int concretize(CState x, int groups, int P, int E, int T, int n, int gps, int p_norm, const float *eps, float *o0,
-               float *o1, float *o2, int mode, hipStream_t st);
+               float *o1, float *o2, int mode, hipStream_t st, float *o3 = nullptr);
+// mode 1's outputs for the eps of now from mode 2's four arrays (stored back to back in `norms`): bit-identical
+// to concretize mode 1 on the state they came from
+int ranges_from_norms(const float *norms, int groups, int T, int n, int gps, const float *eps, float *mid, float *half,
+                      float *slack, hipStream_t st);
 int activation(int act, CState x, int groups, int P, int E, int T, int n, int gps, int p_norm, const float *eps,
                State y, int32_t *status, hipStream_t st);
 int layernorm(CState x, int groups, int P, int E, int T, int n, int gps, int p_norm, const float *eps,
@@ -114,6 +119,7 @@ int fill_zero(float *p, size_t count, hipStream_t st);
 size_t attention_workspace_ext(int B, int L, int H, int D, int P, bool own_scores);
 // ld: row stride of the q, k, v states (D when separate, 3D when they are column slices of one tensor)
 int attention(CState q, CState k, CState v, int ld, int B, int L, int H, int D, int P, int p_norm, const float *eps,
-              State o, State s, int stop_after, int32_t *status, void *ws, size_t ws_bytes, hipStream_t st);
+              State o, State s, int stop_after, int32_t *status, void *ws, size_t ws_bytes, hipStream_t st,
+              const float *qkv_norms = nullptr);
 
 }  // namespace tv

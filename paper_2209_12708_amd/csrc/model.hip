@@ -195,7 +195,7 @@ struct tv_model {
 namespace {
 
 struct Plan {      // workspace offsets in floats for a chunk of Bc sentences
-  size_t x, qkv, t1, big, attn, attn_floats, wh, bh, hy, hl, hu, eps, margin, lohi, labels, status, cnt, qkv0, total;
+  size_t x, qkv, t1, big, attn, attn_floats, wh, bh, hy, hl, hu, eps, margin, lohi, labels, status, cnt, qkv0, norms0, total;
   int NP;
 };
 
@@ -229,6 +229,7 @@ Plan make_plan(const tv_config &c, int Bc, int L, int P, bool cache0 = false) {
   p.status = take(Bc);
   p.cnt = take(Bc);
   p.qkv0 = cache0 ? take(2 * rows * C * 3 * D) : 0;
+  p.norms0 = cache0 ? take(4 * rows * 3 * D) : 0;   // eps-independent part of the cached projection's ranges
   p.total = o;
   return p;
 }
@@ -277,18 +278,22 @@ int init_input(const tv_model *m, const Plan &pl, float *w, const int32_t *token
 }
 
 // q, k, v of the first layer from the input state: the same for every eps, so a bisection computes it once
+// (with the norms and bias values its concretization needs, which do not depend on eps either)
 int project_input(const tv_model *m, const Plan &pl, float *w, const int32_t *tokens, const int32_t *positions,
-                  int Bc, int L, int P, hipStream_t st) {
+                  int Bc, int L, int P, int pn, hipStream_t st) {
   const int D = m->cfg.hidden, C = P * D + 1;
-  const long M = (long)Bc * L * C;
+  const long M = (long)Bc * L * C, n3 = (long)Bc * L * 3 * D;
   if (int rc = init_input(m, pl, w, tokens, positions, Bc, L, P, st)) return rc;
-  return affine(w + pl.x, M * D, M, C, L, D, 3 * D, m->layers[0].Wqkv, m->layers[0].Wqkv3, m->layers[0].bqkv, nullptr, 0,
-                w + pl.qkv0, M * 3 * D, st);
+  float *Q = w + pl.qkv0, *nrm = w + pl.norms0;
+  if (int rc = affine(w + pl.x, M * D, M, C, L, D, 3 * D, m->layers[0].Wqkv, m->layers[0].Wqkv3, m->layers[0].bqkv,
+                      nullptr, 0, Q, M * 3 * D, st)) return rc;
+  return concretize(CState{Q, Q + M * 3 * D}, Bc, P, D, L, 3 * D, 1, pn, w + pl.eps, nrm, nrm + n3, nrm + 2 * n3, 2, st,
+                    nrm + 3 * n3);
 }
 
 // one pass of the encoder.  qkv0: the cached first-layer projection (project_input), or nullptr to compute it.
 int sweep(const tv_model *m, const Plan &pl, float *w, const int32_t *tokens, const int32_t *positions, int Bc, int L,
-          int P, int pn, const float *eps, int32_t *status, const float *qkv0, hipStream_t st) {
+          int P, int pn, const float *eps, int32_t *status, const float *qkv0, const float *norms0, hipStream_t st) {
   const tv_config &c = m->cfg;
   const int D = c.hidden, F = c.ffn, H = c.n_heads;
   const int C = P * D + 1;
@@ -309,7 +314,8 @@ int sweep(const tv_model *m, const Plan &pl, float *w, const int32_t *tokens, co
     else if (int rc = affine(X, pD, M, C, L, D, 3 * D, lw.Wqkv, lw.Wqkv3, lw.bqkv, nullptr, 0, QKV, p3D, st)) return rc;
     CState q{Q, Q + p3D}, k{Q + D, Q + p3D + D}, v{Q + 2 * D, Q + p3D + 2 * D};
     State o{T1, T1 + pD}, s{BIG, BIG + pS};
-    if (int rc = attention(q, k, v, 3 * D, Bc, L, H, D, P, pn, eps, o, s, 0, status, attn_ws, attn_bytes, st))
+    if (int rc = attention(q, k, v, 3 * D, Bc, L, H, D, P, pn, eps, o, s, 0, status, attn_ws, attn_bytes, st,
+                           l == 0 && qkv0 ? norms0 : nullptr))
       return rc;
     // a = o Wo^T + bo + x   (written over the dead q/k/v region), x' = LN(a) (over the dead x)
     float *A = QKV;
@@ -381,7 +387,7 @@ int chunk_labels(const tv_model *m, float *w, const Plan &pl, const int32_t *tok
                      Bc, 0);
   TV_HIP(hipGetLastError());
   if (int rc = sweep(m, p0, w, tokens, positions, Bc, L, 0, pn, eps0, reinterpret_cast<int32_t *>(w + p0.status), nullptr,
-                     st))
+                     nullptr, st))
     return rc;
   if (int rc = head(m, p0, w, Bc, L, 0, pn, eps0, reinterpret_cast<int32_t *>(w + p0.labels), st)) return rc;
   // p0's small arrays sit below pl's (its big regions are smaller), so writing pl.labels last is safe
@@ -529,7 +535,7 @@ int tv_verify(const tv_model *m, const int32_t *tokens, int B, int L, const int3
     if (int rc = chunk_labels(m, w, pl, tok, pos, Bc, L, pn, labels ? labels + b0 : nullptr, st)) return rc;
     hipLaunchKernelGGL(fill_i32_kernel, dim3(nblk(Bc)), dim3(256), 0, st, stat, Bc, 0);
     TV_HIP(hipGetLastError());
-    if (int rc = sweep(m, pl, w, tok, pos, Bc, L, P, pn, eps + b0, stat, nullptr, st)) return rc;
+    if (int rc = sweep(m, pl, w, tok, pos, Bc, L, P, pn, eps + b0, stat, nullptr, nullptr, st)) return rc;
     if (int rc = head(m, pl, w, Bc, L, P, pn, eps + b0, lab, st)) return rc;
     hipLaunchKernelGGL(head_out_kernel, dim3(nblk(Bc)), dim3(256), 0, st, w + pl.hl, w + pl.hu, stat, lab, Bc, nc,
                        pl.NP, out_lower + (size_t)b0 * nc, out_upper + (size_t)b0 * nc,
@@ -568,12 +574,13 @@ int tv_certify(const tv_model *m, const int32_t *tokens, int B, int L, const int
     hipLaunchKernelGGL(search_init_kernel, dim3(nblk(Bc)), dim3(256), 0, st, lohi, Bc, eps_lo, eps_hi, cnt);
     TV_HIP(hipGetLastError());
     if (cache0)
-      if (int rc = project_input(m, pl, w, tok, pos, Bc, L, P, st)) return rc;
+      if (int rc = project_input(m, pl, w, tok, pos, Bc, L, P, pn, st)) return rc;
     for (int it = 0; it < steps; ++it) {
       hipLaunchKernelGGL(search_mid_kernel, dim3(nblk(Bc)), dim3(256), 0, st, lohi, Bc, eps);
       hipLaunchKernelGGL(fill_i32_kernel, dim3(nblk(Bc)), dim3(256), 0, st, stat, Bc, 0);
       TV_HIP(hipGetLastError());
-      if (int rc = sweep(m, pl, w, tok, pos, Bc, L, P, pn, eps, stat, cache0 ? w + pl.qkv0 : nullptr, st)) return rc;
+      if (int rc = sweep(m, pl, w, tok, pos, Bc, L, P, pn, eps, stat, cache0 ? w + pl.qkv0 : nullptr,
+                         cache0 ? w + pl.norms0 : nullptr, st)) return rc;
       if (int rc = head(m, pl, w, Bc, L, P, pn, eps, lab, st)) return rc;
       hipLaunchKernelGGL(head_out_kernel, dim3(nblk(Bc)), dim3(256), 0, st, w + pl.hl, w + pl.hu, stat, lab, Bc, nc,
                          pl.NP, (float *)nullptr, (float *)nullptr, (float *)nullptr, (int32_t *)nullptr, stat, margin);

@@ -226,11 +226,13 @@ __device__ __forceinline__ void apply_maps(const float *S, const float *R, float
 
 // ------------------------------------------------------------------------------------------------
 // Eq. (1) on the flat [T*n] axis of a group.  grid = (groups, column chunks).
-// mode 0 writes (l, u); mode 1 writes (mid, half) and, if o2 != nullptr, the slack S_b - l = R_b + e NL.
+// mode 0 writes (l, u); mode 1 writes (mid, half) and, if o2 != nullptr, the slack S_b - l = R_b + e NL;
+// mode 2 writes what does not depend on eps - the two norms and the bias values (o0..o3 = NL, NU, S_b, R_b) -
+// from which ranges_kernel forms mode 1's outputs for any eps.
 template <int VEC, int PN>
 __global__ __launch_bounds__(kThreads) void concretize_kernel(const float *S, const float *R, int P, int E, int X,
                                                               int G, int gps, const float *eps,
-                                                              float *o0, float *o1, float *o2, int mode) {
+                                                              float *o0, float *o1, float *o2, float *o3, int mode) {
   constexpr int pn = PN;   // the norm is a compile-time constant: no selects in the accumulation loops
   __shared__ float red[4 * kWave * 8 * VEC];
   const int chunk = 4 * G * VEC, c0 = blockIdx.y * chunk;
@@ -239,13 +241,20 @@ __global__ __launch_bounds__(kThreads) void concretize_kernel(const float *S, co
   float NL[4 * VEC], NU[4 * VEC], bS[4 * VEC], bR[4 * VEC];
   column_norms<VEC>(S, R, lc, P, E, ge, pn, nullptr, red, NL, NU, bS, bR);
   if (ge.slot == 0) {
-    const float e = eps[blockIdx.x / gps];
+    const float e = mode == 2 ? 0.f : eps[blockIdx.x / gps];
     const long o = (long)blockIdx.x * X + c0;
 #pragma unroll
     for (int v = 0; v < VEC; ++v) {
       const int f = ge.g + ge.G * v;
       if (f < ge.n4) {
         float4 a, b, c3;
+        if (mode == 2) {
+          reinterpret_cast<float4 *>(o0 + o)[f] = make_float4(NL[4 * v], NL[4 * v + 1], NL[4 * v + 2], NL[4 * v + 3]);
+          reinterpret_cast<float4 *>(o1 + o)[f] = make_float4(NU[4 * v], NU[4 * v + 1], NU[4 * v + 2], NU[4 * v + 3]);
+          reinterpret_cast<float4 *>(o2 + o)[f] = make_float4(bS[4 * v], bS[4 * v + 1], bS[4 * v + 2], bS[4 * v + 3]);
+          reinterpret_cast<float4 *>(o3 + o)[f] = make_float4(bR[4 * v], bR[4 * v + 1], bR[4 * v + 2], bR[4 * v + 3]);
+          continue;
+        }
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
           const int i = 4 * v + c;
@@ -264,6 +273,17 @@ __global__ __launch_bounds__(kThreads) void concretize_kernel(const float *S, co
         if (mode != 0 && o2) reinterpret_cast<float4 *>(o2 + o)[f] = c3;
       }
     }
+  }
+}
+
+// mode 1 of concretize_kernel from stored norms and bias values (the same float expressions, so the same bits)
+__global__ void ranges_kernel(const float *NL, const float *NU, const float *bS, const float *bR, long X, long total,
+                              int gps, const float *eps, float *mid, float *half, float *slack) {
+  for (long t = (long)blockIdx.x * blockDim.x + threadIdx.x; t < total; t += (long)gridDim.x * blockDim.x) {
+    const float e = eps[(t / X) / gps];
+    mid[t] = bS[t] + 0.5f * e * (NU[t] - NL[t]);
+    half[t] = bR[t] + 0.5f * e * (NU[t] + NL[t]);
+    if (slack) slack[t] = bR[t] + e * NL[t];
   }
 }
 
@@ -1078,10 +1098,24 @@ int check_common(const void *S, const void *R, int groups, int P, int E, int T, 
 
 }  // namespace
 
+int ranges_from_norms(const float *norms, int groups, int T, int n, int gps, const float *eps, float *mid, float *half,
+                      float *slack, hipStream_t st) {
+  TV_REQUIRE(norms && eps && mid && half, TV_E_NULL, "ranges_from_norms: null pointer");
+  TV_REQUIRE(groups > 0 && T > 0 && n > 0 && gps > 0 && groups % gps == 0, TV_E_SHAPE, "ranges_from_norms: bad shape");
+  const long X = (long)T * n, total = X * groups;
+  ProfScope prof(K_CONCRETIZE, st, 6.0 * total, 28.0 * total);
+  const long blocks = (total + 255) / 256;
+  hipLaunchKernelGGL(ranges_kernel, dim3((unsigned)(blocks > 16384 ? 16384 : blocks)), dim3(256), 0, st, norms,
+                     norms + total, norms + 2 * total, norms + 3 * total, X, total, gps, eps, mid, half, slack);
+  TV_HIP(hipGetLastError());
+  return TV_OK;
+}
+
 int concretize(CState x, int groups, int P, int E, int T, int n, int gps, int pn, const float *eps, float *o0,
-               float *o1, float *o2, int mode, hipStream_t st) {
+               float *o1, float *o2, int mode, hipStream_t st, float *o3) {
   if (int rc = check_common(x.S, x.R, groups, P, E, T, n, gps, pn, eps)) return rc;
   TV_REQUIRE(o0 && o1, TV_E_NULL, "null output");
+  TV_REQUIRE(mode == 0 || mode == 1 || (mode == 2 && o2 && o3), TV_E_ARG, "concretize: bad mode or outputs");
   const long X = (long)T * n;
   int G, nch;
   chunk_geo(X, G, nch);
@@ -1089,7 +1123,7 @@ int concretize(CState x, int groups, int P, int E, int T, int n, int gps, int pn
   ProfScope prof(K_CONCRETIZE, st, 4.0 * groups * C * X, 8.0 * groups * C * X + 8.0 * groups * X);
 #define CONC_LAUNCH(PN)                                                                                            \
   hipLaunchKernelGGL((concretize_kernel<1, PN>), dim3(groups, nch), dim3(kThreads), 0, st, x.S, x.R, P, E, (int)X, G, \
-                     gps, eps, o0, o1, o2, mode)
+                     gps, eps, o0, o1, o2, o3, mode)
   NORM_SWITCH(pn, CONC_LAUNCH);
 #undef CONC_LAUNCH
   TV_HIP(hipGetLastError());
