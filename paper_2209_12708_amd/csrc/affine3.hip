@@ -35,6 +35,10 @@ struct Affine3Args {
   const float *bias; long sBias;        // [N] added on bias rows, or nullptr
   int bias_T, bias_C;                   // rows are (group, coefficient row, t): bias rows have r == bias_C - 1
   int M, N, K;
+  // Residual = the input state of Sec. 2.1 given by what generates it instead of as stored planes (or nullptr):
+  // bias row (group, t) += in_x0[group][t][n]; coefficient row r * N + e of perturbed position r has a one at
+  // t = in_pos[group][r], n = e; the radius plane has no residual.  Needs bias_T, bias_C; excludes Cadd.
+  const float *in_x0; const int32_t *in_pos; int in_P;
 };
 
 // x = a + b + c exactly (up to the last piece's rounding, below 2^-24 |x|)
@@ -291,6 +295,18 @@ void affine3_kernel(const Affine3Args g, int mtiles, int ntiles) {
     if (m >= M || n >= N) continue;
     float4 v = *reinterpret_cast<const float4 *>(Ct + row * CS + c4 * 4);
     v.x += radd[it].x; v.y += radd[it].y; v.z += radd[it].z; v.w += radd[it].w;
+    if (g.in_x0 && z == 0) {
+      const int blk = m / g.bias_T, t = m - blk * g.bias_T, c = blk % g.bias_C, grp = blk / g.bias_C;
+      if (c == g.bias_C - 1) {
+        const float4 a = *reinterpret_cast<const float4 *>(g.in_x0 + ((long)grp * g.bias_T + t) * N + n);
+        v.x += a.x; v.y += a.y; v.z += a.z; v.w += a.w;
+      } else {
+        const int r = c / N, e = c - r * N;
+        if (e >= n && e < n + 4 && g.in_pos[grp * g.in_P + r] == t) {
+          if (e == n) v.x += 1.f; else if (e == n + 1) v.y += 1.f; else if (e == n + 2) v.z += 1.f; else v.w += 1.f;
+        }
+      }
+    }
     if (tile_has_bias && (m / g.bias_T) % g.bias_C == g.bias_C - 1) {
       // rows are ordered (group, coefficient row, t); the last coefficient row is the bias row
       const float4 b = *reinterpret_cast<const float4 *>(bias + n);
@@ -335,22 +351,26 @@ int split_bf16x3(const float *in, unsigned short *out, int N, int K, bool take_a
 }
 
 int affine_split(const float *xS, long xplane, long M, int C, int T, int K, int N, const unsigned short *W3pair,
-                 const float *bpair, const float *addS, long addplane, float *yS, long yplane, hipStream_t st, int planes) {
+                 const float *bpair, const float *addS, long addplane, float *yS, long yplane, hipStream_t st, int planes,
+                 const float *in_x0, const int32_t *in_pos, int in_P) {
   TV_REQUIRE(planes == 1 || planes == 2, TV_E_ARG, "affine: planes must be 1 or 2");
   TV_REQUIRE(xS && W3pair && yS, TV_E_NULL, "affine: null operand");
   TV_REQUIRE(M > 0 && M < (1L << 31) && N > 0 && K > 0 && K % 8 == 0, TV_E_SHAPE,
              "affine (split weights): need 0 < M < 2^31, K %% 8 == 0 (M=%ld N=%d K=%d)", M, N, K);
   TV_REQUIRE(bpair == nullptr || (T > 0 && C > 0), TV_E_ARG, "affine: bias without row structure");
+  TV_REQUIRE(in_x0 == nullptr || (addS == nullptr && in_pos && in_P >= 0 && T > 0 && C == in_P * N + 1 && N % 4 == 0),
+             TV_E_ARG, "affine: the input-state residual needs C = P N + 1 rows, positions and no stored residual");
   Affine3Args g;
   g.A = xS; g.sA = xplane;
   g.W3 = W3pair; g.sW = 3L * N * ((K + 31) / 32 * 32);
   g.C = yS; g.sC = yplane;
   g.Cadd = addS; g.sAdd = addplane;
   g.bias = bpair; g.sBias = N; g.bias_T = T; g.bias_C = C;
+  g.in_x0 = in_x0; g.in_pos = in_pos; g.in_P = in_P;
   g.M = (int)M; g.N = N; g.K = K;
   const double mn = (double)M * N;
   ProfScope prof(K_AFFINE, st, planes * 2.0 * mn * K,
-                 planes * 4.0 * ((double)M * K + (double)N * K + mn * (addS ? 2.0 : 1.0)));
+                 planes * 4.0 * ((double)M * K + (double)N * K + mn * (addS ? 2.0 : 1.0)));   // the input-state residual is not counted: it reads M N / C values
   const bool big = M >= 128 * 256;
   if (N <= 64) return launch3<128, 64, 2, 2>(g, planes, st);
   // wide layers: 64 x 64 per wave halves the LDS traffic per MFMA (measured +4..13 % from K = 256, N = 512 up)

@@ -89,9 +89,11 @@ int split_bf16x3(const float *in, unsigned short *out, int N, int K, bool take_a
 // y = x W^T (+ bias on bias rows of the centre plane) (+ add) for both planes in one launch.  W3pair:
 // split_bf16x3 of W, then of |W| (3 * N * Kp values each); bpair: [2][N] = (b, 0) or nullptr; planes of x / add / y are xplane /
 // addplane / yplane floats apart; rows are (group, coefficient row of C, t of T).  K % 8 == 0.
+// in_x0 / in_pos / in_P: the residual is the input state of Sec. 2.1, given as the clean embeddings [groups][T][N]
+// and the perturbed positions [groups][in_P] instead of as stored planes (then addS must be null and C = in_P N + 1).
 int affine_split(const float *xS, long xplane, long M, int C, int T, int K, int N, const unsigned short *W3pair,
                  const float *bpair, const float *addS, long addplane, float *yS, long yplane, hipStream_t st,
-                 int planes = 2);
+                 int planes = 2, const float *in_x0 = nullptr, const int32_t *in_pos = nullptr, int in_P = 0);
 
 // ---- elementwise / reduction kernels (rowops.hip) ------------------------------------------
 // States are [groups][C][T][n]; eps is indexed by group / gps (groups per sentence).

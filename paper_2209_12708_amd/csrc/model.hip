@@ -71,6 +71,17 @@ __global__ void init_state_kernel(const int32_t *tokens, const int32_t *position
   }
 }
 
+// the clean embeddings alone, [B][L][D] (the same sum as in init_state_kernel)
+__global__ void embed_kernel(const int32_t *tokens, const float *tok_emb, const float *pos_emb, int B, int L, int D,
+                             float *x0) {
+  const long total = (long)B * L * D;
+  for (long i = (long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long)gridDim.x * blockDim.x) {
+    const int d = (int)(i % D);
+    const long bt = i / D;
+    x0[i] = tok_emb[(long)tokens[bt] * D + d] + pos_emb[(long)(bt % L) * D + d];
+  }
+}
+
 // Head rows per sentence: classes 0..n_cls-1, then margins w[label] - w[j] (j != label, increasing j);
 // padded with zero rows to NP.  Wh: [2][B][NP][D] (weights, then their absolute values); bh: [2][B][NP].
 __global__ void head_prep_kernel(const float *Wc, const float *bc, const int32_t *labels, int B, int n_cls, int NP,
@@ -195,7 +206,7 @@ struct tv_model {
 namespace {
 
 struct Plan {      // workspace offsets in floats for a chunk of Bc sentences
-  size_t x, qkv, t1, big, attn, attn_floats, wh, bh, hy, hl, hu, eps, margin, lohi, labels, status, cnt, qkv0, norms0, total;
+  size_t x, qkv, t1, big, attn, attn_floats, wh, bh, hy, hl, hu, eps, margin, lohi, labels, status, cnt, qkv0, norms0, x0, total;
   int NP;
 };
 
@@ -230,6 +241,7 @@ Plan make_plan(const tv_config &c, int Bc, int L, int P, bool cache0 = false) {
   p.cnt = take(Bc);
   p.qkv0 = cache0 ? take(2 * rows * C * 3 * D) : 0;
   p.norms0 = cache0 ? take(4 * rows * 3 * D) : 0;   // eps-independent part of the cached projection's ranges
+  p.x0 = cache0 ? take(rows * D) : 0;               // clean embeddings: the input state's bias rows
   p.total = o;
   return p;
 }
@@ -285,6 +297,9 @@ int project_input(const tv_model *m, const Plan &pl, float *w, const int32_t *to
   const long M = (long)Bc * L * C, n3 = (long)Bc * L * 3 * D;
   if (int rc = init_input(m, pl, w, tokens, positions, Bc, L, P, st)) return rc;
   float *Q = w + pl.qkv0, *nrm = w + pl.norms0;
+  hipLaunchKernelGGL(embed_kernel, dim3(nblk((long)Bc * L * D)), dim3(256), 0, st, tokens, m->tok_emb, m->pos_emb, Bc, L,
+                     D, w + pl.x0);
+  TV_HIP(hipGetLastError());
   if (int rc = affine(w + pl.x, M * D, M, C, L, D, 3 * D, m->layers[0].Wqkv, m->layers[0].Wqkv3, m->layers[0].bqkv,
                       nullptr, 0, Q, M * 3 * D, st)) return rc;
   return concretize(CState{Q, Q + M * 3 * D}, Bc, P, D, L, 3 * D, 1, pn, w + pl.eps, nrm, nrm + n3, nrm + 2 * n3, 2, st,
@@ -304,7 +319,12 @@ int sweep(const tv_model *m, const Plan &pl, float *w, const int32_t *tokens, co
   void *attn_ws = w + pl.attn;
   const size_t attn_bytes = pl.attn_floats * sizeof(float);
 
-  if (int rc = init_input(m, pl, w, tokens, positions, Bc, L, P, st)) return rc;
+  // With the first layer's projection cached the input state is needed once more only, as the residual of the first
+  // W_o product: there it is added from its generators (clean embeddings, perturbed positions), and the planes
+  // are neither cleared nor filled nor read.
+  const bool input_from_generators = qkv0 && m->layers[0].Wo3 && P >= 1;
+  if (!input_from_generators)
+    if (int rc = init_input(m, pl, w, tokens, positions, Bc, L, P, st)) return rc;
 
   for (int l = 0; l < c.n_layers; ++l) {
     const tv_layer_dev &lw = m->layers[l];
@@ -319,7 +339,10 @@ int sweep(const tv_model *m, const Plan &pl, float *w, const int32_t *tokens, co
       return rc;
     // a = o Wo^T + bo + x   (written over the dead q/k/v region), x' = LN(a) (over the dead x)
     float *A = QKV;
-    if (int rc = affine(T1, pD, M, C, L, D, D, lw.Wo, lw.Wo3, lw.bo, X, pD, A, pD, st)) return rc;
+    if (l == 0 && input_from_generators) {
+      if (int rc = affine_split(T1, pD, M, C, L, D, D, lw.Wo3, lw.bo, nullptr, 0, A, pD, st, 2, w + pl.x0, positions, P))
+        return rc;
+    } else if (int rc = affine(T1, pD, M, C, L, D, D, lw.Wo, lw.Wo3, lw.bo, X, pD, A, pD, st)) return rc;
     if (int rc = layernorm(CState{A, A + pD}, Bc, P, D, L, D, 1, pn, eps, lw.ln1_g, lw.ln1_b, c.ln_eps,
                            State{X, X + pD}, status, st)) return rc;
     // feed-forward: h = x' W1^T + b1 ; act ; f = act W2^T + b2 + x' ; x'' = LN(f)
