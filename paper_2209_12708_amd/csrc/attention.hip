@@ -307,6 +307,7 @@ int attention(CState q, CState k, CState v, int ld, int B, int L, int H, int D, 
   // Both halves of a product in one launch (the half over y's state accumulated from fragments loaded straight
   // from memory) when the shapes allow; otherwise two launches, the second accumulating through memory.
   const bool fused_products = L % 32 == 0 && dh % 32 == 0;
+  bool fix_qk_in_product = false, fix_pv_in_product = false;
   {  // scores, part 1: [S_q | R_q] x coefficients from k's range  -> both planes of s
     GemmArgs g;
     g.A = q.S; g.A2 = q.R; g.K1 = dh; g.lda = ld;
@@ -325,6 +326,10 @@ int attention(CState q, CState k, CState v, int ld, int B, int L, int H, int D, 
       g.spA[0] = bld; g.spA[1] = dh; g.spA[2] = (long)L * D;
       g.spB[0] = k.R - k.S; g.spB[1] = dh; g.spB[2] = clx;
     }
+    if (dual_split_fits(g)) {   // that kernel also writes the radius plane's recomputed bias rows
+      g.fix = w + lay.fix_qk; g.fix_ld = L; g.sFix[1] = (long)L * L; g.sFix[2] = (long)H * L * L;
+      fix_qk_in_product = true;
+    }
     if (int rc = gemm(g, st)) return rc;
   }
   if (!fused_products) {  // scores, part 2: coefficients from q's range x the state of k, accumulated.  n = (r, j)
@@ -340,7 +345,7 @@ int attention(CState q, CState k, CState v, int ld, int B, int L, int H, int D, 
     g.sAdd[0] = g.sC[0]; g.sAdd[1] = g.sC[1]; g.sAdd[2] = g.sC[2];
     if (int rc = gemm(g, st)) return rc;
   }
-  {
+  if (!fix_qk_in_product) {
     ProfScope prof(K_PREP, st, 0.0, 0.0);
     hipLaunchKernelGGL(bias_row_put_kernel, dim3(blocks_for((long)B * H * L * L)), dim3(256), 0, st, w + lay.fix_qk, s.R,
                        (long)B * H, C, (long)L * L);
@@ -376,6 +381,10 @@ int attention(CState q, CState k, CState v, int ld, int B, int L, int H, int D, 
       g.spA[0] = 0; g.spA[1] = (long)L * L; g.spA[2] = (long)H * L * L;
       g.spB[0] = v.R - v.S; g.spB[1] = dh; g.spB[2] = clx;
     }
+    if (dual_split_fits(g)) {
+      g.fix = w + lay.fix_pv; g.fix_ld = D; g.sFix[1] = dh; g.sFix[2] = (long)L * D;
+      fix_pv_in_product = true;
+    }
     if (int rc = gemm(g, st)) return rc;
   }
   if (!fused_products) {  // o, part 2: lp x the state of v, accumulated.  n = (r, d)
@@ -391,7 +400,7 @@ int attention(CState q, CState k, CState v, int ld, int B, int L, int H, int D, 
     g.sAdd[0] = g.sC[0]; g.sAdd[1] = g.sC[1]; g.sAdd[2] = g.sC[2];
     if (int rc = gemm(g, st)) return rc;
   }
-  {
+  if (!fix_pv_in_product) {
     ProfScope prof(K_PREP, st, 0.0, 0.0);
     hipLaunchKernelGGL(bias_row_put_kernel, dim3(blocks_for(bld)), dim3(256), 0, st, w + lay.fix_pv, o.R, (long)B, C,
                        (long)L * D);

@@ -86,6 +86,7 @@ __global__ __launch_bounds__(256) void bilinear3_kernel(const GemmArgs g, int mt
   const float *bias = g.bias ? g.bias + z0 * g.sBias[0] + z1 * g.sBias[1] + z2 * g.sBias[2] : nullptr;
   const float *pA = g.pA + z0 * g.spA[0] + z1 * g.spA[1] + z2 * g.spA[2];
   const float *pB = g.pB + z0 * g.spB[0] + z1 * g.spB[1] + z2 * g.spB[2];
+  const float *fix = (g.fix && z0 == 1) ? g.fix + z1 * g.sFix[1] + z2 * g.sFix[2] : nullptr;
 
   const int tid = threadIdx.x, lane = tid & 63, wm = tid >> 6;
   const int l32 = lane & 31, half = lane >> 5;
@@ -217,8 +218,14 @@ __global__ __launch_bounds__(256) void bilinear3_kernel(const GemmArgs g, int mt
       // rows are ordered (group, coefficient row, t); the last coefficient row is the bias row
       const int blk = m / g.bias_T;
       if (blk % g.bias_C == g.bias_C - 1) {
-        const float *brow = bias + ((long)(blk / g.bias_C) * g.bias_T + m % g.bias_T) * g.bias_ld + n;
-        v.x += brow[0]; v.y += brow[1]; v.z += brow[2]; v.w += brow[3];
+        const long at = (long)(blk / g.bias_C) * g.bias_T + m % g.bias_T;
+        if (fix) {        // the radius plane's bias value comes ready-made
+          const float *frow = fix + at * g.fix_ld + n;
+          v = make_float4(frow[0], frow[1], frow[2], frow[3]);
+        } else {
+          const float *brow = bias + at * g.bias_ld + n;
+          v.x += brow[0]; v.y += brow[1]; v.z += brow[2]; v.w += brow[3];
+        }
       }
     }
     *reinterpret_cast<float4 *>(C + (long)m * g.ldc + n) = v;
@@ -228,7 +235,7 @@ __global__ __launch_bounds__(256) void bilinear3_kernel(const GemmArgs g, int mt
 }  // namespace
 
 bool dual_split_fits(const GemmArgs &g) {
-  return g.pA && g.pB && g.b_mode == 0 && g.cq == 0 && g.Cadd == nullptr && g.M >= 128 && g.N % 32 == 0 &&
+  return g.pA && g.pB && g.bias && g.b_mode == 0 && g.cq == 0 && g.Cadd == nullptr && g.M >= 128 && g.N % 32 == 0 &&
          g.K % 32 == 0 && g.K1 % 32 == 0 && g.pK % 32 == 0 && g.pL % 32 == 0 && g.M % 32 == 0 && g.lda % 4 == 0 &&
          g.ldb % 4 == 0 && g.ldc % 4 == 0 && g.pA_ld % 4 == 0 && g.pB_ld % 4 == 0 &&
          (reinterpret_cast<uintptr_t>(g.C) & 15) == 0 && g.sC[0] % 4 == 0 && g.sC[1] % 4 == 0 && g.sC[2] % 4 == 0;

@@ -72,6 +72,10 @@ struct GemmArgs {
   const float *pB = nullptr; long pB_ld = 0;
   int pB_mode = 0, pL = 0, pK = 0;
   long spA[3] = {0, 0, 0}, spB[3] = {0, 0, 0};
+  // Optional replacement of the bias rows of the planes with z0 == 1 (the radius plane of a dot-product bound,
+  // whose bias value is formed from slacks and half-widths, not by the contraction): C = fix[t * fix_ld + n] there.
+  // Honoured by gemm_dual_split only; gemm() itself requires it to be null.
+  const float *fix = nullptr; long fix_ld = 0; long sFix[3] = {0, 0, 0};
 };
 int gemm(const GemmArgs &g, hipStream_t st);
 // The same contraction with its second product on the bf16 matrix cores, three bf16 pieces per operand cut on the

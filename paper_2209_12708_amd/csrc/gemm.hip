@@ -334,6 +334,7 @@ int gemm(const GemmArgs &g, hipStream_t st) {
                  4.0 * nz * ((double)g.M * g.K + (double)g.N * g.K + mn * (g.Cadd ? 2.0 : 1.0) +
                              (g.pA ? (double)g.M * (g.pB_mode == 0 ? k2 * g.N / g.pL : (double)g.N * k2 / g.pL) : 0.0)));
   if (dual_split_fits(a)) return gemm_dual_split(a, st);
+  TV_REQUIRE(a.fix == nullptr, TV_E_ARG, "gemm: bias-row replacement needs the split dual kernel");
   // tile shape by problem shape: small M (per-batch contractions over tokens) vs small N (head width)
   if (a.M <= 32) return launch<32, 128, 1, 4>(a, st);
   if (a.M <= 64) return launch<64, 128, 2, 2>(a, st);
