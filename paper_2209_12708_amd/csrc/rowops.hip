@@ -1051,6 +1051,229 @@ __global__ __launch_bounds__(kThreads) void softmax_kernel(float *S, float *R, i
   }
 }
 
+// Softmax for small blocks (one perturbed position, attention rows of 16 .. 128 scores): a workgroup takes as many
+// neighbouring attention rows as make 128 contiguous floats per coefficient row (TT = 128 / n tokens, `seg` = n / 4
+// lanes each), reads the block once - all loads in flight together - and keeps it in registers for all three
+// sweeps; rows of 512 bytes instead of n * 4, and two workgroups per CU whose phases overlap.  Same arithmetic as
+// softmax_kernel, with the per-row scalars kept once per token of the block.
+template <int ROWS, int LROWS, int PN>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2)))
+void softmax_cached_kernel(float *S, float *R, int nrows, int TB, int seg, int gps,
+                                                                  const float *eps, float *lp_out, float *slack_out,
+                                                                  int32_t *status) {
+  constexpr int pn = PN;
+  constexpr int NCOL = 128, GL = 32, MAXT = 8;             // columns, lanes per coefficient row, tokens per block at most
+  __shared__ float red[4 * kWave * 8];
+  __shared__ double col_d[6][NCOL];                        // in: l, u (shifted), shift; out: kL, hk, dk, hc -> e_S_b, dc -> e_R_b, le
+  __shared__ float sgrow[2][ROWS][kThreads / GL * MAXT];   // sigma's planes per cached row and token
+  __shared__ float tokf[MAXT][8];
+  __shared__ double tokd[MAXT][6];
+  const int C = nrows + 1;
+  const Geo ge(GL, NCOL / 4);
+  const Loc lc{(long)(blockIdx.x / TB), C, TB, (int)(blockIdx.x % TB), NCOL, 0};
+  const int sent = (int)(lc.grp / gps);
+  const double e = eps[sent];
+  const int ts = ge.g / seg;                               // token of this lane within the block
+  const int TT = GL / seg;
+  bool bad = false;
+
+  // The first RROWS rows of a thread stay in registers, the last LROWS in LDS (its own slots, no exchange): the exp
+  // relaxation in the middle of the kernel needs about a hundred registers of its own, and with the whole block in
+  // registers the second workgroup would not fit on the CU.
+  constexpr int RROWS = ROWS - LROWS;
+  __shared__ float4 keepS[LROWS][kThreads], keepR[LROWS][kThreads];
+  float4 xs4[RROWS], xr4[RROWS];
+#pragma unroll
+  for (int it = 0; it < ROWS; ++it) {
+    const int r = ge.slot + it * ge.NS;
+    float4 a = make_float4(0.f, 0.f, 0.f, 0.f), b = a;
+    if (r < nrows) {
+      const long o = lc.off(r);
+      a = reinterpret_cast<const float4 *>(S + o)[ge.g];
+      b = reinterpret_cast<const float4 *>(R + o)[ge.g];
+    }
+    if (it < RROWS) { xs4[it] = a; xr4[it] = b; }
+    else { keepS[it - RROWS][threadIdx.x] = a; keepR[it - RROWS][threadIdx.x] = b; }
+  }
+  auto row = [&](int it, float (&a)[4], float (&b)[4]) {
+    const float4 va = it < RROWS ? xs4[it < RROWS ? it : 0] : keepS[it < RROWS ? 0 : it - RROWS][threadIdx.x];
+    const float4 vb = it < RROWS ? xr4[it < RROWS ? it : 0] : keepR[it < RROWS ? 0 : it - RROWS][threadIdx.x];
+    a[0] = va.x; a[1] = va.y; a[2] = va.z; a[3] = va.w;
+    b[0] = vb.x; b[1] = vb.y; b[2] = vb.z; b[3] = vb.w;
+  };
+  // ---- sweep 1: norms of s per column, range, shift by the largest upper bound of the attention row
+  float NLs[4];
+  {
+    float acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] = 0.f;
+#pragma unroll
+    for (int it = 0; it < ROWS; ++it) {
+      if (ge.slot + it * ge.NS < nrows) {
+        float xs[4], xr[4];
+        row(it, xs, xr);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          acc[2 * i] = norm_acc(acc[2 * i], xs[i] - xr[i], pn);
+          acc[2 * i + 1] = norm_acc(acc[2 * i + 1], xs[i] + xr[i], pn);
+        }
+      }
+    }
+    slot_reduce<8>(acc, ge, pn == 1, red);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) NLs[i] = norm_fin(acc[2 * i], pn);
+    if (ge.slot == 0) {
+      float bS[4], bR[4];
+      load_row<1>(S, R, lc, C - 1, ge, bS, bR);
+      double ls[4], us[4];
+      float mx = -FLT_MAX;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        range_of(bS[i], bR[i], e, NLs[i], norm_fin(acc[2 * i + 1], pn), ls[i], us[i]);
+        bad |= !(finite_d(ls[i]) && finite_d(us[i]));
+        mx = fmaxf(mx, (float)us[i]);
+      }
+      const double shift = row_max(mx, seg);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int col = 4 * ge.g + i;
+        col_d[0][col] = ls[i] - shift; col_d[1][col] = us[i] - shift; col_d[2][col] = shift;
+      }
+    }
+  }
+  __syncthreads();
+  // exp relaxation, one lane per column (two waves, chosen by the block index), see softmax_kernel
+  {
+    const int first = (blockIdx.x & 1) * 2 * kWave;
+    const int col = ((int)threadIdx.x - first + kThreads) % kThreads;
+    if (col < NCOL) {
+      const double l = col_d[0][col], u = col_d[1][col], shift = col_d[2][col];
+      const Line2 ex = relax_exp(l, u);
+      const double cL = ex.cL - ex.kL * shift, cU = ex.cU - ex.kU * shift;
+      col_d[0][col] = ex.kL;
+      col_d[1][col] = 0.5 * (ex.kL + ex.kU); col_d[2][col] = 0.5 * (ex.kU - ex.kL);
+      col_d[3][col] = 0.5 * (cL + cU); col_d[4][col] = 0.5 * (cU - cL);
+      col_d[5][col] = ex.kL * l + ex.cL;
+    }
+  }
+  __syncthreads();
+  float hkf[4], dkf[4], lef[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int col = 4 * ge.g + i;
+    hkf[i] = (float)col_d[1][col]; dkf[i] = (float)col_d[2][col]; lef[i] = (float)col_d[5][col];
+  }
+  // the bias row of e and sigma in double (row slot 0); e's bias values replace the intercepts in LDS
+  double sgSb = 0.0, sgRb = 0.0;
+  if (ge.slot == 0) {
+    float bS[4], bR[4];
+    load_row<1>(S, R, lc, C - 1, ge, bS, bR);
+    double a = 0.0, b = 0.0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int col = 4 * ge.g + i;
+      const double hk = col_d[1][col], dk = col_d[2][col];
+      const double eSb = hk * bS[i] + dk * bR[i] + col_d[3][col];
+      const double eRb = dk * bS[i] + hk * bR[i] + col_d[4][col];
+      col_d[3][col] = eSb; col_d[4][col] = eRb;
+      a += eSb; b += eRb;
+    }
+    sgSb = row_sum<double>(a, seg); sgRb = row_sum<double>(b, seg);
+  }
+  // ---- sweep 2: sigma per coefficient row and token, its norms, the reciprocal's relaxation per token
+  {
+    float acc[2] = {0.f, 0.f};
+#pragma unroll
+    for (int it = 0; it < ROWS; ++it) {
+      if (ge.slot + it * ge.NS < nrows) {
+        float a = 0.f, b = 0.f, xs[4], xr[4];
+        row(it, xs, xr);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          a += hkf[i] * xs[i] + dkf[i] * xr[i];
+          b += dkf[i] * xs[i] + hkf[i] * xr[i];
+        }
+        const float sgS = row_sum<float>(a, seg), sgR = row_sum<float>(b, seg);
+        if (ge.g % seg == 0) { sgrow[0][it][ge.slot * MAXT + ts] = sgS; sgrow[1][it][ge.slot * MAXT + ts] = sgR; }
+        acc[0] = norm_acc(acc[0], sgS - sgR, pn);
+        acc[1] = norm_acc(acc[1], sgS + sgR, pn);
+      }
+    }
+    slot_reduce<2>(acc, ge, pn == 1, red);
+    if (ge.slot == 0) {
+      double lsg, usg;
+      range_of(sgSb, sgRb, e, norm_fin(acc[0], pn), norm_fin(acc[1], pn), lsg, usg);
+      bad |= !(finite_d(lsg) && finite_d(usg)) || !(lsg >= kRecipMin);
+      const Line2 rcp = relax_recip(lsg, usg);
+      double lr, ur;
+      line_range(rcp, lsg, usg, lr, ur);
+      const Map2 mr = form_map(form_sub(form_identity(), rcp));      // rho relative to sigma
+      const Mul2 mc = mul_coeffs(lr, ur);
+      if (bad) status[sent] = 1;
+      if (ge.g % seg == 0) {
+        tokf[ts][0] = mr.sS; tokf[ts][1] = mr.sR; tokf[ts][2] = mr.rS; tokf[ts][3] = mr.rR;
+        tokf[ts][4] = mc.a1; tokf[ts][5] = mc.a2; tokf[ts][6] = mc.a3; tokf[ts][7] = mc.a4;
+        tokd[ts][0] = mr.sSd * sgSb + mr.sRd * sgRb + mr.sCd;           // rho's bias values
+        tokd[ts][1] = mr.rSd * sgSb + mr.rRd * sgRb + mr.rCd;
+        tokd[ts][2] = mc.a1d; tokd[ts][3] = mc.a2d; tokd[ts][4] = mc.a3d; tokd[ts][5] = mc.a4d;
+      }
+    }
+  }
+  __syncthreads();
+  const float m_sS = tokf[ts][0], m_sR = tokf[ts][1], m_rS = tokf[ts][2], m_rR = tokf[ts][3];
+  const float c_a1 = tokf[ts][4], c_a2 = tokf[ts][5], c_a3 = tokf[ts][6], c_a4 = tokf[ts][7];
+
+  // ---- sweep 3: p = e * rho, its lower line's norm
+  float NLp[4];
+  {
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int it = 0; it < ROWS; ++it) {
+      const int r = ge.slot + it * ge.NS;
+      if (r < nrows) {
+        const float sgS = sgrow[0][it][ge.slot * MAXT + ts], sgR = sgrow[1][it][ge.slot * MAXT + ts];
+        const float rhoS = m_sS * sgS + m_sR * sgR, rhoR = m_rS * sgS + m_rR * sgR;
+        float ps[4], pr[4], xs[4], xr[4];
+        row(it, xs, xr);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const float eS = hkf[i] * xs[i] + dkf[i] * xr[i], eR = dkf[i] * xs[i] + hkf[i] * xr[i];
+          ps[i] = c_a1 * eS + c_a2 * eR + lef[i] * rhoS;
+          pr[i] = c_a3 * eS + c_a4 * eR + fabsf(lef[i]) * rhoR;
+          acc[i] = norm_acc(acc[i], ps[i] - pr[i], pn);
+        }
+        store_row<1>(S, R, lc, r, ge, ps, pr);
+      }
+    }
+    slot_reduce<4>(acc, ge, pn == 1, red);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) NLp[i] = norm_fin(acc[i], pn);
+  }
+  if (ge.slot == 0) {   // bias row, in double; concretized lower bound of p and its slack
+    const double rhoS = tokd[ts][0], rhoR = tokd[ts][1];
+    const double a1d = tokd[ts][2], a2d = tokd[ts][3], a3d = tokd[ts][4], a4d = tokd[ts][5];
+    float ps[4], pr[4], lpv[4], slv[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int col = 4 * ge.g + i;
+      const double kLe = col_d[0][col], le = col_d[5][col], eSb = col_d[3][col], eRb = col_d[4][col];
+      const double slack_e = eRb + e * kLe * (double)NLs[i];           // e_S_b - le without cancellation
+      const double pS = a1d * eSb + a2d * eRb + le * rhoS - le * a1d;
+      const double pR = a3d * slack_e + a4d * eRb + fabs(le) * rhoR;
+      const double half = pR + e * (double)NLp[i];                     // S_p_b - (lower bound of p)
+      const double lraw = pS - half;
+      const double lcl = fmin(fmax(lraw, 0.0), 1.0);
+      ps[i] = (float)pS; pr[i] = (float)fmax(pR, 0.0);
+      lpv[i] = (float)lcl;
+      slv[i] = (float)(lraw == lcl ? half : pS - lcl);
+    }
+    store_row<1>(S, R, lc, C - 1, ge, ps, pr);
+    const long o = (lc.grp * TB + lc.t) * (long)NCOL;
+    reinterpret_cast<float4 *>(lp_out + o)[ge.g] = make_float4(lpv[0], lpv[1], lpv[2], lpv[3]);
+    reinterpret_cast<float4 *>(slack_out + o)[ge.g] = make_float4(slv[0], slv[1], slv[2], slv[3]);
+  }
+}
+
 __global__ void abs_kernel(const float *in, float *out, size_t count) {
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   const size_t stride = (size_t)gridDim.x * blockDim.x;
@@ -1237,6 +1460,19 @@ int softmax(State s, int groups, int P, int E, int T, int n, int gps, int pn, co
   TV_REQUIRE(row_geo(n, G, VEC), TV_E_SHAPE, "softmax width %d exceeds %d", n, 4 * 64 * kMaxVec);
   const double C = (double)P * E + 1, rows = (double)groups * T;
   ProfScope prof(K_SOFTMAX, st, 40.0 * rows * C * n, 16.0 * rows * C * n);
+  // small blocks: attention rows of 16 .. 128 scores, gathered to 128 columns per workgroup, held in registers
+  const int per8 = (E + 7) / 8;                      // coefficient rows per thread with 8 row slots
+  if (P == 1 && per8 <= 16 && (n == 16 || n == 32 || n == 64 || n == 128) && T % (128 / n) == 0) {
+    const int TB = T / (128 / n);
+    dim3 gridc((unsigned)(groups * TB));
+#define SMC_LAUNCH(PN)                                                                                            \
+  hipLaunchKernelGGL((softmax_cached_kernel<16, 6, PN>), gridc, dim3(kThreads), 0, st, s.S, s.R, E, TB, n / 4, gps, eps, lp, \
+                     slack, status)
+    NORM_SWITCH(pn, SMC_LAUNCH);
+#undef SMC_LAUNCH
+    TV_HIP(hipGetLastError());
+    return TV_OK;
+  }
   dim3 grid((unsigned)(groups * T)), block(kThreads);
 #define SM_LAUNCH2(V, PN)                                                                                    \
   hipLaunchKernelGGL((softmax_kernel<V, PN>), grid, block, 6 * (size_t)n * sizeof(double), st, s.S, s.R, P, E, T, n, \
