@@ -24,7 +24,7 @@ BF16_SPLIT_PEAK_TF = 2500.0 / 6.0   # dense bf16 peak over the six bf16 products
 # scaled by the counters' readings for the 2^30-byte copy of the same run (2048 and 1024 bytes per unit) and
 # averaged over the launches of one certify call; counters cannot be read inside this process, so the figure is
 # a constant of the workload and is reported only for the workload it was collected on
-PMC_TRAFFIC = {"c2": {"affine_gemm": 422.0e6, "layernorm": 246.6e6, "activation": 371.0e6, "softmax": 126.4e6}}
+PMC_TRAFFIC = {"c2": {"affine_gemm": 407.5e6, "layernorm": 246.8e6, "activation": 492.4e6, "softmax": 247.6e6}}
 MFMA_KINDS = ("affine_gemm", "qk_gemm_x", "qk_gemm_y", "pv_gemm_x", "pv_gemm_y", "head_gemm")
 
 

@@ -1363,8 +1363,10 @@ int activation(int act, CState x, int groups, int P, int E, int T, int n, int gp
   chunk_geo(X, G, nch);
   const double C = (double)P * E + 1;
   ProfScope prof(K_ACTIVATION, st, 12.0 * groups * C * X, 16.0 * groups * C * X);
-  if (P == 1 && X % 64 == 0 && (E + 15) / 16 <= 8) {
-    // small blocks: 16 lanes (64 columns) per row and 16 row slots leave at most 8 rows per thread - read once
+  if (act == TV_ACT_RELU && P == 1 && X % 64 == 0 && (E + 15) / 16 <= 8) {
+    // small blocks: 16 lanes (64 columns) per row and 16 row slots leave at most 8 rows per thread - read once.
+    // ReLU only: with 64 columns per workgroup a wave relaxes 16 columns at a time instead of 64, which a
+    // root search per column (tanh, and GELU's tanh) pays for four times over (measured: 213 us against 132)
     const int Gc = 16, nchc = (int)(X / 64);
     dim3 gridc(groups, nchc), blockc(kThreads);
 #define ACTC_LAUNCH2(ROWS, A, PN)                                                                                   \
@@ -1373,9 +1375,7 @@ int activation(int act, CState x, int groups, int P, int E, int T, int n, int gp
 #define ACTC_LAUNCH(PN)                                                                 \
   do {                                                                                  \
     const bool small = (E + 15) / 16 <= 4;                                              \
-    if (act == TV_ACT_RELU) { if (small) ACTC_LAUNCH2(4, TV_ACT_RELU, PN); else ACTC_LAUNCH2(8, TV_ACT_RELU, PN); } \
-    else if (act == TV_ACT_TANH) { if (small) ACTC_LAUNCH2(4, TV_ACT_TANH, PN); else ACTC_LAUNCH2(8, TV_ACT_TANH, PN); } \
-    else { if (small) ACTC_LAUNCH2(4, TV_ACT_GELU, PN); else ACTC_LAUNCH2(8, TV_ACT_GELU, PN); } \
+    if (small) ACTC_LAUNCH2(4, TV_ACT_RELU, PN); else ACTC_LAUNCH2(8, TV_ACT_RELU, PN);  \
   } while (0)
     NORM_SWITCH(pn, ACTC_LAUNCH);
 #undef ACTC_LAUNCH
