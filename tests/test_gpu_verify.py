@@ -141,17 +141,24 @@ def test_chunked_batch_equals_resident_batch(tv):
     model.close()
 
 
-def test_certify_with_and_without_cached_first_projection(tv):
-    """tv_certify keeps the first layer's q/k/v across probes when the workspace has room; a workspace a few
-    KB short of that recomputes it in every probe and must return the same radii."""
-    w = CONFIGS["c1"]
+@pytest.mark.parametrize("case", ["one_position", "two_positions"])
+def test_certify_with_and_without_cached_first_projection(tv, case):
+    """tv_certify keeps what does not depend on eps across probes when the workspace has room (the first layer's
+    q/k/v, the norms of their concretization, the input state as its generators); a workspace a few KB short of
+    that recomputes everything in every probe and must return the same radii."""
+    if case == "one_position":
+        w, p, hi, steps = CONFIGS["c1"], 2, 0.5, 14
+    else:   # two perturbed positions, l_inf ball, tanh
+        w = scaled(CONFIGS["c3"], n_layers=1, hidden=64, n_heads=2, ffn=128, seq_len=16, max_len=16)
+        p, hi, steps = 0, 0.5, 14
     model = tv.Model(make_model(w))
     tok, pos = dev(make_tokens(w, 4)), dev(make_positions(w, 4))
-    full, _ = model.workspace_query(4, w.seq_len, 1)
-    a = model.certify(tok, pos, 2, 0.0, 0.5, 8, workspace=torch.empty(full, dtype=torch.uint8, device="cuda:0"))
-    b = model.certify(tok, pos, 2, 0.0, 0.5, 8, workspace=torch.empty(full - 4096, dtype=torch.uint8, device="cuda:0"))
+    P = pos.shape[1]
+    full, _ = model.workspace_query(4, w.seq_len, P)
+    a = model.certify(tok, pos, p, 0.0, hi, steps, workspace=torch.empty(full, dtype=torch.uint8, device="cuda:0"))
+    b = model.certify(tok, pos, p, 0.0, hi, steps, workspace=torch.empty(full - 4096, dtype=torch.uint8, device="cuda:0"))
     assert torch.equal(a["eps"], b["eps"]) and torch.equal(a["status"], b["status"])
-    assert float(a["eps"].max()) > 0.0
+    assert float(a["eps"].max()) > 0.0 and float(a["eps"].min()) < hi * (1 - 2.0 ** -steps)
     model.close()
 
 
