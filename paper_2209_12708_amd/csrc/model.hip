@@ -149,23 +149,30 @@ __global__ void copy_i32_kernel(const int32_t *in, int32_t *out, int n) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) out[i] = in[i];
 }
-// bisection state: st[0][b] = lo, st[1][b] = hi
-__global__ void search_init_kernel(float *lohi, int B, float lo, float hi, int32_t *cnt) {
+// bisection state: st[0][b] = lo, st[1][b] = hi; eps = the first probe's mid-point, status cleared for it
+__global__ void search_init_kernel(float *lohi, int B, float lo, float hi, int32_t *cnt, float *eps, int32_t *status) {
   const int b = blockIdx.x * blockDim.x + threadIdx.x;
-  if (b < B) { lohi[b] = lo; lohi[B + b] = hi; cnt[b] = 0; }
+  if (b < B) { lohi[b] = lo; lohi[B + b] = hi; cnt[b] = 0; eps[b] = 0.5f * (lo + hi); status[b] = 0; }
 }
-__global__ void search_mid_kernel(const float *lohi, int B, float *eps) {
-  const int b = blockIdx.x * blockDim.x + threadIdx.x;
-  if (b < B) eps[b] = 0.5f * (lohi[b] + lohi[B + b]);
-}
-__global__ void search_update_kernel(float *lohi, int B, const float *eps, const float *margin, int nm,
-                                     const int32_t *status, int32_t *cnt) {
+// End of a probe in one launch: the decision of head_out_kernel (a non-finite bound or a raised status counts as
+// not verified; verified = every margin's lower bound > 0), the bracket update, and the next probe's mid-point
+// with its status cleared.
+__global__ void probe_end_kernel(const float *l, const float *u, int32_t *status, int B, int n_cls, int NP, float *lohi,
+                                 float *eps, int32_t *cnt) {
   const int b = blockIdx.x * blockDim.x + threadIdx.x;
   if (b >= B) return;
-  bool ok = status[b] == 0;
-  for (int j = 0; j < nm; ++j) ok &= margin[b * nm + j] > 0.f;
-  if (ok) lohi[b] = eps[b]; else lohi[B + b] = eps[b];
-  cnt[b] += status[b] != 0 ? 1 : 0;
+  bool bad = status[b] != 0;
+  for (int o = 0; o < 2 * n_cls - 1; ++o)
+    bad |= !(fabsf(l[b * NP + o]) <= 3.4028234663852886e38f) || !(fabsf(u[b * NP + o]) <= 3.4028234663852886e38f);
+  bool ok = !bad;
+  for (int j = 0; j < n_cls - 1; ++j) ok &= l[b * NP + n_cls + j] > 0.f;
+  const float e = eps[b];
+  float lo = lohi[b], hi = lohi[B + b];
+  if (ok) lo = e; else hi = e;
+  lohi[b] = lo; lohi[B + b] = hi;
+  cnt[b] += bad ? 1 : 0;
+  eps[b] = 0.5f * (lo + hi);
+  status[b] = 0;
 }
 
 __global__ void zero_eps_kernel(float *p, int n) {
@@ -591,24 +598,19 @@ int tv_certify(const tv_model *m, const int32_t *tokens, int B, int L, const int
     const Plan pl = make_plan(m->cfg, Bc, L, P, cache0);
     int32_t *lab = reinterpret_cast<int32_t *>(w + pl.labels), *stat = reinterpret_cast<int32_t *>(w + pl.status);
     int32_t *cnt = reinterpret_cast<int32_t *>(w + pl.cnt);
-    float *eps = w + pl.eps, *lohi = w + pl.lohi, *margin = w + pl.margin;
+    float *eps = w + pl.eps, *lohi = w + pl.lohi;
     const int32_t *tok = tokens + (size_t)b0 * L, *pos = positions + (size_t)b0 * P;
     if (int rc = chunk_labels(m, w, pl, tok, pos, Bc, L, pn, labels ? labels + b0 : nullptr, st)) return rc;
-    hipLaunchKernelGGL(search_init_kernel, dim3(nblk(Bc)), dim3(256), 0, st, lohi, Bc, eps_lo, eps_hi, cnt);
+    hipLaunchKernelGGL(search_init_kernel, dim3(nblk(Bc)), dim3(256), 0, st, lohi, Bc, eps_lo, eps_hi, cnt, eps, stat);
     TV_HIP(hipGetLastError());
     if (cache0)
       if (int rc = project_input(m, pl, w, tok, pos, Bc, L, P, pn, st)) return rc;
     for (int it = 0; it < steps; ++it) {
-      hipLaunchKernelGGL(search_mid_kernel, dim3(nblk(Bc)), dim3(256), 0, st, lohi, Bc, eps);
-      hipLaunchKernelGGL(fill_i32_kernel, dim3(nblk(Bc)), dim3(256), 0, st, stat, Bc, 0);
-      TV_HIP(hipGetLastError());
       if (int rc = sweep(m, pl, w, tok, pos, Bc, L, P, pn, eps, stat, cache0 ? w + pl.qkv0 : nullptr,
                          cache0 ? w + pl.norms0 : nullptr, st)) return rc;
       if (int rc = head(m, pl, w, Bc, L, P, pn, eps, lab, st)) return rc;
-      hipLaunchKernelGGL(head_out_kernel, dim3(nblk(Bc)), dim3(256), 0, st, w + pl.hl, w + pl.hu, stat, lab, Bc, nc,
-                         pl.NP, (float *)nullptr, (float *)nullptr, (float *)nullptr, (int32_t *)nullptr, stat, margin);
-      hipLaunchKernelGGL(search_update_kernel, dim3(nblk(Bc)), dim3(256), 0, st, lohi, Bc, eps, margin, nc - 1, stat,
-                         cnt);
+      hipLaunchKernelGGL(probe_end_kernel, dim3(nblk(Bc)), dim3(256), 0, st, w + pl.hl, w + pl.hu, stat, Bc, nc, pl.NP,
+                         lohi, eps, cnt);
       TV_HIP(hipGetLastError());
     }
     hipLaunchKernelGGL(copy_f32_kernel, dim3(nblk(Bc)), dim3(256), 0, st, lohi, out_eps + b0, Bc);
