@@ -98,8 +98,10 @@ def test_affine(tv, G, T, P, E, K, N, bias, add):
     (5, 1, 1, 33, 24, 20, True, True),        # K below one stage, tiny N
     (1, 2, 1, 300, 128, 128, True, False),    # > 2 M tiles
     (2, 5, 1, 64, 64, 384, True, False),      # T not a power of two, three N tiles
-    (3, 32, 1, 64, 64, 256, True, True),      # T = 32: coefficient rows as whole tiles, bias rows as 32-row pieces
-    (2, 64, 2, 32, 32, 128, True, False),     # the same cut with two pieces of bias rows per group
+    (3, 32, 1, 64, 64, 256, True, True),      # 32 tokens per group
+    (2, 64, 2, 32, 32, 128, True, False),     # 64 tokens per group
+    (8, 32, 1, 128, 128, 256, True, True),    # > 32768 rows: the eight-wave 128 x 128 tiles
+    (4, 32, 2, 128, 64, 128, True, False),    # the same with two perturbed positions
 ])
 def test_affine_split_weights(tv, G, T, P, E, K, N, bias, add):
     """The kernel the encoder sweep uses for constant weights: three bf16 pieces per fp32 operand, six MFMA
