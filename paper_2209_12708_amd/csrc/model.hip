@@ -224,7 +224,6 @@ Plan make_plan(const tv_config &c, int Bc, int L, int P, bool cache0 = false) {
   const size_t C = (size_t)P * D + 1;
   const size_t rows = (size_t)Bc * L;
   size_t o = 0;
-  auto pad32 = [](size_t k) { return (k + 31) / 32 * 32; };
   auto take = [&](size_t n) { size_t r = o; o += align_up(n); return r; };
   Plan p;
   p.NP = (2 * c.n_classes - 1 + 3) / 4 * 4;

@@ -1073,8 +1073,7 @@ void softmax_cached_kernel(float *S, float *R, int nrows, int TB, int seg, int g
   const Loc lc{(long)(blockIdx.x / TB), C, TB, (int)(blockIdx.x % TB), NCOL, 0};
   const int sent = (int)(lc.grp / gps);
   const double e = eps[sent];
-  const int ts = ge.g / seg;                               // token of this lane within the block
-  const int TT = GL / seg;
+  const int ts = ge.g / seg;                               // token of this lane within the block (GL / seg tokens)
   bool bad = false;
 
   // The first RROWS rows of a thread stay in registers, the last LROWS in LDS (its own slots, no exchange): the exp
