@@ -65,25 +65,30 @@ __device__ __forceinline__ double tanh_tangent_through(double end, double lo, do
   TV_NO_CONTRACT
   const double te = tanh(end);
   const double lo0 = lo, hi0 = hi;
+  const double scale = fmax(hi0 - lo0, 1e-300);
   double t = tanh(lo);
   const bool neg_lo = t + (1.0 - t * t) * (end - lo) - te < 0.0;
+  // to leading order g(d) = (end - d)^2 (end + 2 d) / 3: the root of a short interval is near -end / 2
   double d = 0.5 * (lo + hi);
+  if (fabs(end) < 0.5 && -0.5 * end > lo && -0.5 * end < hi) d = -0.5 * end;
   for (int it = 0; it < 64; ++it) {       // far from the root the steps are bisections; near it, Newton's
     t = tanh(d);
     const double s = 1.0 - t * t;
     const double gd = t + s * (end - d) - te;
+    // below the rounding noise of its own terms g says nothing more about the root (intervals under ~1e-5,
+    // where the candidate lines differ by less than 1e-10 in slope)
+    if (fabs(gd) <= 4.5e-16 * (fabs(t) + fabs(te) + s * fabs(end - d))) break;
     if ((gd < 0.0) == neg_lo) lo = d; else hi = d;
     const double dg = -2.0 * t * s * (end - d);
     double dn = d - gd / dg;
     if (!(dn > lo && dn < hi)) dn = 0.5 * (lo + hi);
-    const bool done = fabs(dn - d) <= 4.0e-16 * fmax(1.0, fabs(d));
+    const bool done = fabs(dn - d) <= 1.0e-13 * scale + 4.0e-16 * fmax(1.0, fabs(d));
     d = dn;
     if (done) break;
   }
   // step off the root towards the sound side until g confirms the side
-  const double scale = fmax(hi0 - lo0, 1e-300);
   double step = 1.5e-14 * scale;
-  for (int k = 0; k < 6; ++k, step *= 16.0) {
+  for (int k = 0; k < 12; ++k, step *= 16.0) {   // up to 0.26 of the bracket: past any noise band of g around the root
     const double c = sound_lo ? fmax(d - step, lo0) : fmin(d + step, hi0);
     t = tanh(c);
     const bool neg = t + (1.0 - t * t) * (end - c) - te < 0.0;

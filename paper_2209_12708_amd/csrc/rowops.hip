@@ -364,6 +364,76 @@ __device__ __forceinline__ void relax_columns(const Geo &ge, double e, float (&N
   for (int i = 0; i < 4; ++i) maps[i] = smap[4 * ge.g + i];
 }
 
+// The same relaxation for a workgroup that holds only 64 columns (16 lanes of four): one lane of one wave per
+// column, all 64 lanes busy, instead of four waves relaxing 16 columns each.  Row slot 0 passes the column values
+// through LDS (cin: bias centre, bias radius, norm of the lower line, norm of the upper line); the wave is chosen by
+// the block index so the root searches of neighbouring workgroups land on different SIMDs.
+template <int ACT, typename NormFn>
+__device__ __forceinline__ void relax_columns_by_lane(const Geo &ge, double e, const float (&NL)[4], const float (&NU)[4],
+                                                      const float (&bS)[4], const float (&bR)[4], NormFn second_norms,
+                                                      float (*cin)[kWave], Map2 *smap, LineCoef *slc, int owner_wave,
+                                                      bool &bad) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const bool owner = (int)(threadIdx.x / kWave) == owner_wave && lane < 4 * ge.G;
+  auto publish = [&](const float (&nl)[4], const float (&nu)[4]) {
+    if (ge.slot == 0) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int c = 4 * ge.g + i;
+        cin[0][c] = bS[i]; cin[1][c] = bR[i]; cin[2][c] = nl[i]; cin[3][c] = nu[i];
+      }
+    }
+  };
+  publish(NL, NU);
+  __syncthreads();
+  if (ACT != TV_ACT_GELU) {
+    if (owner) {
+      double l, u;
+      range_of(cin[0][lane], cin[1][lane], e, cin[2][lane], cin[3][lane], l, u);
+      bad |= !(finite_d(l) && finite_d(u));
+      const Line2 ln = ACT == TV_ACT_RELU ? relax_relu(l, u) : relax_tanh(l, u);
+      smap[lane] = form_map(form_sub(form_identity(), ln));
+    }
+  } else {
+    Form fg = form_identity();
+    double lx = 0.0, xS = 0.0, xR = 0.0;
+    if (owner) {
+      double ux;
+      xS = cin[0][lane]; xR = cin[1][lane];
+      range_of(xS, xR, e, cin[2][lane], cin[3][lane], lx, ux);
+      bad |= !(finite_d(lx) && finite_d(ux));
+      double lb, ub;
+      const Form b = gelu_inner(lx, ux, lb, ub);
+      fg = form_mul(form_identity(), b, lx, lb, ub);     // g = x * b
+      slc[lane] = LineCoef{(float)(fg.pL + fg.qL), (float)(fg.qL - fg.pL), (float)(fg.pU + fg.qU),
+                           (float)(fg.pU - fg.qU)};
+    }
+    __syncthreads();
+    LineCoef lcf[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) lcf[i] = slc[4 * ge.g + i];
+    float nl2[4], nu2[4];
+    second_norms(lcf, nl2, nu2);                          // ends with the norms in every row slot
+    publish(nl2, nu2);
+    __syncthreads();
+    if (owner) {
+      // bias values of g's two lines, as centre / radius in double
+      const Form &f = fg;
+      const double gS = 0.5 * ((f.pL + f.qL + f.pU + f.qU) * xS + (-f.pL + f.qL + f.pU - f.qU) * xR + f.cL + f.cU);
+      const double gR = 0.5 * (((f.pU - f.pL) + (f.qU - f.qL)) * xS + ((f.pU + f.pL) - (f.qU + f.qL)) * xR + (f.cU - f.cL));
+      double lg, ug;
+      range_of(gS, gR, e, cin[2][lane], cin[3][lane], lg, ug);
+      bad |= !(finite_d(lg) && finite_d(ug));
+      const Line2 th = relax_tanh(lg, ug);
+      double lt, ut;
+      line_range(th, lg, ug, lt, ut);
+      const Form h = form_sub(form_sub(f, th), 0.5, 0.5, 0.5, 0.5);
+      smap[lane] = form_map(form_mul(form_identity(), h, lx, 0.5 * lt + 0.5, 0.5 * ut + 0.5));
+    }
+  }
+  __syncthreads();
+}
+
 template <int VEC, int ACT, int PN>
 __global__ __launch_bounds__(kThreads) void activation_kernel(const float *S, const float *R, int P, int E, int X,
                                                               int G, int gps, const float *eps,
@@ -399,8 +469,8 @@ __global__ __launch_bounds__(kThreads) void activation_cached_kernel(const float
                                                                      float *Ro, int32_t *status) {
   constexpr int pn = PN;
   __shared__ float red[4 * kWave * 8];
-  __shared__ Map2 smap[4 * kWave];
-  __shared__ LineCoef slc[4 * kWave];
+  __shared__ Map2 smap[kWave];          // one per column of the workgroup
+  __shared__ LineCoef slc[kWave];
   const int chunk = 4 * G, c0 = blockIdx.y * chunk;
   const Geo ge(G, min(chunk, X - c0) / 4);
   const Loc lc{(long)blockIdx.x, nrows + 1, 1, 0, X, c0};
@@ -448,11 +518,17 @@ __global__ __launch_bounds__(kThreads) void activation_cached_kernel(const float
   };
   float NL[4], NU[4];
   norms(nullptr, NL, NU);
-  Map2 maps[4];
   bool bad = false;
   auto second = [&](const LineCoef (&lcf)[4], float (&nl)[4], float (&nu)[4]) { norms(lcf, nl, nu); };
-  relax_columns<ACT>(ge, e, NL, NU, bS, bR, second, smap, slc, maps, bad);
+  __shared__ float cin[4][kWave];
+  relax_columns_by_lane<ACT>(ge, e, NL, NU, bS, bR, second, cin, smap, slc, (int)((blockIdx.x + blockIdx.y) & 3), bad);
   if (bad) status[blockIdx.x / gps] = 1;
+  float msS[4], msR[4], mrS[4], mrR[4];                // the float part of the columns' maps
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const Map2 &mp = smap[4 * ge.g + i];
+    msS[i] = mp.sS; msR[i] = mp.sR; mrS[i] = mp.rS; mrR[i] = mp.rR;
+  }
 
 #pragma unroll
   for (int it = 0; it < ROWS; ++it) {
@@ -461,8 +537,8 @@ __global__ __launch_bounds__(kThreads) void activation_cached_kernel(const float
       float ys[4], yr[4];
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        ys[i] = maps[i].sS * xs[it][i] + maps[i].sR * xr[it][i];
-        yr[i] = maps[i].rS * xs[it][i] + maps[i].rR * xr[it][i];
+        ys[i] = msS[i] * xs[it][i] + msR[i] * xr[it][i];
+        yr[i] = mrS[i] * xs[it][i] + mrR[i] * xr[it][i];
       }
       store_row<1>(So, Ro, lc, r, ge, ys, yr);
     }
@@ -1362,10 +1438,9 @@ int activation(int act, CState x, int groups, int P, int E, int T, int n, int gp
   chunk_geo(X, G, nch);
   const double C = (double)P * E + 1;
   ProfScope prof(K_ACTIVATION, st, 12.0 * groups * C * X, 16.0 * groups * C * X);
-  if (act == TV_ACT_RELU && P == 1 && X % 64 == 0 && (E + 15) / 16 <= 8) {
-    // small blocks: 16 lanes (64 columns) per row and 16 row slots leave at most 8 rows per thread - read once.
-    // ReLU only: with 64 columns per workgroup a wave relaxes 16 columns at a time instead of 64, which a
-    // root search per column (tanh, and GELU's tanh) pays for four times over (measured: 213 us against 132)
+  if (P == 1 && X % 64 == 0 && (E + 15) / 16 <= 8) {
+    // small blocks: 16 lanes (64 columns) per row and 16 row slots leave at most 8 rows per thread - read once;
+    // the 64 columns are relaxed by the 64 lanes of one wave
     const int Gc = 16, nchc = (int)(X / 64);
     dim3 gridc(groups, nchc), blockc(kThreads);
 #define ACTC_LAUNCH2(ROWS, A, PN)                                                                                   \
@@ -1374,7 +1449,9 @@ int activation(int act, CState x, int groups, int P, int E, int T, int n, int gp
 #define ACTC_LAUNCH(PN)                                                                 \
   do {                                                                                  \
     const bool small = (E + 15) / 16 <= 4;                                              \
-    if (small) ACTC_LAUNCH2(4, TV_ACT_RELU, PN); else ACTC_LAUNCH2(8, TV_ACT_RELU, PN);  \
+    if (act == TV_ACT_RELU) { if (small) ACTC_LAUNCH2(4, TV_ACT_RELU, PN); else ACTC_LAUNCH2(8, TV_ACT_RELU, PN); } \
+    else if (act == TV_ACT_TANH) { if (small) ACTC_LAUNCH2(4, TV_ACT_TANH, PN); else ACTC_LAUNCH2(8, TV_ACT_TANH, PN); } \
+    else { if (small) ACTC_LAUNCH2(4, TV_ACT_GELU, PN); else ACTC_LAUNCH2(8, TV_ACT_GELU, PN); } \
   } while (0)
     NORM_SWITCH(pn, ACTC_LAUNCH);
 #undef ACTC_LAUNCH
