@@ -40,6 +40,8 @@ def main():
                     help="leave the per-launch HIP events out of the timed region")
     ap.add_argument("--op-sweep", action="store_true",
                     help="time single operators over sentence length and hidden size instead of the certify benchmark")
+    ap.add_argument("--tile-search", action="store_true",
+                    help="rule-pruned tile search of the affine kernel over the layer shapes of c1..c4 (one JSON line each)")
     ap.add_argument("--probe", action="store_true",
                     help="counter probe: a 1 GiB device copy (known traffic) followed by one verify sweep, no timing")
     args = ap.parse_args()
@@ -51,6 +53,22 @@ def main():
     import torch
     from paper_2209_12708_amd import binding as tv
     from tv_synth import CONFIGS, make_model, make_positions, make_tokens
+
+    if args.tile_search:
+        # Layer shapes (K -> N) of every affine map of a configuration: W_q|W_k|W_v stacked, W_o, W_1, W_2.  c4 is
+        # searched on 8 of its 64 sentences (the tiles only see the row count through the grid size).
+        from paper_2209_12708_amd import tile_search
+        for name, sentences in (("c1", None), ("c2", None), ("c3", None), ("c4", 8)):
+            c = CONFIGS[name]
+            Bn = sentences or c.batch
+            D, F = c.enc.hidden, c.enc.ffn
+            for K, N in ((D, 3 * D), (D, D), (D, F), (F, D)):
+                rec = tile_search.search(Bn, c.n_perturbed, D, c.seq_len, K, N)
+                rec["workload"] = name
+                rec["sentences"] = Bn
+                print(json.dumps({"tile_search": rec}), flush=True)
+                torch.cuda.empty_cache()
+        return
 
     w = CONFIGS[args.workload]
     weights = make_model(w)

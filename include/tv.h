@@ -160,6 +160,22 @@ int tv_op_affine_split(const float *Sx, const float *Rx, int groups, int P, int 
                        const uint16_t *W3, const uint16_t *Wabs3, const float *bias, const float *Sadd,
                        const float *Radd, float *Sy, float *Ry, void *stream);
 
+/* Tile search (paper Sec. 5, rule-pruned candidates that are then timed): the affine kernel is built in
+ * tv_affine_tile_count() tile shapes.  tv_affine_tile_info fills shape[4] = {rows, columns of the output tile,
+ * waves along rows, waves along columns} and the LDS bytes per workgroup, vector registers per lane and scratch
+ * bytes per lane that the loaded code object reports (host pointers; needs a device).
+ * tv_affine_tile_default returns the index the built-in rules choose for a product of M rows, N outputs and
+ * K inputs.  tv_op_affine_split_tile runs both planes in one launch, as a sweep does, with shape `tile`
+ * (-1: the built-in choice): SRx = the two planes [2][groups][C][T][K] (device), W3pair = tv_op_split3 of W
+ * followed by tv_op_split3 of |W| in one buffer, bias2 = [2][N] (the bias, then zeros) or NULL,
+ * SRy = [2][groups][C][T][N].  Every shape gives the same result bit for bit (the order of the sums over K does
+ * not depend on the tile). */
+int tv_affine_tile_count(void);
+int tv_affine_tile_default(long long M, int N, int K);
+int tv_affine_tile_info(int tile, int *shape, int *lds_bytes, int *vgprs, int *scratch_bytes);
+int tv_op_affine_split_tile(const float *SRx, int groups, int P, int E, int T, int K, int N,
+                            const uint16_t *W3pair, const float *bias2, float *SRy, int tile, void *stream);
+
 /* Fused concretize + relaxation + substitution for an activation (paper Sec. 4.1 second pattern,
  * Sec. 4.3): act = TV_ACT_*.  In-place allowed (Sy == Sx, Ry == Rx).  status [groups/groups_per_sentence]
  * is set to 1 on non-finite bounds. */

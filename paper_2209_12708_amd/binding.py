@@ -42,7 +42,8 @@ class _Weights(C.Structure):
 _lib = None
 
 EXPORTS = ("tv_version", "tv_last_error", "tv_model_create", "tv_model_destroy", "tv_workspace_query", "tv_verify",
-           "tv_certify", "tv_op_concretize", "tv_op_abs", "tv_op_affine", "tv_op_split3", "tv_op_affine_split", "tv_probe_mfma", "tv_profile_select", "tv_op_activation", "tv_op_layernorm",
+           "tv_certify", "tv_op_concretize", "tv_op_abs", "tv_op_affine", "tv_op_split3", "tv_op_affine_split", "tv_affine_tile_count", "tv_affine_tile_default",
+           "tv_affine_tile_info", "tv_op_affine_split_tile", "tv_probe_mfma", "tv_profile_select", "tv_op_activation", "tv_op_layernorm",
            "tv_attention_workspace", "tv_op_attention", "tv_profile_enable", "tv_profile_reset",
            "tv_profile_kinds", "tv_profile_get")
 
@@ -72,6 +73,10 @@ def lib():
         L.tv_op_split3.argtypes = [vp, vp, i, i, i, vp]
         L.tv_probe_mfma.argtypes = [i, i, i, vp, C.POINTER(C.c_double), vp]
         L.tv_op_affine_split.argtypes = [vp, vp, i, i, i, i, i, i, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.tv_affine_tile_default.argtypes = [C.c_longlong, i, i]
+        ip = C.POINTER(C.c_int)
+        L.tv_affine_tile_info.argtypes = [i, ip, ip, ip, ip]
+        L.tv_op_affine_split_tile.argtypes = [vp, i, i, i, i, i, i, vp, vp, vp, i, vp]
         L.tv_op_activation.argtypes = [i, vp, vp, i, i, i, i, i, i, i, vp, vp, vp, vp, vp]
         L.tv_op_layernorm.argtypes = [vp, vp, i, i, i, i, i, i, i, vp, vp, vp, f, vp, vp, vp, vp]
         L.tv_op_attention.argtypes = [vp] * 6 + [i] * 6 + [vp] * 5 + [i, vp, vp, sz, vp]
@@ -241,6 +246,42 @@ def op_affine_split(S, R, P, E, W, bias=None, add=None):
                                     _ptr(add[0]) if add else None, _ptr(add[1]) if add else None, _ptr(Sy),
                                     _ptr(Ry), _stream()))
     return Sy, Ry
+
+
+def affine_tile_count():
+    return lib().tv_affine_tile_count()
+
+
+def affine_tile_default(M, N, K):
+    """Index of the tile shape the built-in rules choose for M rows, N outputs, K inputs."""
+    t = lib().tv_affine_tile_default(M, N, K)
+    if t < 0:
+        _check(t)
+    return t
+
+
+def affine_tile_info(tile):
+    """(BM, BN, waves along M, waves along N), LDS bytes per workgroup, VGPRs per lane, scratch bytes per lane."""
+    shape = (C.c_int * 4)()
+    lds, regs, scratch = C.c_int(), C.c_int(), C.c_int()
+    _check(lib().tv_affine_tile_info(tile, shape, C.byref(lds), C.byref(regs), C.byref(scratch)))
+    return tuple(shape), lds.value, regs.value, scratch.value
+
+
+def split3_pair(W):
+    """Pieces of W followed by the pieces of |W| in one buffer: the weight operand of a two-plane launch."""
+    return torch.stack([op_split3(W), op_split3(W, take_abs=True)])
+
+
+def op_affine_split_tile(SR, P, E, W3pair, N, bias2=None, tile=-1, out=None):
+    """Both planes SR [2, G, C, T, K] through the affine kernel in tile shape `tile` (-1: built-in choice)."""
+    two, G, Cc, T, K = SR.shape
+    assert two == 2
+    if out is None:
+        out = torch.empty(2, G, Cc, T, N, dtype=torch.float32, device=SR.device)
+    _check(lib().tv_op_affine_split_tile(_ptr(SR), G, P, E, T, K, N, _ptr(W3pair), _ptr(bias2), _ptr(out), tile,
+                                         _stream()))
+    return out
 
 
 def op_activation(act, S, R, P, E, groups_per_sentence, p_norm, eps, inplace=False):

@@ -332,6 +332,13 @@ int launch3(const Affine3Args &g, int planes, hipStream_t st) {
   return TV_OK;
 }
 
+// Every instantiated shape of the kernel: the candidates of the tile search (paper Sec. 5), in the order of the
+// switch in affine_split().
+struct TileShape { int BM, BN, WM, WN; };
+constexpr TileShape kTiles[] = {{128, 64, 2, 2}, {128, 128, 2, 2}, {128, 128, 4, 2}, {64, 128, 2, 2},
+                                {128, 128, 2, 4}, {64, 64, 2, 2}, {64, 128, 2, 4}};
+constexpr int kTileCount = sizeof(kTiles) / sizeof(kTiles[0]);
+
 }  // namespace
 
 int mfma_probe(int bf16, int workgroups, int iters, float *out, double *flops, hipStream_t st) {
@@ -357,7 +364,7 @@ int split_bf16x3(const float *in, unsigned short *out, int N, int K, bool take_a
 
 int affine_split(const float *xS, long xplane, long M, int C, int T, int K, int N, const unsigned short *W3pair,
                  const float *bpair, const float *addS, long addplane, float *yS, long yplane, hipStream_t st, int planes,
-                 const float *in_x0, const int32_t *in_pos, int in_P) {
+                 const float *in_x0, const int32_t *in_pos, int in_P, int tile) {
   TV_REQUIRE(planes == 1 || planes == 2, TV_E_ARG, "affine: planes must be 1 or 2");
   TV_REQUIRE(xS && W3pair && yS, TV_E_NULL, "affine: null operand");
   TV_REQUIRE(M > 0 && M < (1L << 31) && N > 0 && K > 0 && K % 8 == 0, TV_E_SHAPE,
@@ -376,14 +383,52 @@ int affine_split(const float *xS, long xplane, long M, int C, int T, int K, int 
   const double mn = (double)M * N;
   ProfScope prof(K_AFFINE, st, planes * 2.0 * mn * K,
                  planes * 4.0 * ((double)M * K + (double)N * K + mn * (addS ? 2.0 : 1.0)));   // the input-state residual is not counted: it reads M N / C values
-  const bool big = M >= 128 * 256;
-  if (N <= 64) return launch3<128, 64, 2, 2>(g, planes, st);
-  // wide layers: 64 x 64 per wave halves the LDS traffic per MFMA (measured +4..13 % from K = 256, N = 512 up)
-  if (K >= 256 && N >= 512 && big) return launch3<128, 128, 2, 2>(g, planes, st);
-  // many rows, narrow layers: eight waves on a 128 x 128 tile fetch the weight pieces once per 128 rows and keep
-  // 16 waves per CU resident (measured +2..7 % against four waves on 64 x 128)
-  if (big) return launch3<128, 128, 4, 2>(g, planes, st);
-  return launch3<64, 128, 2, 2>(g, planes, st);
+  if (tile < 0) tile = affine_tile_default(M, N, K);
+  TV_REQUIRE(tile < kTileCount, TV_E_ARG, "affine: tile %d of %d", tile, kTileCount);
+  switch (tile) {
+    case 0: return launch3<128, 64, 2, 2>(g, planes, st);
+    case 1: return launch3<128, 128, 2, 2>(g, planes, st);
+    case 2: return launch3<128, 128, 4, 2>(g, planes, st);
+    case 3: return launch3<64, 128, 2, 2>(g, planes, st);
+    case 4: return launch3<128, 128, 2, 4>(g, planes, st);
+    case 5: return launch3<64, 64, 2, 2>(g, planes, st);
+    default: return launch3<64, 128, 2, 4>(g, planes, st);
+  }
+}
+
+int affine_tile_count() { return kTileCount; }
+
+// The shape the built-in rules pick (from measured sweeps; the tile search re-measures them).
+int affine_tile_default(long M, int N, int K) {
+  if (N <= 64) return 0;
+  // many rows: eight waves on a 128 x 128 tile fetch the weight pieces once per 128 rows and keep 16 waves per CU
+  // resident; the tile search puts it first or within 1 % of the first on every layer of the configurations with
+  // 32768 rows or more (four waves on the same tile, 64 x 64 per wave, lose 1.5..4 % from K = 256 up)
+  if (M >= 128 * 256) return 2;
+  return 3;
+}
+
+int affine_tile_info(int tile, int *shape, int *lds_bytes, int *vgprs, int *scratch_bytes) {
+  TV_REQUIRE(tile >= 0 && tile < kTileCount, TV_E_ARG, "affine: tile %d of %d", tile, kTileCount);
+  TV_REQUIRE(shape && lds_bytes && vgprs && scratch_bytes, TV_E_NULL, "affine_tile_info: null pointer");
+  const void *fn = nullptr;
+  switch (tile) {
+    case 0: fn = (const void *)affine3_kernel<128, 64, 2, 2, 1, 1>; break;
+    case 1: fn = (const void *)affine3_kernel<128, 128, 2, 2, 1, 1>; break;
+    case 2: fn = (const void *)affine3_kernel<128, 128, 4, 2, 1, 1>; break;
+    case 3: fn = (const void *)affine3_kernel<64, 128, 2, 2, 1, 1>; break;
+    case 4: fn = (const void *)affine3_kernel<128, 128, 2, 4, 1, 1>; break;
+    case 5: fn = (const void *)affine3_kernel<64, 64, 2, 2, 1, 1>; break;
+    default: fn = (const void *)affine3_kernel<64, 128, 2, 4, 1, 1>; break;
+  }
+  const TileShape &t = kTiles[tile];
+  shape[0] = t.BM; shape[1] = t.BN; shape[2] = t.WM; shape[3] = t.WN;
+  hipFuncAttributes at;
+  TV_HIP(hipFuncGetAttributes(&at, fn));
+  *lds_bytes = (int)at.sharedSizeBytes;
+  *vgprs = at.numRegs;
+  *scratch_bytes = (int)at.localSizeBytes;
+  return TV_OK;
 }
 
 }  // namespace tv

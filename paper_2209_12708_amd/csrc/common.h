@@ -97,7 +97,14 @@ int split_bf16x3(const float *in, unsigned short *out, int N, int K, bool take_a
 // and the perturbed positions [groups][in_P] instead of as stored planes (then addS must be null and C = in_P N + 1).
 int affine_split(const float *xS, long xplane, long M, int C, int T, int K, int N, const unsigned short *W3pair,
                  const float *bpair, const float *addS, long addplane, float *yS, long yplane, hipStream_t st,
-                 int planes = 2, const float *in_x0 = nullptr, const int32_t *in_pos = nullptr, int in_P = 0);
+                 int planes = 2, const float *in_x0 = nullptr, const int32_t *in_pos = nullptr, int in_P = 0,
+                 int tile = -1);
+// The tile shapes affine_split() can run (candidates of the tile search, paper Sec. 5): tile < 0 above takes
+// affine_tile_default().  affine_tile_info: shape = {BM, BN, waves along M, waves along N}; LDS bytes per workgroup,
+// vector registers per lane and scratch bytes per lane as the loaded code object reports them (needs a device).
+int affine_tile_count();
+int affine_tile_default(long M, int N, int K);
+int affine_tile_info(int tile, int *shape, int *lds_bytes, int *vgprs, int *scratch_bytes);
 
 // ---- elementwise / reduction kernels (rowops.hip) ------------------------------------------
 // States are [groups][C][T][n]; eps is indexed by group / gps (groups per sentence).

@@ -712,6 +712,30 @@ int tv_op_affine_split(const float *Sx, const float *Rx, int groups, int P, int 
   return affine_split(Rx, 0, M, C, T, K, N, Wabs3, nullptr, Radd, 0, Ry, 0, st, 1);
 }
 
+int tv_affine_tile_count(void) { return affine_tile_count(); }
+
+int tv_affine_tile_default(long long M, int N, int K) {
+  TV_REQUIRE(M > 0 && N > 0 && K > 0, TV_E_SHAPE, "tv_affine_tile_default: empty shape");
+  return affine_tile_default((long)M, N, K);
+}
+
+int tv_affine_tile_info(int tile, int *shape, int *lds_bytes, int *vgprs, int *scratch_bytes) {
+  return affine_tile_info(tile, shape, lds_bytes, vgprs, scratch_bytes);
+}
+
+int tv_op_affine_split_tile(const float *SRx, int groups, int P, int E, int T, int K, int N, const uint16_t *W3pair,
+                            const float *bias2, float *SRy, int tile, void *stream) {
+  TV_REQUIRE(SRx && W3pair && SRy, TV_E_NULL, "tv_op_affine_split_tile: null pointer");
+  TV_REQUIRE(groups > 0 && P >= 0 && E > 0 && T > 0 && K > 0 && N > 0 && K % 8 == 0 && N % 4 == 0, TV_E_SHAPE,
+             "tv_op_affine_split_tile: bad shape groups=%d P=%d E=%d T=%d K=%d N=%d", groups, P, E, T, K, N);
+  TV_REQUIRE(tile >= -1 && tile < affine_tile_count(), TV_E_ARG, "tv_op_affine_split_tile: tile %d of %d", tile,
+             affine_tile_count());
+  const int C = P * E + 1;
+  const long M = (long)groups * C * T;
+  return affine_split(SRx, M * K, M, C, T, K, N, W3pair, bias2, nullptr, 0, SRy, M * N,
+                      static_cast<hipStream_t>(stream), 2, nullptr, nullptr, 0, tile);
+}
+
 int tv_op_activation(int act, const float *Sx, const float *Rx, int groups, int P, int E, int T, int n, int gps, int pn,
                      const float *eps, float *Sy, float *Ry, int32_t *status, void *stream) {
   return activation(act, CState{Sx, Rx}, groups, P, E, T, n, gps, pn, eps, State{Sy, Ry}, status,

@@ -1,0 +1,147 @@
+"""Rule-pruned tile search for the affine contraction (paper Sec. 5, without the learned cost model).
+
+The paper prunes candidate implementations with hard rules (hardware limits: violating them means spilling or a
+launch that cannot run) and weighs them by soft rules (trade-offs between work per workgroup and workgroups per
+processor) taken from a per-GPU "metafile", then profiles the survivors.  Here the candidates are the tile shapes the
+affine kernel is built in, their LDS / register / scratch use comes from the loaded code object, the metafile is
+GFX950 below, and since only a handful of shapes survive they are all timed instead of ranked by a model first.
+
+The rules themselves (`hard_rule_violations`, `soft_features`, `prune`) are plain host logic; only `time_tile`
+and `search` touch the GPU.
+"""
+from dataclasses import dataclass
+
+# metafile of one MI355X: limits for the hard rules, unit counts for the soft ones
+GFX950 = {
+    "compute_units": 256,
+    "simds_per_cu": 4,
+    "wave": 64,
+    "lds_per_cu": 160 * 1024,
+    "lds_per_workgroup": 160 * 1024,     # one workgroup may take the whole LDS of its compute unit
+    "vgprs_per_lane": 512,               # unified vector register file of one SIMD, per lane
+    "vgpr_granule": 8,
+    "max_waves_per_simd": 8,
+    "max_threads_per_workgroup": 1024,
+}
+
+
+@dataclass(frozen=True)
+class Candidate:
+    tile: int
+    BM: int
+    BN: int
+    WM: int
+    WN: int
+    lds: int
+    vgprs: int
+    scratch: int
+
+    @property
+    def waves(self):
+        return self.WM * self.WN
+
+
+def hard_rule_violations(c, hw=GFX950):
+    """Names of the hardware limits candidate c breaks (empty: it may run)."""
+    bad = []
+    if c.scratch > 0:
+        bad.append("register spilling")
+    if c.lds > hw["lds_per_workgroup"]:
+        bad.append("LDS per workgroup")
+    if c.vgprs > hw["vgprs_per_lane"]:
+        bad.append("vector registers per lane")
+    if c.waves * hw["wave"] > hw["max_threads_per_workgroup"]:
+        bad.append("threads per workgroup")
+    return bad
+
+
+def resident_workgroups(c, hw=GFX950):
+    """Workgroups of candidate c one compute unit holds at once (LDS and registers decide)."""
+    g = hw["vgpr_granule"]
+    regs = max(g, (c.vgprs + g - 1) // g * g)
+    waves_per_simd = min(hw["max_waves_per_simd"], hw["vgprs_per_lane"] // regs)
+    by_regs = waves_per_simd * hw["simds_per_cu"] // c.waves
+    by_lds = hw["lds_per_cu"] // max(c.lds, 1)
+    return max(0, min(by_regs, by_lds))
+
+
+def soft_features(c, M, N, planes=2, hw=GFX950):
+    """The trade-offs of a candidate on a product of M rows and N outputs:
+    useful = fraction of the computed tile area that is output; workgroups; rounds = how many times the grid fills
+    the chip's resident slots (below 1 the chip is not full); waves_per_cu = latency-hiding capacity."""
+    mt, nt = -(-M // c.BM), -(-N // c.BN)
+    wgs = mt * nt * planes
+    res = resident_workgroups(c, hw)
+    slots = max(1, res * hw["compute_units"])
+    return {"useful": (M * N) / (mt * c.BM * nt * c.BN), "workgroups": wgs, "rounds": wgs / slots,
+            "waves_per_cu": res * c.waves}
+
+
+def prune(cands, M, N, planes=2, hw=GFX950, min_useful=0.6):
+    """Hard rules drop a candidate outright.  Soft rule: a shape that wastes more than 1 - min_useful of its tile
+    area on padding is dropped when some other surviving shape does not.  Returns (kept, dropped[(cand, why)])."""
+    kept, dropped = [], []
+    for c in cands:
+        bad = hard_rule_violations(c, hw)
+        if bad or resident_workgroups(c, hw) == 0:
+            dropped.append((c, "hard: " + ", ".join(bad or ["does not fit a compute unit"])))
+        else:
+            kept.append(c)
+    useful = {c.tile: soft_features(c, M, N, planes, hw)["useful"] for c in kept}
+    if any(u >= min_useful for u in useful.values()):
+        for c in list(kept):
+            if useful[c.tile] < min_useful:
+                kept.remove(c)
+                dropped.append((c, f"soft: {100 * (1 - useful[c.tile]):.0f} % of the tile area is padding"))
+    return kept, dropped
+
+
+def candidates():
+    """The tile shapes of the loaded library with the resources its code object reports (needs a GPU)."""
+    from . import binding as tv
+    out = []
+    for t in range(tv.affine_tile_count()):
+        (BM, BN, WM, WN), lds, regs, scratch = tv.affine_tile_info(t)
+        out.append(Candidate(t, BM, BN, WM, WN, lds, regs, scratch))
+    return out
+
+
+def time_tile(tile, SR, P, E, W3pair, N, out, warmup=2, iters=8):
+    """Average microseconds of one two-plane launch in tile shape `tile` (HIP events on the current stream)."""
+    import torch
+    from . import binding as tv
+    for _ in range(warmup):
+        tv.op_affine_split_tile(SR, P, E, W3pair, N, tile=tile, out=out)
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(iters):
+        tv.op_affine_split_tile(SR, P, E, W3pair, N, tile=tile, out=out)
+    b.record()
+    b.synchronize()
+    return a.elapsed_time(b) * 1e3 / iters
+
+
+def search(groups, P, E, T, K, N, seed=0, hw=GFX950):
+    """Prune, time the survivors on a synthetic state [2][groups][P E + 1][T][K], return a record with the ranking,
+    the dropped shapes and the shape the built-in rules choose."""
+    import torch
+    from . import binding as tv
+    C = P * E + 1
+    M = groups * C * T
+    gen = torch.Generator(device="cuda").manual_seed(seed)
+    SR = torch.randn(2, groups, C, T, K, device="cuda", generator=gen)
+    SR[1].abs_()
+    W = torch.randn(N, K, device="cuda", generator=gen) * 0.02
+    W3pair = tv.split3_pair(W)
+    out = torch.empty(2, groups, C, T, N, device="cuda")
+    kept, dropped = prune(candidates(), M, N, 2, hw)
+    timed = []
+    for c in kept:
+        us = time_tile(c.tile, SR, P, E, W3pair, N, out)
+        f = soft_features(c, M, N, 2, hw)
+        timed.append({"tile": c.tile, "shape": [c.BM, c.BN, c.WM, c.WN], "lds": c.lds, "vgprs": c.vgprs,
+                      "us": round(us, 1), "useful": round(f["useful"], 3), "rounds": round(f["rounds"], 2),
+                      "waves_per_cu": f["waves_per_cu"]})
+    timed.sort(key=lambda r: r["us"])
+    return {"M": M, "K": K, "N": N, "default": tv.affine_tile_default(M, N, K), "ranking": timed,
+            "dropped": [{"tile": c.tile, "shape": [c.BM, c.BN, c.WM, c.WN], "why": why} for c, why in dropped]}

@@ -121,6 +121,32 @@ def test_affine_split_weights(tv, G, T, P, E, K, N, bias, add):
     assert_state_close(host(out), Y, "affine (split weights)")
 
 
+def test_every_tile_shape_computes_the_same_affine_map(tv):
+    """Candidates of the tile search (paper Sec. 5): each instantiated shape passes the hard rules as loaded, gives
+    Eq. (2) to the oracle's tolerance, and agrees with the built-in choice bit for bit."""
+    from paper_2209_12708_amd import tile_search as ts
+    cands = ts.candidates()
+    assert len(cands) == tv.affine_tile_count() >= 4
+    for c in cands:
+        assert ts.hard_rule_violations(c) == [] and c.vgprs > 0 and c.lds > 0 and ts.resident_workgroups(c) >= 1
+    for (G, T, P, E, K, N) in ((3, 20, 1, 32, 64, 96), (2, 37, 2, 16, 40, 200)):
+        rng = np.random.default_rng(G + T + K + N)
+        X = quantize(random_state(rng, (G * T, K), P, E, 0.3, 2), G)
+        W = rng.standard_normal((N, K)).astype(np.float32)
+        c = rng.standard_normal(N).astype(np.float32)
+        Y = B.affine(X, W.astype(np.float64), c.astype(np.float64))
+        S, R = planes_dev(X, G)
+        SR = torch.stack([S, R])
+        W3 = tv.split3_pair(dev(W))
+        b2 = dev(np.stack([c, np.zeros_like(c)]))
+        ref = tv.op_affine_split_tile(SR, P, E, W3, N, bias2=b2, tile=-1)
+        assert_state_close(host((ref[0], ref[1])), Y, "affine (built-in tile)")
+        assert 0 <= tv.affine_tile_default(G * (P * E + 1) * T, N, K) < len(cands)
+        for cd in cands:
+            out = tv.op_affine_split_tile(SR, P, E, W3, N, bias2=b2, tile=cd.tile)
+            assert torch.equal(out, ref), f"tile {cd.tile} {cd.BM}x{cd.BN} differs from the built-in choice"
+
+
 def test_split3_pieces_sum_to_the_input(tv):
     rng = np.random.default_rng(5)
     N, K = 96, 40                                   # K is padded to 64 in the staged layout

@@ -1,0 +1,47 @@
+"""Host logic of the rule-pruned tile search (paper Sec. 5: hard rules drop candidates that break a hardware
+limit, soft rules weigh padding against parallelism).  That every tile shape computes the same affine map is a
+GPU test beside the other operator tests."""
+import pytest
+
+from paper_2209_12708_amd import tile_search as ts
+
+
+def cand(tile, BM, BN, WM, WN, lds=40000, vgprs=96, scratch=0):
+    return ts.Candidate(tile, BM, BN, WM, WN, lds, vgprs, scratch)
+
+
+def test_hard_rules_name_the_broken_limit():
+    assert ts.hard_rule_violations(cand(0, 128, 128, 2, 2)) == []
+    assert ts.hard_rule_violations(cand(0, 128, 128, 2, 2, scratch=16)) == ["register spilling"]
+    assert ts.hard_rule_violations(cand(0, 256, 256, 2, 2, lds=200 * 1024)) == ["LDS per workgroup"]
+    assert ts.hard_rule_violations(cand(0, 128, 128, 2, 2, vgprs=600)) == ["vector registers per lane"]
+    assert ts.hard_rule_violations(cand(0, 512, 512, 8, 4)) == ["threads per workgroup"]
+
+
+def test_resident_workgroups_take_the_tighter_of_lds_and_registers():
+    # 67584 bytes of LDS: two workgroups per compute unit, whatever the registers allow
+    assert ts.resident_workgroups(cand(0, 128, 128, 4, 2, lds=67584, vgprs=98)) == 2
+    # 232 registers: two waves per SIMD = eight waves per unit = two workgroups of four waves; LDS would allow five
+    assert ts.resident_workgroups(cand(0, 128, 128, 2, 2, lds=30000, vgprs=232)) == 2
+    # 68 registers round up to 72: seven waves per SIMD, 28 per unit, three workgroups of eight waves (LDS: three)
+    assert ts.resident_workgroups(cand(0, 64, 128, 2, 4, lds=46080, vgprs=68)) == 3
+
+
+def test_soft_features_count_padding_and_fill():
+    c = cand(0, 128, 128, 2, 2, lds=67584, vgprs=232)
+    f = ts.soft_features(c, M=4128, N=64, planes=2)
+    assert f["workgroups"] == 33 * 1 * 2
+    assert f["useful"] == pytest.approx(4128 * 64 / (33 * 128 * 128))
+    assert f["rounds"] == pytest.approx(66 / (2 * 256))
+    assert f["waves_per_cu"] == 8
+
+
+def test_prune_drops_hard_failures_and_padded_shapes_but_never_everything():
+    cands = [cand(0, 128, 64, 2, 2), cand(1, 128, 128, 2, 2), cand(2, 128, 128, 2, 2, scratch=8)]
+    kept, dropped = ts.prune(cands, M=4096, N=64)
+    assert [c.tile for c in kept] == [0]
+    why = {c.tile: w for c, w in dropped}
+    assert why[2].startswith("hard: register spilling") and why[1].startswith("soft:")
+    # when every shape pads heavily the soft rule keeps them all
+    kept, dropped = ts.prune([cand(1, 128, 128, 2, 2), cand(3, 64, 128, 2, 2)], M=4096, N=32)
+    assert [c.tile for c in kept] == [1, 3] and dropped == []
