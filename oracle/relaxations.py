@@ -55,6 +55,27 @@ def relu(l, u):
     return kL, cL, kU, cU
 
 
+def leaky_relu(alpha):
+    """Leaky ReLU f(x) = x (x >= 0), alpha x (x < 0) with 0 <= alpha <= 1 (convex; one of the further activations
+    the paper's operator list names, Sec. 4.1).  Same design as ReLU: identity when l >= 0, the line alpha x when
+    u <= 0; crossing: upper = chord through (l, alpha l), (u, u); lower = k x with k = 1 if u >= -l else alpha
+    (both support the function at 0).  alpha = 0 is ReLU."""
+    assert 0.0 <= alpha <= 1.0
+
+    def fn(l, u):
+        l = np.asarray(l, np.float64); u = np.asarray(u, np.float64)
+        pos = l >= 0
+        neg = (u <= 0) & ~pos
+        cross = ~pos & ~neg
+        den = np.where(cross, u - l, 1.0)
+        kc = (u - alpha * l) / den
+        kU = np.where(pos, 1.0, np.where(neg, alpha, kc))
+        cU = np.where(cross, (alpha - 1.0) * l * u / den, 0.0)
+        kL = np.where(pos, 1.0, np.where(neg, alpha, np.where(u >= -l, 1.0, alpha)))
+        return kL, np.zeros_like(kL), kU, cU
+    return fn
+
+
 def _dtanh(x):
     t = np.tanh(x)
     return 1.0 - t * t

@@ -25,7 +25,7 @@ import numpy as np
 from . import bounds as B
 from . import relaxations as rx
 
-ACT_RELU, ACT_TANH, ACT_GELU = 0, 1, 2
+ACT_RELU, ACT_TANH, ACT_GELU, ACT_LEAKY_RELU, ACT_SILU = 0, 1, 2, 3, 4
 FLT_MAX = 3.4028234663852886e38
 RECIP_MIN = 1e-12        # domain guard of the reciprocal relaxation
 GELU_C = 0.044715
@@ -120,11 +120,26 @@ def gelu_bound(X, ctx):
     return B.product(X, Hh, lx, lh, uh)
 
 
-def activation_bound(X, act, ctx):
+def silu_bound(X, ctx):
+    """SiLU y = x * sigmoid(x) with sigmoid(x) = 0.5 (1 + tanh(x / 2)), as a chain of relaxations in the manner of
+    the GELU chain: affine (x / 2) -> tanh -> affine -> product with x."""
+    lx, ux = ctx.conc(X)
+    Hx = B.scale_shift(X, 0.5)
+    lh, uh = ctx.conc(Hx)
+    T = B.relax(Hx, rx.tanh, lh, uh)
+    G = B.scale_shift(T, 0.5, 0.5)
+    lg, ug = ctx.conc(G)
+    return B.product(X, G, lx, lg, ug)
+
+
+def activation_bound(X, act, ctx, alpha=0.01):
     if act == ACT_GELU:
         return gelu_bound(X, ctx)
+    if act == ACT_SILU:
+        return silu_bound(X, ctx)
     l, u = ctx.conc(X)
-    return B.relax(X, rx.relu if act == ACT_RELU else rx.tanh, l, u)
+    fn = {ACT_RELU: rx.relu, ACT_TANH: rx.tanh, ACT_LEAKY_RELU: rx.leaky_relu(alpha)}[act]
+    return B.relax(X, fn, l, u)
 
 
 def attention_bound(X, m, layer, ctx):
@@ -169,7 +184,7 @@ def encoder_bounds(m, tokens, positions, p, eps, trace=None):
         ctx.rec(f"l{layer}.x1", X1)
         Hd = B.affine(X1, g("W1"), g("b1"))
         ctx.rec(f"l{layer}.h", Hd)
-        Act = activation_bound(Hd, cfg.activation, ctx)
+        Act = activation_bound(Hd, cfg.activation, ctx, getattr(cfg, "act_alpha", 0.01))
         ctx.rec(f"l{layer}.act", Act)
         F = B.add(B.affine(Act, g("W2"), g("b2")), X1)
         X = layernorm_bound(F, g("ln2_g"), g("ln2_b"), cfg.ln_eps, ctx)

@@ -9,7 +9,7 @@ import math
 import numpy as np
 import torch
 
-ACT_RELU, ACT_TANH, ACT_GELU = 0, 1, 2
+ACT_RELU, ACT_TANH, ACT_GELU, ACT_LEAKY_RELU, ACT_SILU = 0, 1, 2, 3, 4
 
 
 def _t(a):
@@ -28,11 +28,15 @@ def _ln(x, g, b, eps):
     return xc / torch.sqrt(var + eps) * g + b
 
 
-def _act(x, kind):
+def _act(x, kind, alpha=0.01):
     if kind == ACT_RELU:
         return torch.relu(x)
     if kind == ACT_TANH:
         return torch.tanh(x)
+    if kind == ACT_LEAKY_RELU:
+        return torch.where(x >= 0, x, alpha * x)
+    if kind == ACT_SILU:
+        return x / (1.0 + torch.exp(-x))
     return 0.5 * x * (1.0 + torch.tanh(math.sqrt(2.0 / math.pi) * (x + 0.044715 * x ** 3)))
 
 
@@ -53,7 +57,7 @@ def encoder(m, x):
         o = (p @ v).transpose(-2, -3).reshape(x.shape)
         a = x + o @ w("Wo").T + w("bo")
         x1 = _ln(a, w("ln1_g"), w("ln1_b"), cfg.ln_eps)
-        h = _act(x1 @ w("W1").T + w("b1"), cfg.activation)
+        h = _act(x1 @ w("W1").T + w("b1"), cfg.activation, cfg.act_alpha)
         f = x1 + h @ w("W2").T + w("b2")
         x = _ln(f, w("ln2_g"), w("ln2_b"), cfg.ln_eps)
     return x

@@ -179,6 +179,28 @@ def test_gelu_rule_sound(p):
 
 
 @pytest.mark.parametrize("p", [0, 2, 1])
+def test_silu_and_leaky_relu_rules_sound(p):
+    rng = np.random.default_rng(750 + p)
+    eps = 0.4
+    X = Sampled(rng, (60,), eps, p, bscale=2.0)
+    d = deltas(rng, p, eps)
+    x = X.values(rng, d)
+    ctx = _Ctx(eps, P_, p)
+    wid_s, rng_s = check(V.silu_bound(X.state, ctx), x / (1 + np.exp(-x)), d, "silu")
+    assert wid_s < 20 * rng_s                      # and not vacuous
+    out = V.activation_bound(X.state, V.ACT_LEAKY_RELU, ctx, alpha=0.2)
+    check(out, np.where(x >= 0, x, 0.2 * x), d, "leaky relu")
+    # the chain collapses to the exact tangent of x sigmoid(x) on a point interval (one neuron, eps = 0)
+    x0 = np.array([-3.0, -1.2, 0.0, 0.7, 4.0])
+    Pt = B.Bounds(np.ones((5, PE)), x0, np.ones((5, PE)), x0)
+    Y = V.silu_bound(Pt, _Ctx(0.0, P_, p))
+    sg = 1 / (1 + np.exp(-x0))
+    np.testing.assert_allclose(Y.lb, x0 * sg, rtol=1e-12, atol=1e-14); np.testing.assert_allclose(Y.ub, Y.lb, rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(Y.lw[:, 0], sg + x0 * sg * (1 - sg), rtol=1e-10)
+    np.testing.assert_allclose(Y.uw, Y.lw, rtol=1e-10, atol=1e-14)
+
+
+@pytest.mark.parametrize("p", [0, 2, 1])
 def test_bilinear_rules_sound_single_term(p):
     """One contracted index: no slack from other terms hides a wrong plane or a wrong side."""
     rng = np.random.default_rng(800 + p)

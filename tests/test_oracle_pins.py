@@ -21,7 +21,7 @@ from tv_synth.generate import randomize_layernorm
 
 def tiny(act=0, layers=1, D=16, H=2, F=24, L=5, P=1, stress=6.0, seed=0):
     w = scaled(CONFIGS["c1"], n_layers=layers, hidden=D, n_heads=H, ffn=F, activation=act, seq_len=L,
-               n_perturbed=P, vocab=50, max_len=16)
+               n_perturbed=P, vocab=50, max_len=16, act_alpha=0.1)
     m = randomize_layernorm(make_model(w, seed_offset=seed, stress=stress), seed)
     return w, m, make_tokens(w, 2, seed)[0], make_positions(w, 1)[0]
 
@@ -76,7 +76,7 @@ def test_p1_sign_split_mixes_bounds():
 
 
 # ---------------------------------------------------------------- P2 / P3
-@pytest.mark.parametrize("act", [0, 1, 2])
+@pytest.mark.parametrize("act", [0, 1, 2, 3, 4])
 def test_p2_p3_eps0_forward_and_jacobian(act):
     w, m, tokens, _ = tiny(act=act, layers=2, P=2)
     positions = [1, 3]
@@ -104,7 +104,8 @@ def test_p2_p3_eps0_forward_and_jacobian(act):
 
 # ---------------------------------------------------------------- P6
 @pytest.mark.parametrize("act,p,P,eps", [(0, 2, 1, 0.005), (0, 0, 2, 0.0008), (0, 1, 1, 0.008),
-                                         (1, 0, 2, 0.0008), (1, 2, 1, 0.005), (2, 0, 2, 0.0008), (2, 2, 1, 0.005)])
+                                         (1, 0, 2, 0.0008), (1, 2, 1, 0.005), (2, 0, 2, 0.0008), (2, 2, 1, 0.005),
+                                         (3, 2, 1, 0.005), (3, 0, 2, 0.0008), (4, 2, 1, 0.005), (4, 0, 2, 0.0008)])
 def test_p6_sampling_soundness(act, p, P, eps):
     w, m, tokens, _ = tiny(act=act, layers=2, P=P)
     positions = [1, 3][:P]

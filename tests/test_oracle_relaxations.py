@@ -12,6 +12,7 @@ from oracle import relaxations as rx
 RNG = np.random.default_rng(12345)
 FUNCS = {
     "relu": (rx.relu, lambda x: np.maximum(x, 0.0), (-3, 3)),
+    "leaky_relu": (rx.leaky_relu(0.1), lambda x: np.where(x >= 0, x, 0.1 * x), (-3, 3)),
     "tanh": (rx.tanh, np.tanh, (-4, 4)),
     "exp": (rx.exp, np.exp, (-6, 3)),
     "reciprocal": (rx.reciprocal, lambda x: 1.0 / x, (0.05, 5)),
@@ -59,6 +60,28 @@ def test_relu_cases_exact():
     assert list(kL) == [1, 0, 1]
     np.testing.assert_allclose(kU, [2 / 3, 1 / 3, 0.5])
     np.testing.assert_allclose(cU, [2 / 3, 2 / 3, 0.5])
+
+
+def test_leaky_relu_cases_exact():
+    a = 0.25
+    fn = rx.leaky_relu(a)
+    # one-sided: the function's own line
+    kL, cL, kU, cU = fn(np.array([0.0, 0.5, -2.0, -1.0]), np.array([1.0, 2.0, -0.5, 0.0]))
+    assert list(kL) == [1, 1, a, a] and list(kU) == [1, 1, a, a] and not cL.any() and not cU.any()
+    # crossing: chord through (l, a l), (u, u); lower slope 1 iff u >= -l (tie -> 1), else a; no intercept
+    l, u = np.array([-1.0, -2.0, -1.0]), np.array([2.0, 1.0, 1.0])
+    kL, cL, kU, cU = fn(l, u)
+    assert list(kL) == [1, a, 1] and not cL.any()
+    np.testing.assert_allclose(kU * l + cU, a * l, atol=1e-15)
+    np.testing.assert_allclose(kU * u + cU, u, atol=1e-15)
+    np.testing.assert_allclose(kU, [(2 + a) / 3, (1 + 2 * a) / 3, (1 + a) / 2])
+    # the two ends of the family: alpha = 0 is ReLU line for line, alpha = 1 the identity
+    l, u = _intervals(-3, 3)
+    for got, ref in zip(rx.leaky_relu(0.0)(l, u), rx.relu(l, u)):
+        np.testing.assert_array_equal(got, ref)
+    kL, cL, kU, cU = rx.leaky_relu(1.0)(l, u)
+    np.testing.assert_allclose(kL, 1.0); np.testing.assert_allclose(kU, 1.0)
+    np.testing.assert_allclose(cL, 0.0); np.testing.assert_allclose(cU, 0.0, atol=1e-15)
 
 
 def test_chords_and_tangents_closed_form():

@@ -7,7 +7,7 @@ vocabulary, class count) take the defaults documented next to each field.
 """
 from dataclasses import dataclass, replace
 
-ACT_RELU, ACT_TANH, ACT_GELU = 0, 1, 2
+ACT_RELU, ACT_TANH, ACT_GELU, ACT_LEAKY_RELU, ACT_SILU = 0, 1, 2, 3, 4
 NORM_L1, NORM_L2, NORM_LINF = 1, 2, 0   # p of the perturbation ball; 0 encodes infinity
 
 
@@ -22,6 +22,7 @@ class EncoderConfig:
     max_len: int = 128
     n_classes: int = 2
     ln_eps: float = 1e-5
+    act_alpha: float = 0.01   # slope of the leaky ReLU on x < 0 (read by that activation only)
 
 
 @dataclass(frozen=True)
