@@ -118,8 +118,8 @@ def main():
             rec["affine_us"] = round(us, 1)
             rec["affine_TFLOPs"] = round(2 * 2.0 * Bn * C * L * D * D / us / 1e6, 1)
             rec["affine_GBps"] = round(2 * byts / us / 1e3, 0)
-            for act, nm in ((0, "relu"), (1, "tanh")):
-                us = timed(lambda: tv.op_activation(act, x[0], x[1], 1, D, 1, p, eps))
+            for act, nm in ((0, "relu"), (1, "tanh"), (3, "leaky_relu"), (4, "silu")):
+                us = timed(lambda: tv.op_activation(act, x[0], x[1], 1, D, 1, p, eps, act_alpha=0.01))
                 rec[nm + "_us"] = round(us, 1)
                 rec[nm + "_GBps"] = round(2 * byts / us / 1e3, 0)
             if D % 4 == 0 and (D // 4) % 4 == 0:

@@ -52,12 +52,16 @@ extern "C" {
 #define TV_ACT_RELU 0
 #define TV_ACT_TANH 1
 #define TV_ACT_GELU 2        /* tanh-form GELU, relaxed as square/product/tanh/product chain */
+#define TV_ACT_LEAKY_RELU 3  /* x (x >= 0), act_alpha x (x < 0), 0 <= act_alpha <= 1: ReLU's two designs with the
+                                line act_alpha x in place of 0 (further activations of the operator list, Sec. 4.1) */
+#define TV_ACT_SILU 4        /* x sigmoid(x), relaxed as the chain x/2 -> tanh -> 0.5 t + 0.5 -> product with x */
 
 typedef struct tv_model tv_model;
 
 typedef struct {
   int32_t n_layers, hidden, n_heads, ffn, vocab, max_len, n_classes, activation;
   float ln_eps;
+  float act_alpha;           /* slope of TV_ACT_LEAKY_RELU on x < 0; other activations ignore it */
 } tv_config;
 
 /* Linear weights are [out][in] (Y[j] = sum_i W[j][i] X[i] + b[j]). */
@@ -95,7 +99,7 @@ void tv_model_destroy(tv_model *m);
 int tv_workspace_query(const tv_model *m, int B, int L, int P, size_t *bytes_full, size_t *bytes_min);
 
 /* Bounds on the logits over the perturbation set (forward bound propagation: Eq. (2) for affine
- * layers, relaxation rules for ReLU/tanh/GELU, dot products, softmax and LayerNorm, Eq. (1) at the
+ * layers, relaxation rules for ReLU/tanh/GELU/leaky ReLU/SiLU, dot products, softmax and LayerNorm, Eq. (1) at the
  * output).
  *   tokens    [B][L] int32 in [0, vocab);  positions [B][P] int32, distinct, in [0, L), L % 4 == 0
  *   p_norm    1, 2 or TV_NORM_INF: each perturbed embedding moves in its own l_p ball of radius eps[b]
@@ -177,11 +181,11 @@ int tv_op_affine_split_tile(const float *SRx, int groups, int P, int E, int T, i
                             const uint16_t *W3pair, const float *bias2, float *SRy, int tile, void *stream);
 
 /* Fused concretize + relaxation + substitution for an activation (paper Sec. 4.1 second pattern,
- * Sec. 4.3): act = TV_ACT_*.  In-place allowed (Sy == Sx, Ry == Rx).  status [groups/groups_per_sentence]
+ * Sec. 4.3): act = TV_ACT_*, act_alpha as in tv_config.  In-place allowed (Sy == Sx, Ry == Rx).  status [groups/groups_per_sentence]
  * is set to 1 on non-finite bounds. */
 int tv_op_activation(int act, const float *Sx, const float *Rx, int groups, int P, int E, int T, int n,
                      int groups_per_sentence, int p_norm, const float *eps, float *Sy, float *Ry,
-                     int32_t *status, void *stream);
+                     int32_t *status, float act_alpha, void *stream);
 
 /* Full LayerNorm bound over the neuron axis (centre, square, mean, sqrt, reciprocal, product,
  * gamma/beta).  x: [groups][C][T][n] -> y same shape, must not alias. */

@@ -13,7 +13,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "lib", "libtv.so")
 
 NORM_INF = 0
-ACT_RELU, ACT_TANH, ACT_GELU = 0, 1, 2
+ACT_RELU, ACT_TANH, ACT_GELU, ACT_LEAKY_RELU, ACT_SILU = 0, 1, 2, 3, 4
 
 
 class TvError(RuntimeError):
@@ -23,7 +23,7 @@ class TvError(RuntimeError):
 class _Config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in
                 ("n_layers", "hidden", "n_heads", "ffn", "vocab", "max_len", "n_classes", "activation")] + \
-               [("ln_eps", C.c_float)]
+               [("ln_eps", C.c_float), ("act_alpha", C.c_float)]
 
 
 _LAYER_FIELDS = ("Wq", "bq", "Wk", "bk", "Wv", "bv", "Wo", "bo", "ln1_g", "ln1_b", "W1", "b1", "W2", "b2",
@@ -77,7 +77,7 @@ def lib():
         ip = C.POINTER(C.c_int)
         L.tv_affine_tile_info.argtypes = [i, ip, ip, ip, ip]
         L.tv_op_affine_split_tile.argtypes = [vp, i, i, i, i, i, i, vp, vp, vp, i, vp]
-        L.tv_op_activation.argtypes = [i, vp, vp, i, i, i, i, i, i, i, vp, vp, vp, vp, vp]
+        L.tv_op_activation.argtypes = [i, vp, vp, i, i, i, i, i, i, i, vp, vp, vp, vp, f, vp]
         L.tv_op_layernorm.argtypes = [vp, vp, i, i, i, i, i, i, i, vp, vp, vp, f, vp, vp, vp, vp]
         L.tv_op_attention.argtypes = [vp] * 6 + [i] * 6 + [vp] * 5 + [i, vp, vp, sz, vp]
         L.tv_profile_enable.argtypes = [i]
@@ -116,7 +116,7 @@ class Model:
         self.device = torch.device(device)
         torch.cuda.set_device(self.device)
         c = _Config(cfg.n_layers, cfg.hidden, cfg.n_heads, cfg.ffn, cfg.vocab, cfg.max_len, cfg.n_classes,
-                    cfg.activation, cfg.ln_eps)
+                    cfg.activation, cfg.ln_eps, getattr(cfg, "act_alpha", 0.01))
         keep = []
 
         def host(a):
@@ -284,12 +284,12 @@ def op_affine_split_tile(SR, P, E, W3pair, N, bias2=None, tile=-1, out=None):
     return out
 
 
-def op_activation(act, S, R, P, E, groups_per_sentence, p_norm, eps, inplace=False):
+def op_activation(act, S, R, P, E, groups_per_sentence, p_norm, eps, inplace=False, act_alpha=0.01):
     G, Cc, T, n = S.shape
     Sy, Ry = (S, R) if inplace else (torch.empty_like(S), torch.empty_like(R))
     status = torch.zeros(G // groups_per_sentence, dtype=torch.int32, device=S.device)
     _check(lib().tv_op_activation(act, _ptr(S), _ptr(R), G, P, E, T, n, groups_per_sentence, p_norm, _ptr(eps),
-                                  _ptr(Sy), _ptr(Ry), _ptr(status), _stream()))
+                                  _ptr(Sy), _ptr(Ry), _ptr(status), act_alpha, _stream()))
     return Sy, Ry, status
 
 

@@ -117,8 +117,9 @@ int concretize(CState x, int groups, int P, int E, int T, int n, int gps, int p_
 // to concretize mode 1 on the state they came from
 int ranges_from_norms(const float *norms, int groups, int T, int n, int gps, const float *eps, float *mid, float *half,
                       float *slack, hipStream_t st);
+// alpha: slope of the leaky ReLU on x < 0 (read by that activation only)
 int activation(int act, CState x, int groups, int P, int E, int T, int n, int gps, int p_norm, const float *eps,
-               State y, int32_t *status, hipStream_t st);
+               State y, int32_t *status, hipStream_t st, float alpha = 0.01f);
 int layernorm(CState x, int groups, int P, int E, int T, int n, int gps, int p_norm, const float *eps,
               const float *gamma, const float *beta, float ln_eps, State y, int32_t *status, hipStream_t st);
 // in place; also writes lp = clamp(lower bound of p, 0, 1) and slack = S_p_b - lp, both [groups][T][n]

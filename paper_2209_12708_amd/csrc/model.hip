@@ -354,7 +354,7 @@ int sweep(const tv_model *m, const Plan &pl, float *w, const int32_t *tokens, co
     // feed-forward: h = x' W1^T + b1 ; act ; f = act W2^T + b2 + x' ; x'' = LN(f)
     if (int rc = affine(X, pD, M, C, L, D, F, lw.W1, lw.W13, lw.b1, nullptr, 0, BIG, pF, st)) return rc;
     if (int rc = activation(c.activation, CState{BIG, BIG + pF}, Bc, P, D, L, F, 1, pn, eps,
-                            State{BIG, BIG + pF}, status, st)) return rc;
+                            State{BIG, BIG + pF}, status, st, c.act_alpha)) return rc;
     if (int rc = affine(BIG, pF, M, C, L, F, D, lw.W2, lw.W23, lw.b2, X, pD, T1, pD, st)) return rc;
     if (int rc = layernorm(CState{T1, T1 + pD}, Bc, P, D, L, D, 1, pn, eps, lw.ln2_g, lw.ln2_b, c.ln_eps,
                            State{X, X + pD}, status, st)) return rc;
@@ -444,8 +444,11 @@ int tv_model_create(const tv_config *cfg, const tv_weights *w, tv_model **out) {
              TV_E_SHAPE, "tv_model_create: hidden %% n_heads == 0 and hidden, ffn, head width multiples of 4 required");
   TV_REQUIRE(c.hidden <= 1024, TV_E_SHAPE, "tv_model_create: hidden > 1024 not supported");
   TV_REQUIRE(c.n_classes >= 2 && c.n_classes <= 16, TV_E_SHAPE, "tv_model_create: n_classes must be in [2, 16]");
-  TV_REQUIRE(c.activation == TV_ACT_RELU || c.activation == TV_ACT_TANH || c.activation == TV_ACT_GELU, TV_E_ARG,
+  TV_REQUIRE(c.activation == TV_ACT_RELU || c.activation == TV_ACT_TANH || c.activation == TV_ACT_GELU ||
+                 c.activation == TV_ACT_LEAKY_RELU || c.activation == TV_ACT_SILU, TV_E_ARG,
              "tv_model_create: unknown activation %d", c.activation);
+  TV_REQUIRE(c.activation != TV_ACT_LEAKY_RELU || (c.act_alpha >= 0.f && c.act_alpha <= 1.f), TV_E_ARG,
+             "tv_model_create: act_alpha %g outside [0, 1]", (double)c.act_alpha);
   TV_REQUIRE(c.ln_eps > 0.f, TV_E_ARG, "tv_model_create: ln_eps must be positive");
   TV_REQUIRE(w->tok_emb && w->pos_emb && w->Wc && w->bc, TV_E_NULL, "tv_model_create: null weight array");
   for (int l = 0; l < c.n_layers; ++l) {
@@ -737,9 +740,9 @@ int tv_op_affine_split_tile(const float *SRx, int groups, int P, int E, int T, i
 }
 
 int tv_op_activation(int act, const float *Sx, const float *Rx, int groups, int P, int E, int T, int n, int gps, int pn,
-                     const float *eps, float *Sy, float *Ry, int32_t *status, void *stream) {
+                     const float *eps, float *Sy, float *Ry, int32_t *status, float act_alpha, void *stream) {
   return activation(act, CState{Sx, Rx}, groups, P, E, T, n, gps, pn, eps, State{Sy, Ry}, status,
-                    static_cast<hipStream_t>(stream));
+                    static_cast<hipStream_t>(stream), act_alpha);
 }
 
 int tv_op_layernorm(const float *Sx, const float *Rx, int groups, int P, int E, int T, int n, int gps, int pn,

@@ -55,6 +55,21 @@ __device__ __forceinline__ Line2 relax_relu(double l, double u) {
   return r;
 }
 
+// Leaky ReLU x (x >= 0), a x (x < 0) with 0 <= a <= 1, convex: the design of ReLU with the line a x in place of 0
+// (upper = chord through (l, a l), (u, u); lower = the steeper or the flatter branch, whichever end is farther).
+__device__ __forceinline__ Line2 relax_leaky_relu(double l, double u, double a) {
+  TV_NO_CONTRACT
+  Line2 r;
+  if (l >= 0.0) { r.kL = r.kU = 1.0; r.cL = r.cU = 0.0; }
+  else if (u <= 0.0) { r.kL = r.kU = a; r.cL = r.cU = 0.0; }
+  else {
+    const double den = u - l;
+    r.kU = (u - a * l) / den; r.cU = (a - 1.0) * l * u / den;
+    r.kL = (u >= -l) ? 1.0 : a; r.cL = 0.0;
+  }
+  return r;
+}
+
 // tangent point d in [lo, hi] whose tangent passes through (end, tanh end): the root of
 //   g(d) = tanh d + (1 - tanh^2 d)(end - d) - tanh end,      g'(d) = -2 tanh d (1 - tanh^2 d)(end - d),
 // which changes sign once on the bracket.  Returned on the sound side of the root (towards lo for the lower line,
@@ -211,6 +226,19 @@ __device__ __forceinline__ void line_range(const Line2 &ln, double ly, double uy
   TV_NO_CONTRACT
   lz = (ln.kL >= 0.0 ? ln.kL * ly : ln.kL * uy) + ln.cL;
   uz = (ln.kU >= 0.0 ? ln.kU * uy : ln.kU * ly) + ln.cU;
+}
+
+// SiLU x sigmoid(x) with sigmoid(x) = 0.5 (1 + tanh(x / 2)) as a chain on one neuron: x / 2 -> tanh -> 0.5 t + 0.5 ->
+// product with x.  Every link is a function of x alone, so the chain is one form in x.
+__device__ __forceinline__ Form silu_form(double l, double u) {
+  TV_NO_CONTRACT
+  const double lh = 0.5 * l, uh = 0.5 * u;
+  const Line2 th = relax_tanh(lh, uh);
+  double lt, ut;
+  line_range(th, lh, uh, lt, ut);
+  const Form half = form_sub(form_identity(), 0.5, 0.0, 0.5, 0.0);
+  const Form sg = form_sub(form_sub(half, th), 0.5, 0.5, 0.5, 0.5);
+  return form_mul(form_identity(), sg, l, 0.5 * lt + 0.5, 0.5 * ut + 0.5);
 }
 
 // centre/radius map of a form:  S_y = sS*S + sR*R + sC [bias row],  R_y = rS*S + rR*R + rC [bias row].

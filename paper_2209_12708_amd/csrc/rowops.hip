@@ -302,6 +302,16 @@ __device__ __forceinline__ Form gelu_inner(double lx, double ux, double &lb, dou
   return form_sub(a, k * c3, k, k * c3, k);
 }
 
+// The activations whose relaxation is a function of the neuron's own range alone (all but GELU), as a form in x.
+// alpha: slope of the leaky ReLU on x < 0.
+template <int ACT>
+__device__ __forceinline__ Form single_form(double l, double u, double alpha) {
+  if (ACT == TV_ACT_SILU) return silu_form(l, u);
+  const Line2 ln = ACT == TV_ACT_RELU ? relax_relu(l, u)
+                   : ACT == TV_ACT_TANH ? relax_tanh(l, u) : relax_leaky_relu(l, u, alpha);
+  return form_sub(form_identity(), ln);
+}
+
 // Relaxation of this thread's four columns from their norms and bias values, as centre / radius maps.
 // Every row slot holds the same norms for the same columns.  The relaxation of a column (double precision; a root
 // search for tanh) is computed once: four row slots, one in each wave, take one column of each float4 group each
@@ -309,7 +319,7 @@ __device__ __forceinline__ Form gelu_inner(double lx, double ux, double &lb, dou
 template <int ACT, typename NormFn>
 __device__ __forceinline__ void relax_columns(const Geo &ge, double e, float (&NL)[4], float (&NU)[4],
                                               const float (&bS)[4], const float (&bR)[4], NormFn second_norms,
-                                              Map2 *smap, LineCoef *slc, Map2 (&maps)[4], bool &bad) {
+                                              Map2 *smap, LineCoef *slc, Map2 (&maps)[4], bool &bad, double alpha) {
   const int own = ge.NS / 4;     // column i belongs to row slot i * NS / 4: one owner per wave when a wave holds several slots
   if (ACT != TV_ACT_GELU) {
 #pragma unroll
@@ -318,8 +328,7 @@ __device__ __forceinline__ void relax_columns(const Geo &ge, double e, float (&N
       double l, u;
       range_of(bS[i], bR[i], e, NL[i], NU[i], l, u);
       bad |= !(finite_d(l) && finite_d(u));
-      const Line2 ln = ACT == TV_ACT_RELU ? relax_relu(l, u) : relax_tanh(l, u);
-      smap[4 * ge.g + i] = form_map(form_sub(form_identity(), ln));
+      smap[4 * ge.g + i] = form_map(single_form<ACT>(l, u, alpha));
     }
   } else {
     Form fg = form_identity();                // of this thread's own column
@@ -372,7 +381,7 @@ template <int ACT, typename NormFn>
 __device__ __forceinline__ void relax_columns_by_lane(const Geo &ge, double e, const float (&NL)[4], const float (&NU)[4],
                                                       const float (&bS)[4], const float (&bR)[4], NormFn second_norms,
                                                       float (*cin)[kWave], Map2 *smap, LineCoef *slc, int owner_wave,
-                                                      bool &bad) {
+                                                      bool &bad, double alpha) {
   const int lane = threadIdx.x & (kWave - 1);
   const bool owner = (int)(threadIdx.x / kWave) == owner_wave && lane < 4 * ge.G;
   auto publish = [&](const float (&nl)[4], const float (&nu)[4]) {
@@ -391,8 +400,7 @@ __device__ __forceinline__ void relax_columns_by_lane(const Geo &ge, double e, c
       double l, u;
       range_of(cin[0][lane], cin[1][lane], e, cin[2][lane], cin[3][lane], l, u);
       bad |= !(finite_d(l) && finite_d(u));
-      const Line2 ln = ACT == TV_ACT_RELU ? relax_relu(l, u) : relax_tanh(l, u);
-      smap[lane] = form_map(form_sub(form_identity(), ln));
+      smap[lane] = form_map(single_form<ACT>(l, u, alpha));
     }
   } else {
     Form fg = form_identity();
@@ -437,7 +445,7 @@ __device__ __forceinline__ void relax_columns_by_lane(const Geo &ge, double e, c
 template <int VEC, int ACT, int PN>
 __global__ __launch_bounds__(kThreads) void activation_kernel(const float *S, const float *R, int P, int E, int X,
                                                               int G, int gps, const float *eps,
-                                                              float *So, float *Ro, int32_t *status) {
+                                                              float *So, float *Ro, int32_t *status, float alpha) {
   constexpr int pn = PN;
   static_assert(VEC == 1, "one float4 group per lane");
   __shared__ float red[4 * kWave * 8 * VEC];
@@ -455,7 +463,7 @@ __global__ __launch_bounds__(kThreads) void activation_kernel(const float *S, co
     float s0[4], r0[4];
     column_norms<VEC>(S, R, lc, P, E, ge, pn, lcf, red, nl, nu, s0, r0);
   };
-  relax_columns<ACT>(ge, e, NL, NU, bS, bR, second, smap, slc, maps, bad);
+  relax_columns<ACT>(ge, e, NL, NU, bS, bR, second, smap, slc, maps, bad, (double)alpha);
   if (bad) status[blockIdx.x / gps] = 1;
   apply_maps<VEC>(S, R, So, Ro, lc, ge, maps);
 }
@@ -466,7 +474,7 @@ __global__ __launch_bounds__(kThreads) void activation_kernel(const float *S, co
 template <int ROWS, int ACT, int PN>
 __global__ __launch_bounds__(kThreads) void activation_cached_kernel(const float *S, const float *R, int nrows, int X,
                                                                      int G, int gps, const float *eps, float *So,
-                                                                     float *Ro, int32_t *status) {
+                                                                     float *Ro, int32_t *status, float alpha) {
   constexpr int pn = PN;
   __shared__ float red[4 * kWave * 8];
   __shared__ Map2 smap[kWave];          // one per column of the workgroup
@@ -521,7 +529,8 @@ __global__ __launch_bounds__(kThreads) void activation_cached_kernel(const float
   bool bad = false;
   auto second = [&](const LineCoef (&lcf)[4], float (&nl)[4], float (&nu)[4]) { norms(lcf, nl, nu); };
   __shared__ float cin[4][kWave];
-  relax_columns_by_lane<ACT>(ge, e, NL, NU, bS, bR, second, cin, smap, slc, (int)((blockIdx.x + blockIdx.y) & 3), bad);
+  relax_columns_by_lane<ACT>(ge, e, NL, NU, bS, bR, second, cin, smap, slc, (int)((blockIdx.x + blockIdx.y) & 3), bad,
+                             (double)alpha);
   if (bad) status[blockIdx.x / gps] = 1;
   float msS[4], msR[4], mrS[4], mrR[4];                // the float part of the columns' maps
 #pragma unroll
@@ -1429,51 +1438,64 @@ int concretize(CState x, int groups, int P, int E, int T, int n, int gps, int pn
 }
 
 int activation(int act, CState x, int groups, int P, int E, int T, int n, int gps, int pn, const float *eps, State y,
-               int32_t *status, hipStream_t st) {
+               int32_t *status, hipStream_t st, float alpha) {
   if (int rc = check_common(x.S, x.R, groups, P, E, T, n, gps, pn, eps)) return rc;
   TV_REQUIRE(y.S && y.R && status, TV_E_NULL, "null output");
-  TV_REQUIRE(act == TV_ACT_RELU || act == TV_ACT_TANH || act == TV_ACT_GELU, TV_E_ARG, "unknown activation %d", act);
+  TV_REQUIRE(act == TV_ACT_RELU || act == TV_ACT_TANH || act == TV_ACT_GELU || act == TV_ACT_LEAKY_RELU ||
+                 act == TV_ACT_SILU, TV_E_ARG, "unknown activation %d", act);
+  TV_REQUIRE(act != TV_ACT_LEAKY_RELU || (alpha >= 0.f && alpha <= 1.f), TV_E_ARG,
+             "leaky ReLU slope %g outside [0, 1]", (double)alpha);
   const long X = (long)T * n;
   int G, nch;
   chunk_geo(X, G, nch);
   const double C = (double)P * E + 1;
   ProfScope prof(K_ACTIVATION, st, 12.0 * groups * C * X, 16.0 * groups * C * X);
+// one instantiation per activation: M(A) is expanded with the activation as a compile-time constant
+#define ACT_SWITCH(M)                                  \
+  do {                                                 \
+    switch (act) {                                     \
+      case TV_ACT_RELU: M(TV_ACT_RELU); break;         \
+      case TV_ACT_TANH: M(TV_ACT_TANH); break;         \
+      case TV_ACT_GELU: M(TV_ACT_GELU); break;         \
+      case TV_ACT_LEAKY_RELU: M(TV_ACT_LEAKY_RELU); break; \
+      default: M(TV_ACT_SILU); break;                  \
+    }                                                  \
+  } while (0)
   if (P == 1 && X % 64 == 0 && (E + 15) / 16 <= 8) {
     // small blocks: 16 lanes (64 columns) per row and 16 row slots leave at most 8 rows per thread - read once;
     // the 64 columns are relaxed by the 64 lanes of one wave
     const int Gc = 16, nchc = (int)(X / 64);
     dim3 gridc(groups, nchc), blockc(kThreads);
+    const bool small = (E + 15) / 16 <= 4;
 #define ACTC_LAUNCH2(ROWS, A, PN)                                                                                   \
   hipLaunchKernelGGL((activation_cached_kernel<ROWS, A, PN>), gridc, blockc, 0, st, x.S, x.R, E, (int)X, Gc, gps, eps, \
-                     y.S, y.R, status)
-#define ACTC_LAUNCH(PN)                                                                 \
-  do {                                                                                  \
-    const bool small = (E + 15) / 16 <= 4;                                              \
-    if (act == TV_ACT_RELU) { if (small) ACTC_LAUNCH2(4, TV_ACT_RELU, PN); else ACTC_LAUNCH2(8, TV_ACT_RELU, PN); } \
-    else if (act == TV_ACT_TANH) { if (small) ACTC_LAUNCH2(4, TV_ACT_TANH, PN); else ACTC_LAUNCH2(8, TV_ACT_TANH, PN); } \
-    else { if (small) ACTC_LAUNCH2(4, TV_ACT_GELU, PN); else ACTC_LAUNCH2(8, TV_ACT_GELU, PN); } \
+                     y.S, y.R, status, alpha)
+#define ACTC_ONE(A) do { if (small) ACTC_LAUNCH2(4, A, PN_); else ACTC_LAUNCH2(8, A, PN_); } while (0)
+#define ACTC_LAUNCH(PN)                \
+  do {                                 \
+    constexpr int PN_ = PN;            \
+    ACT_SWITCH(ACTC_ONE);              \
   } while (0)
     NORM_SWITCH(pn, ACTC_LAUNCH);
 #undef ACTC_LAUNCH
+#undef ACTC_ONE
 #undef ACTC_LAUNCH2
     TV_HIP(hipGetLastError());
     return TV_OK;
   }
   dim3 grid(groups, nch), block(kThreads);
-#define ACT_LAUNCH(PN)                                                                                              \
-  do {                                                                                                              \
-    if (act == TV_ACT_RELU)                                                                                         \
-      hipLaunchKernelGGL((activation_kernel<1, TV_ACT_RELU, PN>), grid, block, 0, st, x.S, x.R, P, E, (int)X, G, gps, \
-                         eps, y.S, y.R, status);                                                                    \
-    else if (act == TV_ACT_TANH)                                                                                    \
-      hipLaunchKernelGGL((activation_kernel<1, TV_ACT_TANH, PN>), grid, block, 0, st, x.S, x.R, P, E, (int)X, G, gps, \
-                         eps, y.S, y.R, status);                                                                    \
-    else                                                                                                            \
-      hipLaunchKernelGGL((activation_kernel<1, TV_ACT_GELU, PN>), grid, block, 0, st, x.S, x.R, P, E, (int)X, G, gps, \
-                         eps, y.S, y.R, status);                                                                    \
+#define ACT_ONE(A)                                                                                                  \
+  hipLaunchKernelGGL((activation_kernel<1, A, PN_>), grid, block, 0, st, x.S, x.R, P, E, (int)X, G, gps, eps, y.S, \
+                     y.R, status, alpha)
+#define ACT_LAUNCH(PN)                 \
+  do {                                 \
+    constexpr int PN_ = PN;            \
+    ACT_SWITCH(ACT_ONE);               \
   } while (0)
   NORM_SWITCH(pn, ACT_LAUNCH);
 #undef ACT_LAUNCH
+#undef ACT_ONE
+#undef ACT_SWITCH
   TV_HIP(hipGetLastError());
   return TV_OK;
 }

@@ -41,6 +41,7 @@ def host(pair):
 
 
 NORMS = [0, 2, 1]
+ALPHA = 0.1      # leaky ReLU slope of the operator tests
 
 
 @pytest.mark.parametrize("p", NORMS)
@@ -165,7 +166,7 @@ def test_split3_pieces_sum_to_the_input(tv):
 
 
 @pytest.mark.parametrize("p", NORMS)
-@pytest.mark.parametrize("act,name", [(0, "relu"), (1, "tanh"), (2, "gelu")])
+@pytest.mark.parametrize("act,name", [(0, "relu"), (1, "tanh"), (2, "gelu"), (3, "leaky_relu"), (4, "silu")])
 @pytest.mark.parametrize("shape", [(2, 3, 2, 24, 192), (2, 2, 1, 100, 96)])   # streaming kernel / register-resident kernel
 def test_activation(tv, act, name, p, shape):
     rng = np.random.default_rng(7 + act + 10 * p)
@@ -177,17 +178,17 @@ def test_activation(tv, act, name, p, shape):
     X.lb[:, 8:16] -= 6.0; X.ub[:, 8:16] -= 6.0
     X = quantize(X, G)
     ctx = _Ctx(eps, P, p)
-    ref = V.activation_bound(X, act, ctx)
+    ref = V.activation_bound(X, act, ctx, alpha=ALPHA)
     S, R = planes_dev(X, G)
-    Sy, Ry, status = tv.op_activation(act, S, R, P, E, gps, p, dev(np.full(G // gps, eps)))
+    Sy, Ry, status = tv.op_activation(act, S, R, P, E, gps, p, dev(np.full(G // gps, eps)), act_alpha=ALPHA)
     assert int(status.sum()) == 0
     assert_state_close(host((Sy, Ry)), ref, name, rtol=2e-4, atol_scale=5e-6)
     # in place gives the same result
-    S2, R2, _ = tv.op_activation(act, S, R, P, E, gps, p, dev(np.full(G // gps, eps)), inplace=True)
+    S2, R2, _ = tv.op_activation(act, S, R, P, E, gps, p, dev(np.full(G // gps, eps)), inplace=True, act_alpha=ALPHA)
     assert torch.equal(S2, Sy) and torch.equal(R2, Ry)
 
 
-@pytest.mark.parametrize("act,name", [(0, "relu"), (1, "tanh"), (2, "gelu")])
+@pytest.mark.parametrize("act,name", [(0, "relu"), (1, "tanh"), (2, "gelu"), (3, "leaky_relu"), (4, "silu")])
 def test_activation_narrow_intervals(tv, act, name):
     """Intervals far narrower than fp32 resolves on their end points (width 1e-6 of the value): the
     radius plane of the output must still match (per-neuron scalars are computed in double)."""
@@ -195,8 +196,8 @@ def test_activation_narrow_intervals(tv, act, name):
     G, T, P, E, n = 1, 2, 1, 16, 64
     eps = 1e-6
     X = quantize(random_state(rng, (G * T, n), P, E, eps, 2, wscale=0.3, slack=1e-7, spread=1e-3), G)
-    ref = V.activation_bound(X, act, _Ctx(eps, P, 2))
-    Sy, Ry, _ = tv.op_activation(act, *planes_dev(X, G), P, E, 1, 2, dev(np.full(G, eps)))
+    ref = V.activation_bound(X, act, _Ctx(eps, P, 2), alpha=ALPHA)
+    Sy, Ry, _ = tv.op_activation(act, *planes_dev(X, G), P, E, 1, 2, dev(np.full(G, eps)), act_alpha=ALPHA)
     assert_state_close(host((Sy, Ry)), ref, name + "/narrow", rtol=2e-4, atol_scale=1e-6)
     # the radius plane alone, relative to its own scale
     _, r_ref = to_planes(ref, G)
@@ -209,7 +210,7 @@ def test_activation_eps0_is_exact(tv):
     rng = np.random.default_rng(3)
     G, T, P, E, n = 1, 2, 1, 16, 64
     X = quantize(random_state(rng, (G * T, n), P, E, 0.0, 2, slack=0.0, spread=0.0), G)
-    for act in (1, 2):
+    for act in (1, 2, 4):
         ref = V.activation_bound(X, act, _Ctx(0.0, P, 2))
         Sy, Ry, _ = tv.op_activation(act, *planes_dev(X, G), P, E, 1, 2, dev(np.zeros(1)))
         assert_state_close(host((Sy, Ry)), ref, f"act{act}@0", rtol=2e-4, atol_scale=5e-6)

@@ -112,6 +112,27 @@ def test_gelu_small(tv):
     run_case(tv, w, m, 0, [1e-6, 1e-5], 3, 2, steps=6, cert_range=(0.0, 4e-5), rtol=5e-4)
 
 
+@pytest.mark.parametrize("act,alpha", [(3, 0.1), (3, 0.0), (4, 0.01)])
+def test_leaky_relu_and_silu_small(tv, act, alpha):
+    """The further activations through the whole path: both kernels of the activation (register-resident at one
+    perturbed position, streaming at two), bounds and certified eps against the oracle.  Slope 0 is ReLU."""
+    for P, p in ((1, 2), (2, 0)):
+        w = scaled(CONFIGS["c2"], n_layers=2, hidden=64, n_heads=2, ffn=128, seq_len=16, max_len=16, batch=4,
+                   n_perturbed=P, activation=act, act_alpha=alpha)
+        m = randomize_layernorm(make_model(w, stress=4.0))
+        run_case(tv, w, m, p, [1e-5, 1e-4], 3, 2, steps=6, cert_range=(0.0, 4e-4), rtol=5e-4)
+    if alpha == 0.0:
+        w0 = scaled(w, activation=0)
+        tok, pos = dev(make_tokens(w0, 2)), dev(make_positions(w0, 2))
+        eps = torch.full((2,), 1e-4, dtype=torch.float32, device="cuda:0")
+        outs = []
+        for wl in (w, w0):
+            model = tv.Model(randomize_layernorm(make_model(wl, stress=4.0)))
+            outs.append(model.verify(tok, pos, 0, eps))
+            model.close()
+        assert torch.equal(outs[0]["lower"], outs[1]["lower"]) and torch.equal(outs[0]["upper"], outs[1]["upper"])
+
+
 def test_blow_up_regime_agrees_loosely(tv):
     """Far beyond the certified radius the LayerNorm bounds amplify every perturbation (widths grow by
     orders of magnitude per layer) and with them the fp32 rounding differences: bounds of size 1e4..1e9

@@ -41,10 +41,25 @@ def intervals(rng, n, kind):
     return l, u
 
 
-CASES = [("relu", RX.relu, np.maximum, ("crossing", "any")), ("tanh", RX.tanh, None, ("crossing", "any", "positive")),
+def silu_lines(l, u):
+    """The oracle's SiLU chain on neurons x = mid + delta, |delta| <= half (one coordinate, l_inf ball), as lines in x."""
+    from oracle import bounds as B
+    from oracle import verifier as V
+    mid, half = 0.5 * (l + u), 0.5 * (u - l)
+    out = []
+    for m_, h_ in zip(mid, half):       # eps differs per neuron: one call each
+        X = B.Bounds(np.ones((1, 1)), np.array([m_]), np.ones((1, 1)), np.array([m_]))
+        Y = V.silu_bound(X, V._Ctx(float(h_), 1, 0))
+        out.append([Y.lw[0, 0], Y.lb[0] - Y.lw[0, 0] * m_, Y.uw[0, 0], Y.ub[0] - Y.uw[0, 0] * m_])
+    return tuple(np.array(out).T)
+
+
+CASES = [("leaky", RX.leaky_relu(0.1), None, ("crossing", "any")), ("silu", silu_lines, None, ("crossing", "any")),
+         ("relu", RX.relu, np.maximum, ("crossing", "any")), ("tanh", RX.tanh, None, ("crossing", "any", "positive")),
          ("exp", RX.exp, None, ("any",)), ("recip", RX.reciprocal, None, ("positive",)),
          ("sqrt", RX.sqrt, None, ("positive",)), ("square", RX.square, None, ("crossing", "any"))]
-FUNCS = {"relu": lambda x: np.maximum(x, 0.0), "tanh": np.tanh, "exp": np.exp, "recip": lambda x: 1.0 / x,
+FUNCS = {"leaky": lambda x: np.where(x >= 0, x, 0.1 * x), "silu": lambda x: x / (1.0 + np.exp(-x)),
+         "relu": lambda x: np.maximum(x, 0.0), "tanh": np.tanh, "exp": np.exp, "recip": lambda x: 1.0 / x,
          "sqrt": np.sqrt, "square": lambda x: x * x}
 
 
