@@ -125,6 +125,22 @@ int tv_certify(const tv_model *m, const int32_t *tokens, int B, int L, const int
                int32_t *out_labels, int32_t *status, void *workspace, size_t workspace_bytes,
                void *stream);
 
+/* tv_verify / tv_certify for sentences of different lengths in one batch (the paper's data sets spread over
+ * 4..128 words, Sec. 6): lengths [B] int32 (device), 1 <= lengths[b] <= L; tokens [b][t] with t >= lengths[b] are
+ * padding (any valid token id) and are ignored - the result for sentence b is the result of a call with that
+ * sentence alone at L = lengths[b] (which itself need not be a multiple of 4).  The perturbed positions of
+ * sentence b must lie below lengths[b].  Scores towards padded keys are replaced by a constant far below the row's
+ * maximum, for which the exp relaxation is exactly zero; the value rows of padded tokens are zeroed; a padded
+ * token cannot raise status.  Everything else as in tv_verify / tv_certify (same workspace). */
+int tv_verify_padded(const tv_model *m, const int32_t *tokens, const int32_t *lengths, int B, int L,
+                     const int32_t *positions, int P, int p_norm, const float *eps, const int32_t *labels,
+                     float *out_lower, float *out_upper, float *out_margin_lower, int32_t *out_labels,
+                     int32_t *status, void *workspace, size_t workspace_bytes, void *stream);
+int tv_certify_padded(const tv_model *m, const int32_t *tokens, const int32_t *lengths, int B, int L,
+                      const int32_t *positions, int P, int p_norm, float eps_lo, float eps_hi, int steps,
+                      const int32_t *labels, float *out_eps, int32_t *out_labels, int32_t *status,
+                      void *workspace, size_t workspace_bytes, void *stream);
+
 /* Measurement aid: launches `workgroups` x 4 waves that each issue iters * 16 independent matrix-core
  * instructions (bf16 == 0: v_mfma_f32_32x32x2_f32, the instruction of the dot-product contractions; bf16 != 0:
  * v_mfma_f32_32x32x16_bf16, the instruction of the affine layers) and sets *flops (host pointer) to the flops of

@@ -42,7 +42,7 @@ class _Weights(C.Structure):
 _lib = None
 
 EXPORTS = ("tv_version", "tv_last_error", "tv_model_create", "tv_model_destroy", "tv_workspace_query", "tv_verify",
-           "tv_certify", "tv_op_concretize", "tv_op_abs", "tv_op_affine", "tv_op_split3", "tv_op_affine_split", "tv_affine_tile_count", "tv_affine_tile_default",
+           "tv_certify", "tv_verify_padded", "tv_certify_padded", "tv_op_concretize", "tv_op_abs", "tv_op_affine", "tv_op_split3", "tv_op_affine_split", "tv_affine_tile_count", "tv_affine_tile_default",
            "tv_affine_tile_info", "tv_op_affine_split_tile", "tv_probe_mfma", "tv_profile_select", "tv_op_activation", "tv_op_layernorm",
            "tv_attention_workspace", "tv_op_attention", "tv_profile_enable", "tv_profile_reset",
            "tv_profile_kinds", "tv_profile_get")
@@ -66,7 +66,9 @@ def lib():
                                          C.POINTER(C.c_size_t)]
         vp, i, f, sz = C.c_void_p, C.c_int, C.c_float, C.c_size_t
         L.tv_verify.argtypes = [vp, vp, i, i, vp, i, i, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.tv_verify_padded.argtypes = [vp, vp, vp, i, i, vp, i, i, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.tv_certify.argtypes = [vp, vp, i, i, vp, i, i, f, f, i, vp, vp, vp, vp, vp, sz, vp]
+        L.tv_certify_padded.argtypes = [vp, vp, vp, i, i, vp, i, i, f, f, i, vp, vp, vp, vp, vp, sz, vp]
         L.tv_op_concretize.argtypes = [vp, vp, i, i, i, i, i, i, i, vp, vp, vp, vp]
         L.tv_op_abs.argtypes = [vp, vp, sz, vp]
         L.tv_op_affine.argtypes = [vp, vp, i, i, i, i, i, i, vp, vp, vp, vp, vp, vp, vp, vp]
@@ -166,8 +168,9 @@ class Model:
             self._ws = torch.empty(want, dtype=torch.uint8, device=self.device)
         return self._ws
 
-    def verify(self, tokens, positions, p_norm, eps, labels=None, workspace=None):
+    def verify(self, tokens, positions, p_norm, eps, labels=None, workspace=None, lengths=None):
         """tokens [B,L] int32, positions [B,P] int32, eps [B] fp32, labels [B] int32 or None (device tensors).
+        lengths [B] int32 or None: sentence b has lengths[b] real tokens, the rest of its row is padding.
         Returns dict of device tensors: lower, upper [B,n_cls], margin_lower [B,n_cls-1], labels, status."""
         B, L = tokens.shape
         P = positions.shape[1]
@@ -179,12 +182,18 @@ class Model:
         margin = torch.empty(B, nc - 1, dtype=torch.float32, device=dev)
         out_labels = torch.empty(B, dtype=torch.int32, device=dev)
         status = torch.empty(B, dtype=torch.int32, device=dev)
-        _check(lib().tv_verify(self._h, _ptr(tokens), B, L, _ptr(positions), P, p_norm, _ptr(eps), _ptr(labels),
-                               _ptr(lower), _ptr(upper), _ptr(margin), _ptr(out_labels), _ptr(status), _ptr(ws),
-                               ws.numel(), _stream()))
+        if lengths is None:
+            _check(lib().tv_verify(self._h, _ptr(tokens), B, L, _ptr(positions), P, p_norm, _ptr(eps), _ptr(labels),
+                                   _ptr(lower), _ptr(upper), _ptr(margin), _ptr(out_labels), _ptr(status), _ptr(ws),
+                                   ws.numel(), _stream()))
+        else:
+            assert lengths.dtype == torch.int32 and lengths.shape == (B,)
+            _check(lib().tv_verify_padded(self._h, _ptr(tokens), _ptr(lengths), B, L, _ptr(positions), P, p_norm,
+                                          _ptr(eps), _ptr(labels), _ptr(lower), _ptr(upper), _ptr(margin),
+                                          _ptr(out_labels), _ptr(status), _ptr(ws), ws.numel(), _stream()))
         return {"lower": lower, "upper": upper, "margin_lower": margin, "labels": out_labels, "status": status}
 
-    def certify(self, tokens, positions, p_norm, eps_lo, eps_hi, steps, labels=None, workspace=None):
+    def certify(self, tokens, positions, p_norm, eps_lo, eps_hi, steps, labels=None, workspace=None, lengths=None):
         B, L = tokens.shape
         P = positions.shape[1]
         ws = workspace if workspace is not None else self.workspace(B, L, P)
@@ -192,9 +201,15 @@ class Model:
         out_eps = torch.empty(B, dtype=torch.float32, device=dev)
         out_labels = torch.empty(B, dtype=torch.int32, device=dev)
         status = torch.empty(B, dtype=torch.int32, device=dev)
-        _check(lib().tv_certify(self._h, _ptr(tokens), B, L, _ptr(positions), P, p_norm, eps_lo, eps_hi, steps,
-                                _ptr(labels), _ptr(out_eps), _ptr(out_labels), _ptr(status), _ptr(ws), ws.numel(),
-                                _stream()))
+        if lengths is None:
+            _check(lib().tv_certify(self._h, _ptr(tokens), B, L, _ptr(positions), P, p_norm, eps_lo, eps_hi, steps,
+                                    _ptr(labels), _ptr(out_eps), _ptr(out_labels), _ptr(status), _ptr(ws), ws.numel(),
+                                    _stream()))
+        else:
+            assert lengths.dtype == torch.int32 and lengths.shape == (B,)
+            _check(lib().tv_certify_padded(self._h, _ptr(tokens), _ptr(lengths), B, L, _ptr(positions), P, p_norm,
+                                           eps_lo, eps_hi, steps, _ptr(labels), _ptr(out_eps), _ptr(out_labels),
+                                           _ptr(status), _ptr(ws), ws.numel(), _stream()))
         return {"eps": out_eps, "labels": out_labels, "status": status}
 
 

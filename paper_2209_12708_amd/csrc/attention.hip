@@ -260,7 +260,7 @@ size_t attention_workspace_ext(int B, int L, int H, int D, int P, bool own_score
 
 int attention(CState q, CState k, CState v, int ld, int B, int L, int H, int D, int P, int pn, const float *eps, State o,
               State s, int stop_after, int32_t *status, void *ws, size_t ws_bytes, hipStream_t st,
-              const float *qkv_norms) {
+              const float *qkv_norms, const int32_t *lengths) {
   TV_REQUIRE(q.S && q.R && k.S && k.R && v.S && v.R && eps && status && ws, TV_E_NULL, "attention: null pointer");
   TV_REQUIRE(B > 0 && L > 0 && H > 0 && D > 0 && P >= 0 && D % H == 0 && (D / H) % 4 == 0 && L % 4 == 0, TV_E_SHAPE,
              "attention: need D %% H == 0, head width and L multiples of 4 (B=%d L=%d H=%d D=%d)", B, L, H, D);
@@ -354,7 +354,10 @@ int attention(CState q, CState k, CState v, int ld, int B, int L, int H, int D, 
   if (stop_after == 1) return TV_OK;
 
   float *lp = w + lay.lp, *slp = w + lay.slack_p;
-  if (int rc = softmax(s, B * H, P, D, L, L, H, pn, eps, lp, slp, status, st)) return rc;
+  // padded keys (sentences shorter than L): their score columns become a constant far below the row's maximum
+  if (lengths)
+    if (int rc = mask_scores(s, B * H, C, L, L, H, lengths, st)) return rc;
+  if (int rc = softmax(s, B * H, P, D, L, L, H, pn, eps, lp, slp, status, st, lengths)) return rc;
   if (stop_after == 2) return TV_OK;
 
   {

@@ -119,12 +119,19 @@ int ranges_from_norms(const float *norms, int groups, int T, int n, int gps, con
                       float *slack, hipStream_t st);
 // alpha: slope of the leaky ReLU on x < 0 (read by that activation only)
 int activation(int act, CState x, int groups, int P, int E, int T, int n, int gps, int p_norm, const float *eps,
-               State y, int32_t *status, hipStream_t st, float alpha = 0.01f);
+               State y, int32_t *status, hipStream_t st, float alpha = 0.01f, const int32_t *lengths = nullptr);
 int layernorm(CState x, int groups, int P, int E, int T, int n, int gps, int p_norm, const float *eps,
-              const float *gamma, const float *beta, float ln_eps, State y, int32_t *status, hipStream_t st);
+              const float *gamma, const float *beta, float ln_eps, State y, int32_t *status, hipStream_t st,
+              const int32_t *lengths = nullptr);
 // in place; also writes lp = clamp(lower bound of p, 0, 1) and slack = S_p_b - lp, both [groups][T][n]
 int softmax(State s, int groups, int P, int E, int T, int n, int gps, int p_norm, const float *eps, float *lp,
-            float *slack, int32_t *status, hipStream_t st);
+            float *slack, int32_t *status, hipStream_t st, const int32_t *lengths = nullptr);
+// Sentences of different lengths in one batch.  lengths [sentences] (device) or nullptr: tokens t >= lengths[b] are
+// padding.  The row kernels above keep a padded token from raising its sentence's status; mask_scores turns the
+// score columns of padded keys into the constant -1e30 (softmax then gives them p = 0 exactly); mask_tokens zeroes
+// `width` columns from col0 of the padded tokens' rows in a state with row stride ld (the v part of q | k | v).
+int mask_scores(State s, int groups, int C, int T, int n, int gps, const int32_t *lengths, hipStream_t st);
+int mask_tokens(State x, int B, int C, int T, int ld, int col0, int width, const int32_t *lengths, hipStream_t st);
 int vec_abs(const float *in, float *out, size_t count, hipStream_t st);
 int fill_zero(float *p, size_t count, hipStream_t st);
 
@@ -134,6 +141,6 @@ size_t attention_workspace_ext(int B, int L, int H, int D, int P, bool own_score
 // ld: row stride of the q, k, v states (D when separate, 3D when they are column slices of one tensor)
 int attention(CState q, CState k, CState v, int ld, int B, int L, int H, int D, int P, int p_norm, const float *eps,
               State o, State s, int stop_after, int32_t *status, void *ws, size_t ws_bytes, hipStream_t st,
-              const float *qkv_norms = nullptr);
+              const float *qkv_norms = nullptr, const int32_t *lengths = nullptr);
 
 }  // namespace tv

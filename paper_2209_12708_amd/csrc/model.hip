@@ -298,7 +298,7 @@ int init_input(const tv_model *m, const Plan &pl, float *w, const int32_t *token
 // q, k, v of the first layer from the input state: the same for every eps, so a bisection computes it once
 // (with the norms and bias values its concretization needs, which do not depend on eps either)
 int project_input(const tv_model *m, const Plan &pl, float *w, const int32_t *tokens, const int32_t *positions,
-                  int Bc, int L, int P, int pn, hipStream_t st) {
+                  int Bc, int L, int P, int pn, const int32_t *lengths, hipStream_t st) {
   const int D = m->cfg.hidden, C = P * D + 1;
   const long M = (long)Bc * L * C, n3 = (long)Bc * L * 3 * D;
   if (int rc = init_input(m, pl, w, tokens, positions, Bc, L, P, st)) return rc;
@@ -308,13 +308,16 @@ int project_input(const tv_model *m, const Plan &pl, float *w, const int32_t *to
   TV_HIP(hipGetLastError());
   if (int rc = affine(w + pl.x, M * D, M, C, L, D, 3 * D, m->layers[0].Wqkv, m->layers[0].Wqkv3, m->layers[0].bqkv,
                       nullptr, 0, Q, M * 3 * D, st)) return rc;
+  if (lengths)
+    if (int rc = mask_tokens(State{Q, Q + M * 3 * D}, Bc, C, L, 3 * D, 2 * D, D, lengths, st)) return rc;
   return concretize(CState{Q, Q + M * 3 * D}, Bc, P, D, L, 3 * D, 1, pn, w + pl.eps, nrm, nrm + n3, nrm + 2 * n3, 2, st,
                     nrm + 3 * n3);
 }
 
 // one pass of the encoder.  qkv0: the cached first-layer projection (project_input), or nullptr to compute it.
 int sweep(const tv_model *m, const Plan &pl, float *w, const int32_t *tokens, const int32_t *positions, int Bc, int L,
-          int P, int pn, const float *eps, int32_t *status, const float *qkv0, const float *norms0, hipStream_t st) {
+          int P, int pn, const float *eps, int32_t *status, const float *qkv0, const float *norms0,
+          const int32_t *lengths, hipStream_t st) {
   const tv_config &c = m->cfg;
   const int D = c.hidden, F = c.ffn, H = c.n_heads;
   const int C = P * D + 1;
@@ -337,11 +340,16 @@ int sweep(const tv_model *m, const Plan &pl, float *w, const int32_t *tokens, co
     // q, k, v in one product: columns [0,D) q, [D,2D) k, [2D,3D) v
     const float *Q = QKV;
     if (l == 0 && qkv0) Q = qkv0;
-    else if (int rc = affine(X, pD, M, C, L, D, 3 * D, lw.Wqkv, lw.Wqkv3, lw.bqkv, nullptr, 0, QKV, p3D, st)) return rc;
+    else {
+      if (int rc = affine(X, pD, M, C, L, D, 3 * D, lw.Wqkv, lw.Wqkv3, lw.bqkv, nullptr, 0, QKV, p3D, st)) return rc;
+      // padded tokens: zero their v rows, so that nothing of them reaches a real token through p v
+      if (lengths)
+        if (int rc = mask_tokens(State{QKV, QKV + p3D}, Bc, C, L, 3 * D, 2 * D, D, lengths, st)) return rc;
+    }
     CState q{Q, Q + p3D}, k{Q + D, Q + p3D + D}, v{Q + 2 * D, Q + p3D + 2 * D};
     State o{T1, T1 + pD}, s{BIG, BIG + pS};
     if (int rc = attention(q, k, v, 3 * D, Bc, L, H, D, P, pn, eps, o, s, 0, status, attn_ws, attn_bytes, st,
-                           l == 0 && qkv0 ? norms0 : nullptr))
+                           l == 0 && qkv0 ? norms0 : nullptr, lengths))
       return rc;
     // a = o Wo^T + bo + x   (written over the dead q/k/v region), x' = LN(a) (over the dead x)
     float *A = QKV;
@@ -350,14 +358,14 @@ int sweep(const tv_model *m, const Plan &pl, float *w, const int32_t *tokens, co
         return rc;
     } else if (int rc = affine(T1, pD, M, C, L, D, D, lw.Wo, lw.Wo3, lw.bo, X, pD, A, pD, st)) return rc;
     if (int rc = layernorm(CState{A, A + pD}, Bc, P, D, L, D, 1, pn, eps, lw.ln1_g, lw.ln1_b, c.ln_eps,
-                           State{X, X + pD}, status, st)) return rc;
+                           State{X, X + pD}, status, st, lengths)) return rc;
     // feed-forward: h = x' W1^T + b1 ; act ; f = act W2^T + b2 + x' ; x'' = LN(f)
     if (int rc = affine(X, pD, M, C, L, D, F, lw.W1, lw.W13, lw.b1, nullptr, 0, BIG, pF, st)) return rc;
     if (int rc = activation(c.activation, CState{BIG, BIG + pF}, Bc, P, D, L, F, 1, pn, eps,
-                            State{BIG, BIG + pF}, status, st, c.act_alpha)) return rc;
+                            State{BIG, BIG + pF}, status, st, c.act_alpha, lengths)) return rc;
     if (int rc = affine(BIG, pF, M, C, L, F, D, lw.W2, lw.W23, lw.b2, X, pD, T1, pD, st)) return rc;
     if (int rc = layernorm(CState{T1, T1 + pD}, Bc, P, D, L, D, 1, pn, eps, lw.ln2_g, lw.ln2_b, c.ln_eps,
-                           State{X, X + pD}, status, st)) return rc;
+                           State{X, X + pD}, status, st, lengths)) return rc;
   }
   return TV_OK;
 }
@@ -400,7 +408,7 @@ int check_call(const tv_model *m, const int32_t *tokens, int B, int L, const int
 // labels of a chunk: given, or the clean prediction from a bias-only sweep (P = 0: every state has
 // the bias row only, so the kernels compute the plain forward pass)
 int chunk_labels(const tv_model *m, float *w, const Plan &pl, const int32_t *tokens, const int32_t *positions,
-                 int Bc, int L, int pn, const int32_t *labels, hipStream_t st) {
+                 int Bc, int L, int pn, const int32_t *labels, const int32_t *lengths, hipStream_t st) {
   int32_t *lab = reinterpret_cast<int32_t *>(w + pl.labels), *status = reinterpret_cast<int32_t *>(w + pl.status);
   if (labels) {
     hipLaunchKernelGGL(copy_i32_kernel, dim3(nblk(Bc)), dim3(256), 0, st, labels, lab, Bc);
@@ -416,7 +424,7 @@ int chunk_labels(const tv_model *m, float *w, const Plan &pl, const int32_t *tok
                      Bc, 0);
   TV_HIP(hipGetLastError());
   if (int rc = sweep(m, p0, w, tokens, positions, Bc, L, 0, pn, eps0, reinterpret_cast<int32_t *>(w + p0.status), nullptr,
-                     nullptr, st))
+                     nullptr, lengths, st))
     return rc;
   if (int rc = head(m, p0, w, Bc, L, 0, pn, eps0, reinterpret_cast<int32_t *>(w + p0.labels), st)) return rc;
   // p0's small arrays sit below pl's (its big regions are smaller), so writing pl.labels last is safe
@@ -548,9 +556,10 @@ int tv_workspace_query(const tv_model *m, int B, int L, int P, size_t *bytes_ful
   return TV_OK;
 }
 
-int tv_verify(const tv_model *m, const int32_t *tokens, int B, int L, const int32_t *positions, int P, int pn,
-              const float *eps, const int32_t *labels, float *out_lower, float *out_upper, float *out_margin_lower,
-              int32_t *out_labels, int32_t *status, void *workspace, size_t workspace_bytes, void *stream) {
+int tv_verify_padded(const tv_model *m, const int32_t *tokens, const int32_t *lengths, int B, int L,
+                     const int32_t *positions, int P, int pn, const float *eps, const int32_t *labels, float *out_lower,
+                     float *out_upper, float *out_margin_lower, int32_t *out_labels, int32_t *status, void *workspace,
+                     size_t workspace_bytes, void *stream) {
   if (int rc = check_call(m, tokens, B, L, positions, P, pn, workspace)) return rc;
   TV_REQUIRE(eps && out_lower && out_upper && status, TV_E_NULL, "tv_verify: null eps or output pointer");
   const int Bmax = chunk_size(m->cfg, B, L, P, workspace_bytes);
@@ -564,10 +573,11 @@ int tv_verify(const tv_model *m, const int32_t *tokens, int B, int L, const int3
     const Plan pl = make_plan(m->cfg, Bc, L, P);
     int32_t *lab = reinterpret_cast<int32_t *>(w + pl.labels), *stat = reinterpret_cast<int32_t *>(w + pl.status);
     const int32_t *tok = tokens + (size_t)b0 * L, *pos = positions + (size_t)b0 * P;
-    if (int rc = chunk_labels(m, w, pl, tok, pos, Bc, L, pn, labels ? labels + b0 : nullptr, st)) return rc;
+    const int32_t *len = lengths ? lengths + b0 : nullptr;
+    if (int rc = chunk_labels(m, w, pl, tok, pos, Bc, L, pn, labels ? labels + b0 : nullptr, len, st)) return rc;
     hipLaunchKernelGGL(fill_i32_kernel, dim3(nblk(Bc)), dim3(256), 0, st, stat, Bc, 0);
     TV_HIP(hipGetLastError());
-    if (int rc = sweep(m, pl, w, tok, pos, Bc, L, P, pn, eps + b0, stat, nullptr, nullptr, st)) return rc;
+    if (int rc = sweep(m, pl, w, tok, pos, Bc, L, P, pn, eps + b0, stat, nullptr, nullptr, len, st)) return rc;
     if (int rc = head(m, pl, w, Bc, L, P, pn, eps + b0, lab, st)) return rc;
     hipLaunchKernelGGL(head_out_kernel, dim3(nblk(Bc)), dim3(256), 0, st, w + pl.hl, w + pl.hu, stat, lab, Bc, nc,
                        pl.NP, out_lower + (size_t)b0 * nc, out_upper + (size_t)b0 * nc,
@@ -578,9 +588,17 @@ int tv_verify(const tv_model *m, const int32_t *tokens, int B, int L, const int3
   return TV_OK;
 }
 
-int tv_certify(const tv_model *m, const int32_t *tokens, int B, int L, const int32_t *positions, int P, int pn,
-               float eps_lo, float eps_hi, int steps, const int32_t *labels, float *out_eps, int32_t *out_labels,
-               int32_t *status, void *workspace, size_t workspace_bytes, void *stream) {
+int tv_verify(const tv_model *m, const int32_t *tokens, int B, int L, const int32_t *positions, int P, int pn,
+              const float *eps, const int32_t *labels, float *out_lower, float *out_upper, float *out_margin_lower,
+              int32_t *out_labels, int32_t *status, void *workspace, size_t workspace_bytes, void *stream) {
+  return tv_verify_padded(m, tokens, nullptr, B, L, positions, P, pn, eps, labels, out_lower, out_upper,
+                          out_margin_lower, out_labels, status, workspace, workspace_bytes, stream);
+}
+
+int tv_certify_padded(const tv_model *m, const int32_t *tokens, const int32_t *lengths, int B, int L,
+                      const int32_t *positions, int P, int pn, float eps_lo, float eps_hi, int steps,
+                      const int32_t *labels, float *out_eps, int32_t *out_labels, int32_t *status, void *workspace,
+                      size_t workspace_bytes, void *stream) {
   if (int rc = check_call(m, tokens, B, L, positions, P, pn, workspace)) return rc;
   TV_REQUIRE(out_eps && status, TV_E_NULL, "tv_certify: null output pointer");
   TV_REQUIRE(steps >= 1 && steps <= 64, TV_E_ARG, "tv_certify: steps must be in [1, 64], got %d", steps);
@@ -602,14 +620,15 @@ int tv_certify(const tv_model *m, const int32_t *tokens, int B, int L, const int
     int32_t *cnt = reinterpret_cast<int32_t *>(w + pl.cnt);
     float *eps = w + pl.eps, *lohi = w + pl.lohi;
     const int32_t *tok = tokens + (size_t)b0 * L, *pos = positions + (size_t)b0 * P;
-    if (int rc = chunk_labels(m, w, pl, tok, pos, Bc, L, pn, labels ? labels + b0 : nullptr, st)) return rc;
+    const int32_t *len = lengths ? lengths + b0 : nullptr;
+    if (int rc = chunk_labels(m, w, pl, tok, pos, Bc, L, pn, labels ? labels + b0 : nullptr, len, st)) return rc;
     hipLaunchKernelGGL(search_init_kernel, dim3(nblk(Bc)), dim3(256), 0, st, lohi, Bc, eps_lo, eps_hi, cnt, eps, stat);
     TV_HIP(hipGetLastError());
     if (cache0)
-      if (int rc = project_input(m, pl, w, tok, pos, Bc, L, P, pn, st)) return rc;
+      if (int rc = project_input(m, pl, w, tok, pos, Bc, L, P, pn, len, st)) return rc;
     for (int it = 0; it < steps; ++it) {
       if (int rc = sweep(m, pl, w, tok, pos, Bc, L, P, pn, eps, stat, cache0 ? w + pl.qkv0 : nullptr,
-                         cache0 ? w + pl.norms0 : nullptr, st)) return rc;
+                         cache0 ? w + pl.norms0 : nullptr, len, st)) return rc;
       if (int rc = head(m, pl, w, Bc, L, P, pn, eps, lab, st)) return rc;
       hipLaunchKernelGGL(probe_end_kernel, dim3(nblk(Bc)), dim3(256), 0, st, w + pl.hl, w + pl.hu, stat, Bc, nc, pl.NP,
                          lohi, eps, cnt);
@@ -621,6 +640,13 @@ int tv_certify(const tv_model *m, const int32_t *tokens, int B, int L, const int
     TV_HIP(hipGetLastError());
   }
   return TV_OK;
+}
+
+int tv_certify(const tv_model *m, const int32_t *tokens, int B, int L, const int32_t *positions, int P, int pn,
+               float eps_lo, float eps_hi, int steps, const int32_t *labels, float *out_eps, int32_t *out_labels,
+               int32_t *status, void *workspace, size_t workspace_bytes, void *stream) {
+  return tv_certify_padded(m, tokens, nullptr, B, L, positions, P, pn, eps_lo, eps_hi, steps, labels, out_eps,
+                           out_labels, status, workspace, workspace_bytes, stream);
 }
 
 // ---- timing ------------------------------------------------------------------------------------

@@ -302,6 +302,13 @@ __device__ __forceinline__ Form gelu_inner(double lx, double ux, double &lb, dou
   return form_sub(a, k * c3, k, k * c3, k);
 }
 
+// Sentences of different lengths in one batch (padding): lengths[sentence] tokens are real, the rest of the T tokens
+// are padding whose values no real token reads (scores towards them and their v rows are masked).  A padded token
+// must not raise the sentence's status either.  lengths == nullptr: every token is real.
+__device__ __forceinline__ bool token_live(const int32_t *lengths, int sent, int t) {
+  return lengths == nullptr || t < lengths[sent];
+}
+
 // The activations whose relaxation is a function of the neuron's own range alone (all but GELU), as a form in x.
 // alpha: slope of the leaky ReLU on x < 0.
 template <int ACT>
@@ -319,7 +326,8 @@ __device__ __forceinline__ Form single_form(double l, double u, double alpha) {
 template <int ACT, typename NormFn>
 __device__ __forceinline__ void relax_columns(const Geo &ge, double e, float (&NL)[4], float (&NU)[4],
                                               const float (&bS)[4], const float (&bR)[4], NormFn second_norms,
-                                              Map2 *smap, LineCoef *slc, Map2 (&maps)[4], bool &bad, double alpha) {
+                                              Map2 *smap, LineCoef *slc, Map2 (&maps)[4], bool &bad, double alpha,
+                                              int live_cols) {
   const int own = ge.NS / 4;     // column i belongs to row slot i * NS / 4: one owner per wave when a wave holds several slots
   if (ACT != TV_ACT_GELU) {
 #pragma unroll
@@ -327,7 +335,7 @@ __device__ __forceinline__ void relax_columns(const Geo &ge, double e, float (&N
       if (ge.slot != i * own) continue;
       double l, u;
       range_of(bS[i], bR[i], e, NL[i], NU[i], l, u);
-      bad |= !(finite_d(l) && finite_d(u));
+      bad |= 4 * ge.g + i < live_cols && !(finite_d(l) && finite_d(u));
       smap[4 * ge.g + i] = form_map(single_form<ACT>(l, u, alpha));
     }
   } else {
@@ -338,7 +346,7 @@ __device__ __forceinline__ void relax_columns(const Geo &ge, double e, float (&N
       if (ge.slot != i * own) continue;
       double ux;
       range_of(bS[i], bR[i], e, NL[i], NU[i], lx, ux);
-      bad |= !(finite_d(lx) && finite_d(ux));
+      bad |= 4 * ge.g + i < live_cols && !(finite_d(lx) && finite_d(ux));
       double lb, ub;
       const Form b = gelu_inner(lx, ux, lb, ub);
       fg = form_mul(form_identity(), b, lx, lb, ub);     // g = x * b
@@ -360,7 +368,7 @@ __device__ __forceinline__ void relax_columns(const Geo &ge, double e, float (&N
       const double gR = 0.5 * (((f.pU - f.pL) + (f.qU - f.qL)) * xS + ((f.pU + f.pL) - (f.qU + f.qL)) * xR + (f.cU - f.cL));
       double lg, ug;
       range_of(gS, gR, e, NL[i], NU[i], lg, ug);
-      bad |= !(finite_d(lg) && finite_d(ug));
+      bad |= 4 * ge.g + i < live_cols && !(finite_d(lg) && finite_d(ug));
       const Line2 th = relax_tanh(lg, ug);
       double lt, ut;
       line_range(th, lg, ug, lt, ut);
@@ -381,7 +389,7 @@ template <int ACT, typename NormFn>
 __device__ __forceinline__ void relax_columns_by_lane(const Geo &ge, double e, const float (&NL)[4], const float (&NU)[4],
                                                       const float (&bS)[4], const float (&bR)[4], NormFn second_norms,
                                                       float (*cin)[kWave], Map2 *smap, LineCoef *slc, int owner_wave,
-                                                      bool &bad, double alpha) {
+                                                      bool &bad, double alpha, int live_cols) {
   const int lane = threadIdx.x & (kWave - 1);
   const bool owner = (int)(threadIdx.x / kWave) == owner_wave && lane < 4 * ge.G;
   auto publish = [&](const float (&nl)[4], const float (&nu)[4]) {
@@ -399,7 +407,7 @@ __device__ __forceinline__ void relax_columns_by_lane(const Geo &ge, double e, c
     if (owner) {
       double l, u;
       range_of(cin[0][lane], cin[1][lane], e, cin[2][lane], cin[3][lane], l, u);
-      bad |= !(finite_d(l) && finite_d(u));
+      bad |= lane < live_cols && !(finite_d(l) && finite_d(u));
       smap[lane] = form_map(single_form<ACT>(l, u, alpha));
     }
   } else {
@@ -409,7 +417,7 @@ __device__ __forceinline__ void relax_columns_by_lane(const Geo &ge, double e, c
       double ux;
       xS = cin[0][lane]; xR = cin[1][lane];
       range_of(xS, xR, e, cin[2][lane], cin[3][lane], lx, ux);
-      bad |= !(finite_d(lx) && finite_d(ux));
+      bad |= lane < live_cols && !(finite_d(lx) && finite_d(ux));
       double lb, ub;
       const Form b = gelu_inner(lx, ux, lb, ub);
       fg = form_mul(form_identity(), b, lx, lb, ub);     // g = x * b
@@ -431,7 +439,7 @@ __device__ __forceinline__ void relax_columns_by_lane(const Geo &ge, double e, c
       const double gR = 0.5 * (((f.pU - f.pL) + (f.qU - f.qL)) * xS + ((f.pU + f.pL) - (f.qU + f.qL)) * xR + (f.cU - f.cL));
       double lg, ug;
       range_of(gS, gR, e, cin[2][lane], cin[3][lane], lg, ug);
-      bad |= !(finite_d(lg) && finite_d(ug));
+      bad |= lane < live_cols && !(finite_d(lg) && finite_d(ug));
       const Line2 th = relax_tanh(lg, ug);
       double lt, ut;
       line_range(th, lg, ug, lt, ut);
@@ -445,7 +453,8 @@ __device__ __forceinline__ void relax_columns_by_lane(const Geo &ge, double e, c
 template <int VEC, int ACT, int PN>
 __global__ __launch_bounds__(kThreads) void activation_kernel(const float *S, const float *R, int P, int E, int X,
                                                               int G, int gps, const float *eps,
-                                                              float *So, float *Ro, int32_t *status, float alpha) {
+                                                              float *So, float *Ro, int32_t *status, float alpha,
+                                                              const int32_t *lengths, int n) {
   constexpr int pn = PN;
   static_assert(VEC == 1, "one float4 group per lane");
   __shared__ float red[4 * kWave * 8 * VEC];
@@ -463,7 +472,9 @@ __global__ __launch_bounds__(kThreads) void activation_kernel(const float *S, co
     float s0[4], r0[4];
     column_norms<VEC>(S, R, lc, P, E, ge, pn, lcf, red, nl, nu, s0, r0);
   };
-  relax_columns<ACT>(ge, e, NL, NU, bS, bR, second, smap, slc, maps, bad, (double)alpha);
+  // columns are (token, neuron): the real ones are the first lengths * n
+  const int live_cols = lengths ? min((long)lengths[blockIdx.x / gps] * n - c0, (long)chunk) : chunk;
+  relax_columns<ACT>(ge, e, NL, NU, bS, bR, second, smap, slc, maps, bad, (double)alpha, live_cols);
   if (bad) status[blockIdx.x / gps] = 1;
   apply_maps<VEC>(S, R, So, Ro, lc, ge, maps);
 }
@@ -474,7 +485,8 @@ __global__ __launch_bounds__(kThreads) void activation_kernel(const float *S, co
 template <int ROWS, int ACT, int PN>
 __global__ __launch_bounds__(kThreads) void activation_cached_kernel(const float *S, const float *R, int nrows, int X,
                                                                      int G, int gps, const float *eps, float *So,
-                                                                     float *Ro, int32_t *status, float alpha) {
+                                                                     float *Ro, int32_t *status, float alpha,
+                                                                     const int32_t *lengths, int n) {
   constexpr int pn = PN;
   __shared__ float red[4 * kWave * 8];
   __shared__ Map2 smap[kWave];          // one per column of the workgroup
@@ -529,8 +541,9 @@ __global__ __launch_bounds__(kThreads) void activation_cached_kernel(const float
   bool bad = false;
   auto second = [&](const LineCoef (&lcf)[4], float (&nl)[4], float (&nu)[4]) { norms(lcf, nl, nu); };
   __shared__ float cin[4][kWave];
+  const int live_cols = lengths ? (int)min((long)lengths[blockIdx.x / gps] * n - c0, (long)chunk) : chunk;
   relax_columns_by_lane<ACT>(ge, e, NL, NU, bS, bR, second, cin, smap, slc, (int)((blockIdx.x + blockIdx.y) & 3), bad,
-                             (double)alpha);
+                             (double)alpha, live_cols);
   if (bad) status[blockIdx.x / gps] = 1;
   float msS[4], msR[4], mrS[4], mrR[4];                // the float part of the columns' maps
 #pragma unroll
@@ -608,7 +621,8 @@ template <int VEC, int PN>
 __global__ __launch_bounds__(kThreads) void layernorm_kernel(const float *S, const float *R, int P, int E, int T_, int n,
                                                              int G, int gps, const float *eps,
                                                              const float *gamma, const float *beta, float ln_eps_f,
-                                                             float *So, float *Ro, int32_t *status) {
+                                                             float *So, float *Ro, int32_t *status,
+                                                             const int32_t *lengths) {
   constexpr int pn = PN;
   __shared__ float red[4 * kWave * 8 * VEC];
   const int C = P * E + 1;
@@ -721,7 +735,7 @@ __global__ __launch_bounds__(kThreads) void layernorm_kernel(const float *S, con
   const LnScalars sc_ = ln_scalars(lv, uv, ln_eps);
   const Map2 &mr = sc_.mr;
   const Mul2 &mc = sc_.mc;
-  if (bad) status[sent] = 1;
+  if (bad && token_live(lengths, sent, lc.t)) status[sent] = 1;
 
   // ---- sweep 3: y = c * rho (x = c_d with multiplier range of rho; y = rho with multiplier l_c), gamma / beta
   float gm[4 * VEC], bt[4 * VEC], lcf[4 * VEC];
@@ -772,7 +786,7 @@ void layernorm_cached_kernel(const float *S, const float *R, int nrows, int T_,
                                                                     int n, int G, int gps, const float *eps,
                                                                     const float *gamma, const float *beta,
                                                                     float ln_eps_f, float *So, float *Ro,
-                                                                    int32_t *status) {
+                                                                    int32_t *status, const int32_t *lengths) {
   constexpr int NW = NT / kWave;
   constexpr int pn = PN;
   __shared__ float red[NW * kWave * 8];
@@ -886,7 +900,7 @@ void layernorm_cached_kernel(const float *S, const float *R, int nrows, int T_,
       bad |= !(finite_d(lv) && finite_d(uv));
       const LnScalars sc_ = ln_scalars(lv, uv, ln_eps);
       mr = sc_.mr; mc = sc_.mc;
-      if (bad) status[sent] = 1;
+      if (bad && token_live(lengths, sent, lc.t)) status[sent] = 1;
       if (ge.g == 0) {
         tokf[0] = mr.sS; tokf[1] = mr.sR; tokf[2] = mr.rS; tokf[3] = mr.rR;
         tokf[4] = mc.a1; tokf[5] = mc.a2; tokf[6] = mc.a3; tokf[7] = mc.a4;
@@ -947,7 +961,7 @@ void layernorm_cached_kernel(const float *S, const float *R, int nrows, int T_,
 template <int VEC, int PN>
 __global__ __launch_bounds__(kThreads) void softmax_kernel(float *S, float *R, int P, int E, int T_, int n, int G,
                                                            int gps, const float *eps, float *lp_out,
-                                                           float *slack_out, int32_t *status) {
+                                                           float *slack_out, int32_t *status, const int32_t *lengths) {
   constexpr int pn = PN;
   __shared__ float red[4 * kWave * 8 * VEC];
   extern __shared__ double col_dyn[];                    // [6][n]  in: l, u (shifted), shift; out: kL, hk, dk, hc, dc, le
@@ -1063,7 +1077,7 @@ __global__ __launch_bounds__(kThreads) void softmax_kernel(float *S, float *R, i
       line_range(rcp, lsg, usg, lr, ur);
       const Map2 mr = form_map(form_sub(form_identity(), rcp));      // rho relative to sigma
       const Mul2 mc = mul_coeffs(lr, ur);
-      if (bad) status[sent] = 1;
+      if (bad && token_live(lengths, sent, lc.t)) status[sent] = 1;
       if (ge.g == 0) {
         tokf[0] = mr.sS; tokf[1] = mr.sR; tokf[2] = mr.rS; tokf[3] = mr.rR;
         tokf[4] = mc.a1; tokf[5] = mc.a2; tokf[6] = mc.a3; tokf[7] = mc.a4;
@@ -1145,7 +1159,7 @@ template <int ROWS, int LROWS, int PN>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2)))
 void softmax_cached_kernel(float *S, float *R, int nrows, int TB, int seg, int gps,
                                                                   const float *eps, float *lp_out, float *slack_out,
-                                                                  int32_t *status) {
+                                                                  int32_t *status, const int32_t *lengths) {
   constexpr int pn = PN;
   constexpr int NCOL = 128, GL = 32, MAXT = 8;             // columns, lanes per coefficient row, tokens per block at most
   __shared__ float red[4 * kWave * 8];
@@ -1293,7 +1307,7 @@ void softmax_cached_kernel(float *S, float *R, int nrows, int TB, int seg, int g
       line_range(rcp, lsg, usg, lr, ur);
       const Map2 mr = form_map(form_sub(form_identity(), rcp));      // rho relative to sigma
       const Mul2 mc = mul_coeffs(lr, ur);
-      if (bad) status[sent] = 1;
+      if (bad && token_live(lengths, sent, lc.t * (GL / seg) + ts)) status[sent] = 1;
       if (ge.g % seg == 0) {
         tokf[ts][0] = mr.sS; tokf[ts][1] = mr.sR; tokf[ts][2] = mr.rS; tokf[ts][3] = mr.rR;
         tokf[ts][4] = mc.a1; tokf[ts][5] = mc.a2; tokf[ts][6] = mc.a3; tokf[ts][7] = mc.a4;
@@ -1438,7 +1452,7 @@ int concretize(CState x, int groups, int P, int E, int T, int n, int gps, int pn
 }
 
 int activation(int act, CState x, int groups, int P, int E, int T, int n, int gps, int pn, const float *eps, State y,
-               int32_t *status, hipStream_t st, float alpha) {
+               int32_t *status, hipStream_t st, float alpha, const int32_t *lengths) {
   if (int rc = check_common(x.S, x.R, groups, P, E, T, n, gps, pn, eps)) return rc;
   TV_REQUIRE(y.S && y.R && status, TV_E_NULL, "null output");
   TV_REQUIRE(act == TV_ACT_RELU || act == TV_ACT_TANH || act == TV_ACT_GELU || act == TV_ACT_LEAKY_RELU ||
@@ -1469,7 +1483,7 @@ int activation(int act, CState x, int groups, int P, int E, int T, int n, int gp
     const bool small = (E + 15) / 16 <= 4;
 #define ACTC_LAUNCH2(ROWS, A, PN)                                                                                   \
   hipLaunchKernelGGL((activation_cached_kernel<ROWS, A, PN>), gridc, blockc, 0, st, x.S, x.R, E, (int)X, Gc, gps, eps, \
-                     y.S, y.R, status, alpha)
+                     y.S, y.R, status, alpha, lengths, n)
 #define ACTC_ONE(A) do { if (small) ACTC_LAUNCH2(4, A, PN_); else ACTC_LAUNCH2(8, A, PN_); } while (0)
 #define ACTC_LAUNCH(PN)                \
   do {                                 \
@@ -1486,7 +1500,7 @@ int activation(int act, CState x, int groups, int P, int E, int T, int n, int gp
   dim3 grid(groups, nch), block(kThreads);
 #define ACT_ONE(A)                                                                                                  \
   hipLaunchKernelGGL((activation_kernel<1, A, PN_>), grid, block, 0, st, x.S, x.R, P, E, (int)X, G, gps, eps, y.S, \
-                     y.R, status, alpha)
+                     y.R, status, alpha, lengths, n)
 #define ACT_LAUNCH(PN)                 \
   do {                                 \
     constexpr int PN_ = PN;            \
@@ -1501,7 +1515,7 @@ int activation(int act, CState x, int groups, int P, int E, int T, int n, int gp
 }
 
 int layernorm(CState x, int groups, int P, int E, int T, int n, int gps, int pn, const float *eps, const float *gamma,
-              const float *beta, float ln_eps, State y, int32_t *status, hipStream_t st) {
+              const float *beta, float ln_eps, State y, int32_t *status, hipStream_t st, const int32_t *lengths) {
   if (int rc = check_common(x.S, x.R, groups, P, E, T, n, gps, pn, eps)) return rc;
   TV_REQUIRE(y.S && y.R && status && gamma && beta, TV_E_NULL, "null pointer");
   TV_REQUIRE(ln_eps > 0.f, TV_E_ARG, "ln_eps must be positive");
@@ -1520,13 +1534,13 @@ int layernorm(CState x, int groups, int P, int E, int T, int n, int gps, int pn,
   do {                                                                                                           \
     if (per256 <= 4)                                                                                             \
       hipLaunchKernelGGL((layernorm_cached_kernel<4, 256, PN>), grid, dim3(256), 0, st, x.S, x.R, crows, T, n, G, gps, \
-                         eps, gamma, beta, ln_eps, y.S, y.R, status);                                            \
+                         eps, gamma, beta, ln_eps, y.S, y.R, status, lengths);                                   \
     else if (per256 <= 8)                                                                                        \
       hipLaunchKernelGGL((layernorm_cached_kernel<8, 256, PN>), grid, dim3(256), 0, st, x.S, x.R, crows, T, n, G, gps, \
-                         eps, gamma, beta, ln_eps, y.S, y.R, status);                                            \
+                         eps, gamma, beta, ln_eps, y.S, y.R, status, lengths);                                   \
     else                                                                                                         \
       hipLaunchKernelGGL((layernorm_cached_kernel<16, 256, PN>), grid, dim3(256), 0, st, x.S, x.R, crows, T, n, G, gps, \
-                         eps, gamma, beta, ln_eps, y.S, y.R, status);                                            \
+                         eps, gamma, beta, ln_eps, y.S, y.R, status, lengths);                                   \
   } while (0)
     NORM_SWITCH(pn, LNC_LAUNCH);
 #undef LNC_LAUNCH
@@ -1535,7 +1549,7 @@ int layernorm(CState x, int groups, int P, int E, int T, int n, int gps, int pn,
   }
 #define LN_LAUNCH2(V, PN)                                                                                        \
   hipLaunchKernelGGL((layernorm_kernel<V, PN>), grid, block, 0, st, x.S, x.R, P, E, T, n, G, gps, eps, gamma, beta, \
-                     ln_eps, y.S, y.R, status)
+                     ln_eps, y.S, y.R, status, lengths)
 #define LN_LAUNCH(PN)                 \
   switch (VEC) {                      \
     case 1: LN_LAUNCH2(1, PN); break; \
@@ -1551,7 +1565,7 @@ int layernorm(CState x, int groups, int P, int E, int T, int n, int gps, int pn,
 }
 
 int softmax(State s, int groups, int P, int E, int T, int n, int gps, int pn, const float *eps, float *lp,
-            float *slack, int32_t *status, hipStream_t st) {
+            float *slack, int32_t *status, hipStream_t st, const int32_t *lengths) {
   if (int rc = check_common(s.S, s.R, groups, P, E, T, n, gps, pn, eps)) return rc;
   TV_REQUIRE(lp && slack && status, TV_E_NULL, "null pointer");
   int G, VEC;
@@ -1565,7 +1579,7 @@ int softmax(State s, int groups, int P, int E, int T, int n, int gps, int pn, co
     dim3 gridc((unsigned)(groups * TB));
 #define SMC_LAUNCH(PN)                                                                                            \
   hipLaunchKernelGGL((softmax_cached_kernel<16, 6, PN>), gridc, dim3(kThreads), 0, st, s.S, s.R, E, TB, n / 4, gps, eps, lp, \
-                     slack, status)
+                     slack, status, lengths)
     NORM_SWITCH(pn, SMC_LAUNCH);
 #undef SMC_LAUNCH
     TV_HIP(hipGetLastError());
@@ -1574,7 +1588,7 @@ int softmax(State s, int groups, int P, int E, int T, int n, int gps, int pn, co
   dim3 grid((unsigned)(groups * T)), block(kThreads);
 #define SM_LAUNCH2(V, PN)                                                                                    \
   hipLaunchKernelGGL((softmax_kernel<V, PN>), grid, block, 6 * (size_t)n * sizeof(double), st, s.S, s.R, P, E, T, n, \
-                     G, gps, eps, lp, slack, status)
+                     G, gps, eps, lp, slack, status, lengths)
 #define SM_LAUNCH(PN)                 \
   switch (VEC) {                      \
     case 1: SM_LAUNCH2(1, PN); break; \
@@ -1585,6 +1599,51 @@ int softmax(State s, int groups, int P, int E, int T, int n, int gps, int pn, co
   NORM_SWITCH(pn, SM_LAUNCH);
 #undef SM_LAUNCH2
 #undef SM_LAUNCH
+  TV_HIP(hipGetLastError());
+  return TV_OK;
+}
+
+// Padding masks.  mask_scores: in the score state [groups][C][T][n] of sentences with lengths[sentence] < n, the
+// columns j >= length become the constant -1e30 (coefficient rows and radius 0): the softmax kernels then relax
+// exp on a point where it is exactly 0 in double, so a padded key gets p = 0 in every plane and the sum over keys
+// is the sum over the real ones.  mask_tokens: zero the rows t >= length of `width` columns from column col0 of a
+// state with row stride ld (the v part of q | k | v): a padded token contributes 0 * 0 to every product.
+__global__ void mask_scores_kernel(float *S, float *R, long rows, int C, int T, int n, int gps,
+                                   const int32_t *lengths) {
+  // one thread per (group, coefficient row, token) row of n scores
+  for (long r = (long)blockIdx.x * blockDim.x + threadIdx.x; r < rows; r += (long)gridDim.x * blockDim.x) {
+    const long grp = r / ((long)C * T);
+    const int c = (int)((r / T) % C);
+    const int len = lengths[grp / gps];
+    const float fill = c == C - 1 ? -1.0e30f : 0.f;
+    for (int j = len; j < n; ++j) { S[r * n + j] = fill; R[r * n + j] = 0.f; }
+  }
+}
+__global__ void mask_tokens_kernel(float *S, float *R, long rows, int C, int T, int ld, int col0, int width,
+                                   const int32_t *lengths) {
+  // one workgroup per (sentence, coefficient row, token) row; live tokens leave at once
+  for (long r = blockIdx.x; r < rows; r += gridDim.x) {
+    const long b = r / ((long)C * T);
+    const int t = (int)(r % T);
+    if (t < lengths[b]) continue;
+    for (int j = threadIdx.x; j < width; j += blockDim.x) { S[r * ld + col0 + j] = 0.f; R[r * ld + col0 + j] = 0.f; }
+  }
+}
+
+int mask_scores(State s, int groups, int C, int T, int n, int gps, const int32_t *lengths, hipStream_t st) {
+  TV_REQUIRE(s.S && s.R && lengths, TV_E_NULL, "mask_scores: null pointer");
+  const long rows = (long)groups * C * T;
+  const unsigned blocks = (unsigned)((rows + 255) / 256 > 65536 ? 65536 : (rows + 255) / 256);
+  hipLaunchKernelGGL(mask_scores_kernel, dim3(blocks), dim3(256), 0, st, s.S, s.R, rows, C, T, n, gps, lengths);
+  TV_HIP(hipGetLastError());
+  return TV_OK;
+}
+
+int mask_tokens(State x, int B, int C, int T, int ld, int col0, int width, const int32_t *lengths, hipStream_t st) {
+  TV_REQUIRE(x.S && x.R && lengths, TV_E_NULL, "mask_tokens: null pointer");
+  const long rows = (long)B * C * T;
+  const unsigned blocks = (unsigned)(rows > 262144 ? 262144 : rows);
+  hipLaunchKernelGGL(mask_tokens_kernel, dim3(blocks), dim3(64), 0, st, x.S, x.R, rows, C, T, ld, col0, width, lengths);
   TV_HIP(hipGetLastError());
   return TV_OK;
 }

@@ -133,6 +133,48 @@ def test_leaky_relu_and_silu_small(tv, act, alpha):
         assert torch.equal(outs[0]["lower"], outs[1]["lower"]) and torch.equal(outs[0]["upper"], outs[1]["upper"])
 
 
+@pytest.mark.parametrize("P,p", [(1, 2), (2, 0)])
+def test_padded_batch_equals_each_sentence_alone(tv, P, p):
+    """Sentences of different lengths in one batch: the result for sentence b is the oracle's for its first
+    lengths[b] tokens alone (the oracle never sees the padding).  One perturbed position runs the register-resident
+    row kernels, two the streaming ones.  The largest eps is past the blow-up of some sentences, where a padded
+    token raising the status would show as a status mismatch."""
+    w = scaled(CONFIGS["c2"], n_layers=2, hidden=64, n_heads=2, ffn=128, seq_len=16, max_len=16, batch=5,
+               n_perturbed=P)
+    m = randomize_layernorm(make_model(w, stress=4.0))
+    lengths = np.array([16, 13, 7, 4, 10], np.int32)
+    tokens = make_tokens(w, 5)
+    positions = np.tile(np.array([1, 3][:P], np.int32), (5, 1))          # below every length
+    model = tv.Model(m)
+    tok_d, pos_d, len_d = dev(tokens), dev(positions), dev(lengths)
+    for eps in (1e-5, 1e-4, 2e-3):
+        e32 = float(np.float32(eps))
+        out = model.verify(tok_d, pos_d, p, torch.full((5,), eps, dtype=torch.float32, device="cuda:0"), lengths=len_d)
+        refs = [V.verify(m, tokens[b][:lengths[b]], positions[b], p, e32) for b in range(5)]
+        print("eps", eps, "oracle status", [r["status"] for r in refs])
+        check_bounds(out, refs, f"padded P={P} p={p} eps={eps}", rtol=5e-4)
+    steps, hi_ = 6, 4e-4
+    cert = model.certify(tok_d, pos_d, p, 0.0, hi_, steps, lengths=len_d)
+    ce = cert["eps"].cpu().numpy()
+    for b in range(5):
+        e_ref, lab = V.certify(m, tokens[b][:lengths[b]], positions[b], p, 0.0, float(np.float32(hi_)), steps)
+        assert abs(ce[b] - e_ref) <= hi_ / 2 ** steps * 1.0001, (b, ce[b], e_ref)
+        assert int(cert["labels"][b]) == lab
+    # full lengths: the padded entry point is the plain one, bit for bit
+    full = dev(np.full(5, 16, np.int32))
+    eps_d = torch.full((5,), 1e-4, dtype=torch.float32, device="cuda:0")
+    a, b_ = model.verify(tok_d, pos_d, p, eps_d, lengths=full), model.verify(tok_d, pos_d, p, eps_d)
+    assert torch.equal(a["lower"], b_["lower"]) and torch.equal(a["upper"], b_["upper"])
+    # what stands in the padding does not matter
+    tok2 = tokens.copy()
+    for b in range(5):
+        tok2[b, lengths[b]:] = (tok2[b, lengths[b]:] + 17) % w.enc.vocab
+    c = model.verify(dev(tok2), pos_d, p, eps_d, lengths=len_d)
+    d = model.verify(tok_d, pos_d, p, eps_d, lengths=len_d)
+    assert torch.equal(c["lower"], d["lower"]) and torch.equal(c["upper"], d["upper"])
+    model.close()
+
+
 def test_blow_up_regime_agrees_loosely(tv):
     """Far beyond the certified radius the LayerNorm bounds amplify every perturbation (widths grow by
     orders of magnitude per layer) and with them the fp32 rounding differences: bounds of size 1e4..1e9
