@@ -1614,7 +1614,8 @@ __global__ void mask_scores_kernel(float *S, float *R, long rows, int C, int T, 
   for (long r = (long)blockIdx.x * blockDim.x + threadIdx.x; r < rows; r += (long)gridDim.x * blockDim.x) {
     const long grp = r / ((long)C * T);
     const int c = (int)((r / T) % C);
-    const int len = lengths[grp / gps];
+    int len = lengths[grp / gps];
+    len = len < 0 ? 0 : len;                         // a bad length must not turn into a write before the row
     const float fill = c == C - 1 ? -1.0e30f : 0.f;
     for (int j = len; j < n; ++j) { S[r * n + j] = fill; R[r * n + j] = 0.f; }
   }

@@ -136,9 +136,9 @@ def test_p6_sampling_soundness(act, p, P, eps):
 
 
 # ---------------------------------------------------------------- P7
-@pytest.mark.parametrize("p", [0, 2, 1])
-def test_p7_bruteforce_tiny(p):
-    w, m, tokens, _ = tiny(act=1, layers=1, D=3, H=1, F=4, L=3, P=1, stress=20.0, seed=3)
+@pytest.mark.parametrize("p,act", [(0, 1), (2, 1), (1, 1), (2, 0), (2, 3), (2, 4), (0, 4)])
+def test_p7_bruteforce_tiny(p, act):
+    w, m, tokens, _ = tiny(act=act, layers=1, D=3, H=1, F=4, L=3, P=1, stress=20.0, seed=3)
     eps = 0.01
     res = V.verify(m, tokens, [1], p, eps)
     g = np.linspace(-1, 1, 41)
