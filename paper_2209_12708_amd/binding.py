@@ -213,6 +213,30 @@ class Model:
         return {"eps": out_eps, "labels": out_labels, "status": status}
 
 
+def certify_sentences(model, sentences, positions, p_norm, eps_lo, eps_hi, steps, max_batch=64, pad_token=0,
+                      device="cuda:0"):
+    """tv_certify_padded over sentences of different lengths (host lists / arrays of token ids; positions[i]: the P
+    perturbed positions of sentence i, all below its length).  Sentences are bucketed by padded length
+    (batching.bucket_by_length), each bucket is one call; returns numpy arrays eps, labels, status in input order."""
+    from . import batching
+    n = len(sentences)
+    positions = np.asarray(positions, dtype=np.int32).reshape(n, -1)
+    lens = [len(s) for s in sentences]
+    if any(positions[i].max() >= lens[i] or positions[i].min() < 0 for i in range(n)):
+        raise TvError("certify_sentences: a perturbed position lies outside its sentence")
+    eps = np.empty(n, np.float32)
+    labels = np.empty(n, np.int32)
+    status = np.empty(n, np.int32)
+    for idx, L in batching.bucket_by_length(lens, max_batch):
+        tok, ln = batching.pad_batch(sentences, idx, L, pad_token)
+        out = model.certify(torch.as_tensor(tok, device=device), torch.as_tensor(positions[idx], device=device), p_norm,
+                            eps_lo, eps_hi, steps, lengths=torch.as_tensor(ln, device=device))
+        eps[idx] = out["eps"].cpu().numpy()
+        labels[idx] = out["labels"].cpu().numpy()
+        status[idx] = out["status"].cpu().numpy()
+    return eps, labels, status
+
+
 # ---- single operators (device tensors in, device tensors out).  States are [G, C, T, n] ------------
 def op_concretize(S, R, P, E, groups_per_sentence, p_norm, eps):
     G, Cc, T, n = S.shape

@@ -175,6 +175,26 @@ def test_padded_batch_equals_each_sentence_alone(tv, P, p):
     model.close()
 
 
+def test_certify_sentences_buckets_by_length(tv):
+    """Sentences of 5..16 tokens through the bucketing front end: certified eps of every sentence, in input order,
+    against the oracle on that sentence alone."""
+    w = scaled(CONFIGS["c2"], n_layers=1, hidden=64, n_heads=2, ffn=128, seq_len=16, max_len=16)
+    m = randomize_layernorm(make_model(w, stress=4.0))
+    rng = np.random.default_rng(21)
+    lens = [5, 16, 9, 12, 7, 16, 6, 11]
+    sents = [rng.integers(0, w.enc.vocab, n).astype(np.int32) for n in lens]
+    pos = [[1]] * len(lens)
+    steps, hi_ = 7, 0.2
+    model = tv.Model(m)
+    eps, labels, status = tv.certify_sentences(model, sents, pos, 2, 0.0, hi_, steps, max_batch=3)
+    model.close()
+    for b, sent in enumerate(sents):
+        e_ref, lab = V.certify(m, sent, [1], 2, 0.0, float(np.float32(hi_)), steps)
+        assert abs(eps[b] - e_ref) <= hi_ / 2 ** steps * 1.0001, (b, eps[b], e_ref)
+        assert labels[b] == lab
+    assert len(set(np.round(eps, 7))) > 1            # the sentences do differ
+
+
 def test_blow_up_regime_agrees_loosely(tv):
     """Far beyond the certified radius the LayerNorm bounds amplify every perturbation (widths grow by
     orders of magnitude per layer) and with them the fp32 rounding differences: bounds of size 1e4..1e9
