@@ -53,3 +53,13 @@ def test_argument_errors_without_gpu(lib):
     one = ctypes.c_void_p(16)   # non-null dummy: shape checks come before any launch
     assert lib.tv_op_concretize(one, one, 1, 1, 4, 1, 6, 1, 2, one, one, one, None) == -2     # n % 4 != 0
     assert lib.tv_op_concretize(one, one, 1, 1, 4, 1, 8, 1, 7, one, one, one, None) == -3     # bad norm
+    assert lib.tv_verify_padded(*([None] * 18)) == -1 and lib.tv_certify_padded(*([None] * 18)) == -1
+    # tile search entry points: the candidate table and the built-in rule are host logic
+    lib.tv_affine_tile_default.argtypes = [ctypes.c_longlong, ctypes.c_int, ctypes.c_int]
+    n_tiles = lib.tv_affine_tile_count()
+    assert n_tiles >= 4
+    for M, N, K in ((2080, 64, 64), (2080, 192, 64), (132096, 128, 256), (1050624, 768, 256)):
+        assert 0 <= lib.tv_affine_tile_default(M, N, K) < n_tiles
+    assert lib.tv_affine_tile_default(0, 8, 8) == -2
+    assert lib.tv_op_affine_split_tile(one, 1, 1, 4, 1, 8, 8, one, None, one, n_tiles, None) == -6
+    assert lib.tv_op_affine_split_tile(one, 1, 1, 4, 1, 6, 8, one, None, one, 0, None) == -2      # K % 8 != 0

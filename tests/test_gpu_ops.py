@@ -312,3 +312,13 @@ def test_error_codes_on_device(tv):
     S3 = torch.zeros(3, 5, 1, 8, device="cuda:0")
     with pytest.raises(tv.TvError, match="shape"):
         tv.op_concretize(S3, torch.zeros_like(S3), 1, 4, 2, 2, dev(np.ones(2)))     # groups % groups_per_sentence != 0
+    with pytest.raises(tv.TvError, match="unknown activation"):
+        tv.op_activation(7, S, R, 1, 4, 1, 2, dev(np.ones(2)))
+    with pytest.raises(tv.TvError, match="slope"):
+        tv.op_activation(tv.ACT_LEAKY_RELU, S, R, 1, 4, 1, 2, dev(np.ones(2)), act_alpha=1.5)
+    SR = torch.zeros(2, 2, 5, 1, 8, device="cuda:0")
+    W3 = tv.split3_pair(torch.zeros(8, 8, device="cuda:0"))
+    with pytest.raises(tv.TvError, match="tile"):
+        tv.op_affine_split_tile(SR, 1, 4, W3, 8, tile=tv.affine_tile_count())
+    with pytest.raises(tv.TvError, match="tile"):
+        tv.affine_tile_info(-1)
