@@ -152,14 +152,18 @@ void affine3_kernel(const Affine3Args g, int mtiles, int ntiles) {
   const int l32 = lane & 31, half = lane >> 5;
   const int M = g.M, N = g.N, K = g.K;
 
-  const float *a_ptr[A_F4]; int a_k[A_F4], a_lds[A_F4];
+  // A thread stages 8 consecutive k of a row (two float4 loads, one 16-byte LDS store per piece) where the tile
+  // has that many chunks per thread, else 4 (8-byte stores).
+  constexpr bool APAIR = (BM * 4) % NT == 0;
+  constexpr int A_CH = APAIR ? BM * 4 / NT : A_F4;
+  const float *a_ptr[A_CH]; int a_k[A_CH], a_lds[A_CH];
 #pragma unroll
-  for (int i = 0; i < A_F4; ++i) {
-    const int f = tid + NT * i, row = f / 8, kq = f % 8;
+  for (int i = 0; i < A_CH; ++i) {
+    const int f = tid + NT * i, per = APAIR ? 4 : 8, row = f / per, kc = f % per;
     int m = m0 + row; if (m >= M) m = M - 1;
     a_ptr[i] = A + (long)m * K;
-    a_k[i] = kq * 4;
-    a_lds[i] = row * RS + kq * 8;
+    a_k[i] = kc * (APAIR ? 8 : 4);
+    a_lds[i] = row * RS + kc * (APAIR ? 16 : 8);
   }
   const __bf16 *b_ptr[B_CH]; int b_lds[B_CH];
   const long b_stage = 3L * N * 32;                // elements from one 32-wide stage of the weights to the next
@@ -176,9 +180,14 @@ void affine3_kernel(const Affine3Args g, int mtiles, int ntiles) {
   float4 ra[PF][A_F4]; u32x4 rb[PB][B_CH];
   auto load_a = [&](float4 (&r)[A_F4], int k0) {
 #pragma unroll
-    for (int i = 0; i < A_F4; ++i) {
-      const int k = k0 + a_k[i];
-      r[i] = k < K ? *reinterpret_cast<const float4 *>(a_ptr[i] + k) : make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int i = 0; i < A_CH; ++i) {
+      const int k = k0 + a_k[i];                         // K % 8 == 0: a chunk of 8 is inside or outside as a whole
+      if constexpr (APAIR) {
+        r[2 * i] = k < K ? *reinterpret_cast<const float4 *>(a_ptr[i] + k) : make_float4(0.f, 0.f, 0.f, 0.f);
+        r[2 * i + 1] = k < K ? *reinterpret_cast<const float4 *>(a_ptr[i] + k + 4) : make_float4(0.f, 0.f, 0.f, 0.f);
+      } else {
+        r[i] = k < K ? *reinterpret_cast<const float4 *>(a_ptr[i] + k) : make_float4(0.f, 0.f, 0.f, 0.f);
+      }
     }
   };
   auto load_b = [&](u32x4 (&r)[B_CH], int kt) {     // stage kt < KT (the pieces are zero-padded to whole stages)
@@ -188,18 +197,33 @@ void affine3_kernel(const Affine3Args g, int mtiles, int ntiles) {
   };
   auto store_stage = [&](const float4 (&xa)[A_F4], const u32x4 (&xb)[B_CH]) {
 #pragma unroll
-    for (int i = 0; i < A_F4; ++i) {
-      bf16x4 p0, p1, p2;
-      const float x[4] = {xa[i].x, xa[i].y, xa[i].z, xa[i].w};
+    for (int i = 0; i < A_CH; ++i) {
+      if constexpr (APAIR) {
+        bf16x8 p0, p1, p2;
+        const float x[8] = {xa[2 * i].x, xa[2 * i].y, xa[2 * i].z, xa[2 * i].w,
+                            xa[2 * i + 1].x, xa[2 * i + 1].y, xa[2 * i + 1].z, xa[2 * i + 1].w};
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        __bf16 a, b, c;
-        split3(x[e], a, b, c);
-        p0[e] = a; p1[e] = b; p2[e] = c;
+        for (int e = 0; e < 8; ++e) {
+          __bf16 a, b, c;
+          split3(x[e], a, b, c);
+          p0[e] = a; p1[e] = b; p2[e] = c;
+        }
+        *reinterpret_cast<bf16x8 *>(As + a_lds[i]) = p0;
+        *reinterpret_cast<bf16x8 *>(As + A_P + a_lds[i]) = p1;
+        *reinterpret_cast<bf16x8 *>(As + 2 * A_P + a_lds[i]) = p2;
+      } else {
+        bf16x4 p0, p1, p2;
+        const float x[4] = {xa[i].x, xa[i].y, xa[i].z, xa[i].w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          __bf16 a, b, c;
+          split3(x[e], a, b, c);
+          p0[e] = a; p1[e] = b; p2[e] = c;
+        }
+        *reinterpret_cast<bf16x4 *>(As + a_lds[i]) = p0;
+        *reinterpret_cast<bf16x4 *>(As + A_P + a_lds[i]) = p1;
+        *reinterpret_cast<bf16x4 *>(As + 2 * A_P + a_lds[i]) = p2;
       }
-      *reinterpret_cast<bf16x4 *>(As + a_lds[i]) = p0;
-      *reinterpret_cast<bf16x4 *>(As + A_P + a_lds[i]) = p1;
-      *reinterpret_cast<bf16x4 *>(As + 2 * A_P + a_lds[i]) = p2;
     }
 #pragma unroll
     for (int i = 0; i < B_CH; ++i) *reinterpret_cast<u32x4 *>(Bs + b_lds[i]) = xb[i];
