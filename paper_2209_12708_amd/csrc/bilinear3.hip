@@ -55,7 +55,10 @@ __device__ __forceinline__ f32x16 mfma6(const bf16x8 (&a)[3], const bf16x8 (&b)[
 template <int PBMODE>
 __global__ __launch_bounds__(256) void bilinear3_kernel(const GemmArgs g, int mtiles, int ntiles) {
   constexpr int BM = 128, BN = 32, BK = 32;
-  constexpr int RS = 80;                           // LDS row stride in bytes (32 bf16 + 16 bytes of padding)
+  constexpr int RS = 64;                           // LDS row stride in bytes: 32 bf16, no padding
+  // 16-byte chunk `chunk` (0..3) of row `row`: the chunk index is XOR-ed with bits 2..3 of the row, which spreads the
+  // rows of a 128-bit access over the banks (as in the affine kernel)
+  auto lds_off = [](int row, int chunk) { return row * RS + ((chunk ^ ((row >> 2) & 3)) * 16); };
   constexpr int A_P = BM * RS, B_P = BN * RS;      // bytes per piece
   constexpr int CS = BN + 4;                       // padded row stride of the staged output tile (floats)
   constexpr int STAGE_BYTES = 3 * A_P + 3 * B_P, TILE_BYTES = BM * CS * 4;
@@ -100,11 +103,11 @@ __global__ __launch_bounds__(256) void bilinear3_kernel(const GemmArgs g, int mt
     const int row = (tid >> 3) + 32 * i;
     int m = m0 + row; if (m >= M) m = M - 1;
     a_off[i] = (long)m * g.lda + kq * 4;
-    a_lds[i] = row * RS + kq * 8;
+    a_lds[i] = lds_off(row, kq / 2) + (kq % 2) * 8;
   }
   int nb = n0 + (tid >> 3); if (nb >= N) nb = N - 1;
   const long b_off = (long)nb * g.ldb + kq * 4;
-  const int b_lds = (tid >> 3) * RS + kq * 8;
+  const int b_lds = lds_off(tid >> 3, kq / 2) + (kq % 2) * 8;
 
   float4 ra[4], rb;
   auto load_stage = [&](int kt) {       // stages do not straddle the two K segments: K1 is a multiple of 32
@@ -149,8 +152,8 @@ __global__ __launch_bounds__(256) void bilinear3_kernel(const GemmArgs g, int mt
       bf16x8 af[3], bf[3];
 #pragma unroll
       for (int p = 0; p < 3; ++p) {
-        af[p] = *reinterpret_cast<const bf16x8 *>(As + p * A_P + (wm * 32 + l32) * RS + ks * 32 + half * 16);
-        bf[p] = *reinterpret_cast<const bf16x8 *>(Bs + p * B_P + l32 * RS + ks * 32 + half * 16);
+        af[p] = *reinterpret_cast<const bf16x8 *>(As + p * A_P + lds_off(wm * 32 + l32, ks * 2 + half));
+        bf[p] = *reinterpret_cast<const bf16x8 *>(Bs + p * B_P + lds_off(l32, ks * 2 + half));
       }
       acc = mfma6(af, bf, acc);
     }
