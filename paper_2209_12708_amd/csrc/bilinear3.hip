@@ -31,14 +31,33 @@ __device__ __forceinline__ void cut3(float x, __bf16 &a, __bf16 &b, __bf16 &c) {
   c = (__bf16)r2;
 }
 
+// cut3 of two numbers at once, each pair of pieces packed in one dword (x0 in the low half): one packed conversion
+// per piece, the pieces come back as floats by a shift and a mask; same roundings, same pieces as cut3
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ void cut3_pair(float x0, float x1, unsigned &pa, unsigned &pb, unsigned &pc) {
+  auto pack = [](float u, float v) {
+    f32x2 f; f[0] = u; f[1] = v;
+    return __builtin_bit_cast(unsigned, __builtin_convertvector(f, bf16x2));
+  };
+  pa = pack(x0, x1);
+  const float r0 = x0 - __uint_as_float(pa << 16), r1 = x1 - __uint_as_float(pa & 0xffff0000u);
+  pb = pack(r0, r1);
+  pc = pack(r0 - __uint_as_float(pb << 16), r1 - __uint_as_float(pb & 0xffff0000u));
+}
+
 // eight consecutive k values of one row as the three fragments of a 16-wide MFMA step
 __device__ __forceinline__ void cut3x8(const float (&x)[8], bf16x8 (&p)[3]) {
+  u32x4 q[3];
 #pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    __bf16 a, b, c;
-    cut3(x[e], a, b, c);
-    p[0][e] = a; p[1][e] = b; p[2][e] = c;
+  for (int e = 0; e < 4; ++e) {
+    unsigned a, b, c;
+    cut3_pair(x[2 * e], x[2 * e + 1], a, b, c);
+    q[0][e] = a; q[1][e] = b; q[2][e] = c;
   }
+#pragma unroll
+  for (int k = 0; k < 3; ++k) p[k] = __builtin_bit_cast(bf16x8, q[k]);
 }
 
 __device__ __forceinline__ f32x16 mfma6(const bf16x8 (&a)[3], const bf16x8 (&b)[3], f32x16 acc) {
